@@ -1,0 +1,210 @@
+/*
+ * bitrl.h - C ABI of the MI355X (gfx950) forward pass of BitRL's frozen
+ * ternary state encoder and its fp32 policy / value heads.
+ *
+ * The library computes h_t = f(token ids) and (logits, V) = (g(h_t), v(h_t))
+ * (paper Sec. 3.1, Eq. 3) for a BitNet-b1.58 style backbone whose linear
+ * layers are BitLinear: ternary weights (Sec. 3.1, Eq. 2), per-token int8
+ * activations, integer accumulation, fp32 rescale.
+ *
+ * Conventions for every function
+ * ------------------------------
+ *  - Plain C, no exceptions.  The return value is a status code (BRL_OK = 0).
+ *    On failure nothing was enqueued and brl_last_error() describes the cause
+ *    (thread-local string, valid until the next failing call on that thread).
+ *  - Every tensor pointer is a DEVICE pointer unless its comment says HOST.
+ *    Tensors are row-major and contiguous; pointers must be 16-byte aligned.
+ *    Structs passed by pointer (weights tables, configs) are read on the HOST
+ *    during the call and need not outlive it; the device buffers they point to
+ *    must stay valid until the enqueued work has run.
+ *  - The caller owns all memory.  The library never allocates or frees device
+ *    memory: scratch space comes in through `workspace` / `ws_bytes`, whose
+ *    minimum size the matching brl_*_workspace_bytes() query returns.  A
+ *    workspace must be passed once through brl_workspace_init() after it is
+ *    allocated; forward calls leave it initialised.  Calls that share a
+ *    workspace must be ordered on one stream.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    *_forward calls only enqueue kernels: no host synchronisation, no
+ *    device-to-host copy.  bitlinear_quantize_weights (an offline step)
+ *    synchronises the stream once so that it can report bad weights.
+ *  - Non-finite activations are not checked: results are then unspecified
+ *    (never out-of-bounds accesses).  Token ids outside [0, vocab) are clamped.
+ *  - Limits: 1 <= K <= 9216 input features per BitLinear (one token row is
+ *    held in the registers of one wavefront), any N, any M.
+ */
+#ifndef BITRL_H
+#define BITRL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ---- */
+#define BRL_OK      0   /* work enqueued */
+#define BRL_EINVAL  1   /* bad shape, null or misaligned pointer, unsupported size, bad weights */
+#define BRL_ENOSPC  2   /* workspace smaller than the query says */
+#define BRL_EHIP    3   /* a HIP runtime call failed */
+
+/* ---- element types of activation inputs ---- */
+#define BRL_F32   0
+#define BRL_BF16  1    /* widened to fp32 exactly on load */
+
+/* ---- head activation ---- */
+#define BRL_ACT_TANH 0
+#define BRL_ACT_RELU 1
+
+/* ---- attention arithmetic ---- */
+#define BRL_ATTN_F32  0   /* fp32 FMA on the vector ALUs */
+
+const char* brl_last_error(void);
+int         brl_abi_version(void);
+
+/* Fill a freshly allocated workspace with the state the forward calls expect
+ * (all zero).  Enqueued on `stream`. */
+int brl_workspace_init(void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * BitLinear weights (Sec. 3.1, Eq. 2: Q(W) = sign(W) * 1[|W| > tau]).
+ *
+ * tau = beta / 2 with beta = mean|W| + eps over the whole matrix (one scale
+ * per matrix; the mean is accumulated in fp64 and rounded to fp32 once).
+ * |w| == tau gives code 0.  beta is also the dequantisation scale.
+ *
+ * Packed format (version 1): rows padded to a multiple of 32, columns to a
+ * multiple of 128, 2 bits per weight holding code + 1 in {0, 1, 2}; padding
+ * holds code 0.  The 32-bit word with index ((nb * (Kp/128) + sb) * 64 + lane)
+ * * 4 + dd holds the 16 weights of row n = 32 nb + (lane & 31) at columns
+ * k = 128 sb + 32 dd + 16 (lane >> 5) + i, i = 0..15, weight i = 4 j + b at
+ * bits [2 j + 8 b, 2 j + 8 b + 1].  So (word >> 2 j) & 0x03030303 is four
+ * consecutive-k bytes ready for an int8 dot product, and a wavefront reading
+ * 16 bytes per lane gets one 32 x 128 block in the int8 MFMA operand order.
+ * The blob may be stored and reloaded; it carries no header.
+ * ------------------------------------------------------------------------ */
+size_t brl_packed_bytes(int n_out, int k_in);
+size_t brl_quantize_workspace_bytes(int n_out, int k_in);
+
+/* W [n_out, k_in] fp32  ->  packed_out [brl_packed_bytes], beta_out [1] fp32.
+ * codes_dbg: optional [n_out, k_in] int8 plain codes in {-1, 0, 1} (or NULL).
+ * Returns BRL_EINVAL if mean|W| is not finite (outputs then unspecified).
+ * Synchronises `stream`. */
+int bitlinear_quantize_weights(const float* W, int n_out, int k_in, float eps,
+                               void* packed_out, float* beta_out, int8_t* codes_dbg,
+                               void* workspace, size_t ws_bytes, void* stream);
+
+/* packed -> plain int8 codes [n_out, k_in] in {-1, 0, 1}. */
+int brl_unpack_codes(const void* packed, int n_out, int k_in, int8_t* codes_out, void* stream);
+
+/* ------------------------------------------------------------------------
+ * BitLinear forward: y = dequant(ternary_matmul(quant(x), W)) (+ residual).
+ *
+ * Per token t: a = max(max_k |x_tk|, eps_act); q_tk = clamp(rne(x_tk *
+ * (127 / a)), -127, 127); acc_tn = sum_k q_tk code_nk (int32, exact);
+ * y_tn = (float(acc_tn) * (a / 127)) * beta (+ residual_tn), each fp32
+ * operation rounded once, in that order.  No normalisation happens inside.
+ *
+ * x [M, K] of x_dtype; y [M, N] fp32; residual [M, N] fp32 or NULL (may alias
+ * y).  Optional taps (NULL to skip): xq_dbg [M, K] int8, absmax_dbg [M] fp32
+ * (the clamped a), acc_dbg [M, N] int32.
+ * M <= 4 takes the bandwidth-bound GEMV path, larger M the int8 MFMA path.
+ * ------------------------------------------------------------------------ */
+size_t brl_bitlinear_workspace_bytes(int M, int N, int K);
+int bitlinear_forward(const void* packed, const float* beta, int N, int K,
+                      const void* x, int x_dtype, int M, float eps_act,
+                      float* y, const float* residual,
+                      int8_t* xq_dbg, float* absmax_dbg, int32_t* acc_dbg,
+                      void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * One feed-forward block:
+ *   n = RMSNorm_d(x; norm_g);  (G, U) = BitLinear_gate(n), BitLinear_up(n)
+ *   (n is quantised once, each matrix keeps its own beta);
+ *   h = (max(G,0) * max(G,0)) * U;  m = RMSNorm_f(h; subln_g);
+ *   y = x + BitLinear_down(m).
+ * RMSNorm: r = fp32(1 / sqrt(mean_k x_k^2 + eps_norm)) with the statistic in
+ * fp64; out_k = (x_k * r) * g_k in fp32.
+ * x [M, d] of x_dtype, y [M, d] fp32 (must not alias x).
+ * ------------------------------------------------------------------------ */
+typedef struct brl_ffn_weights {
+    const float* norm_g;        /* [d] */
+    const void*  gate_packed;   /* [f, d] packed */
+    const float* gate_beta;     /* [1] */
+    const void*  up_packed;     /* [f, d] packed */
+    const float* up_beta;       /* [1] */
+    const float* subln_g;       /* [f] */
+    const void*  down_packed;   /* [d, f] packed */
+    const float* down_beta;     /* [1] */
+} brl_ffn_weights;
+
+size_t brl_ffn_workspace_bytes(int M, int d, int f);
+int ffn_block_forward(const brl_ffn_weights* w /* HOST */, const void* x, int x_dtype,
+                      int M, int d, int f, float eps_norm, float eps_act,
+                      float* y, void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Frozen encoder (Sec. 3.1, Eq. 3: h_t = f(serialize(s_t)), from token ids).
+ *
+ * x = E[ids] (bf16 table, widened); per layer: x += o(subLN(attn(q(n), k(n),
+ * v(n)))) with n = RMSNorm(x), rotary embedding on pairs (i, i + head_dim/2)
+ * at position = index inside the state, causal softmax(q k^T / sqrt(head_dim))
+ * v, query head h reading key/value head h / (n_heads / n_kv_heads); then the
+ * feed-forward block above.  h[b] = mean over the first lengths[b] positions
+ * (all S if lengths is NULL) of RMSNorm(x; final_norm_g), summed in fp64.
+ * States are independent; large batches are processed in micro-batches of
+ * whole states inside the call.
+ * ids [B, S] int32, lengths [B] int32 in [1, S] or NULL, h [B, d] fp32.
+ * ------------------------------------------------------------------------ */
+typedef struct brl_layer_weights {
+    const float* attn_norm_g;   /* [d] */
+    const void*  wq_packed;  const float* wq_beta;   /* [n_heads*head_dim, d] */
+    const void*  wk_packed;  const float* wk_beta;   /* [n_kv_heads*head_dim, d] */
+    const void*  wv_packed;  const float* wv_beta;   /* [n_kv_heads*head_dim, d] */
+    const float* attn_subln_g;  /* [n_heads*head_dim] */
+    const void*  wo_packed;  const float* wo_beta;   /* [d, n_heads*head_dim] */
+    brl_ffn_weights ffn;
+} brl_layer_weights;
+
+typedef struct brl_encoder {
+    int   n_layers, d, n_heads, n_kv_heads, head_dim, f, vocab;
+    float rope_theta, eps_norm, eps_act;
+    int   attn_precision;               /* BRL_ATTN_* */
+    const uint16_t* embedding;          /* [vocab, d] bf16 bit patterns */
+    const float*    final_norm_g;       /* [d] */
+    const brl_layer_weights* layers;    /* HOST array of n_layers entries */
+} brl_encoder;
+
+size_t brl_encoder_workspace_bytes(const brl_encoder* enc /* HOST */, int B, int S);
+int encoder_forward(const brl_encoder* enc /* HOST */, const int32_t* ids, int B, int S,
+                    const int32_t* lengths, float* h,
+                    void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Policy and value heads (Sec. 3.1, Eq. 3; fp32 parameters, Appendix table):
+ * each is an MLP, out = W_L act(... act(W_1 h + b_1) ...) + b_L, accumulated
+ * in fp64 and rounded to fp32 once at the output.  The softmax over the
+ * logits is the caller's.  h [B, dims[0]], logits [B, A], value [B].
+ * ------------------------------------------------------------------------ */
+typedef struct brl_mlp {
+    int n_layers;                 /* number of weight matrices, 1..8 */
+    const int* dims;              /* HOST [n_layers + 1]: in, hidden..., out */
+    const float* const* W;        /* HOST array of DEVICE pointers, W[i] is [dims[i+1], dims[i]] */
+    const float* const* b;        /* HOST array of DEVICE pointers, b[i] is [dims[i+1]] */
+    int act;                      /* BRL_ACT_* between layers */
+} brl_mlp;
+
+typedef struct brl_head {
+    brl_mlp policy;               /* dims[n_layers] = number of actions A */
+    brl_mlp value;                /* dims[n_layers] = 1 */
+} brl_head;
+
+size_t brl_head_workspace_bytes(const brl_head* head /* HOST */, int B);
+int policy_value_head(const brl_head* head /* HOST */, const float* h, int B,
+                      float* logits, float* value,
+                      void* workspace, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITRL_H */

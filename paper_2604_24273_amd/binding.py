@@ -1,0 +1,222 @@
+"""ctypes binding of libbitrl.so: argument marshalling only.
+
+Every function below has the name and the argument order of its C entry point
+(include/bitrl.h).  Tensors are torch tensors on the GPU (torch is used for
+device memory and streams, nothing else); every step of the computation runs
+in the library's kernels.  A missing library is an error, never a fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libbitrl.so")
+
+BRL_OK, BRL_EINVAL, BRL_ENOSPC, BRL_EHIP = 0, 1, 2, 3
+BRL_F32, BRL_BF16 = 0, 1
+BRL_ACT_TANH, BRL_ACT_RELU = 0, 1
+BRL_ATTN_F32 = 0
+
+c_void_p, c_int, c_float, c_size_t = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+
+
+class brl_ffn_weights(C.Structure):
+    _fields_ = [("norm_g", c_void_p), ("gate_packed", c_void_p), ("gate_beta", c_void_p),
+                ("up_packed", c_void_p), ("up_beta", c_void_p), ("subln_g", c_void_p),
+                ("down_packed", c_void_p), ("down_beta", c_void_p)]
+
+
+class brl_layer_weights(C.Structure):
+    _fields_ = [("attn_norm_g", c_void_p),
+                ("wq_packed", c_void_p), ("wq_beta", c_void_p),
+                ("wk_packed", c_void_p), ("wk_beta", c_void_p),
+                ("wv_packed", c_void_p), ("wv_beta", c_void_p),
+                ("attn_subln_g", c_void_p),
+                ("wo_packed", c_void_p), ("wo_beta", c_void_p),
+                ("ffn", brl_ffn_weights)]
+
+
+class brl_encoder(C.Structure):
+    _fields_ = [("n_layers", c_int), ("d", c_int), ("n_heads", c_int), ("n_kv_heads", c_int),
+                ("head_dim", c_int), ("f", c_int), ("vocab", c_int),
+                ("rope_theta", c_float), ("eps_norm", c_float), ("eps_act", c_float),
+                ("attn_precision", c_int),
+                ("embedding", c_void_p), ("final_norm_g", c_void_p),
+                ("layers", C.POINTER(brl_layer_weights))]
+
+
+class brl_mlp(C.Structure):
+    _fields_ = [("n_layers", c_int), ("dims", C.POINTER(c_int)),
+                ("W", C.POINTER(c_void_p)), ("b", C.POINTER(c_void_p)), ("act", c_int)]
+
+
+class brl_head(C.Structure):
+    _fields_ = [("policy", brl_mlp), ("value", brl_mlp)]
+
+
+class BitrlError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("bitrl status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+_SIGNATURES = {
+    "brl_last_error": (C.c_char_p, []),
+    "brl_abi_version": (c_int, []),
+    "brl_workspace_init": (c_int, [c_void_p, c_size_t, c_void_p]),
+    "brl_packed_bytes": (c_size_t, [c_int, c_int]),
+    "brl_quantize_workspace_bytes": (c_size_t, [c_int, c_int]),
+    "bitlinear_quantize_weights": (c_int, [c_void_p, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p,
+                                           c_void_p, c_size_t, c_void_p]),
+    "brl_unpack_codes": (c_int, [c_void_p, c_int, c_int, c_void_p, c_void_p]),
+    "brl_bitlinear_workspace_bytes": (c_size_t, [c_int, c_int, c_int]),
+    "bitlinear_forward": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
+                                  c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "brl_ffn_workspace_bytes": (c_size_t, [c_int, c_int, c_int]),
+    "ffn_block_forward": (c_int, [C.POINTER(brl_ffn_weights), c_void_p, c_int, c_int, c_int, c_int, c_float, c_float,
+                                  c_void_p, c_void_p, c_size_t, c_void_p]),
+    "brl_encoder_workspace_bytes": (c_size_t, [C.POINTER(brl_encoder), c_int, c_int]),
+    "encoder_forward": (c_int, [C.POINTER(brl_encoder), c_void_p, c_int, c_int, c_void_p, c_void_p,
+                                c_void_p, c_size_t, c_void_p]),
+    "brl_head_workspace_bytes": (c_size_t, [C.POINTER(brl_head), c_int]),
+    "policy_value_head": (c_int, [C.POINTER(brl_head), c_void_p, c_int, c_void_p, c_void_p,
+                                  c_void_p, c_size_t, c_void_p]),
+}
+
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: run `python -m paper_2604_24273_amd.build` (hipcc, gfx950) first" % LIB_PATH)
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != BRL_OK:
+        raise BitrlError(status, lib().brl_last_error().decode("utf-8", "replace"))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous GPU tensor")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return BRL_F32
+    if t.dtype == torch.bfloat16:
+        return BRL_BF16
+    raise ValueError("activations must be float32 or bfloat16")
+
+
+# ---------------------------------------------------------------- entry points
+
+def brl_abi_version() -> int:
+    return lib().brl_abi_version()
+
+
+def brl_workspace_init(workspace: torch.Tensor) -> None:
+    _check(lib().brl_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_packed_bytes(n_out: int, k_in: int) -> int:
+    return lib().brl_packed_bytes(n_out, k_in)
+
+
+def brl_quantize_workspace_bytes(n_out: int, k_in: int) -> int:
+    return lib().brl_quantize_workspace_bytes(n_out, k_in)
+
+
+def bitlinear_quantize_weights(W: torch.Tensor, eps: float, packed_out: torch.Tensor, beta_out: torch.Tensor,
+                               codes_dbg: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    n, k = W.shape
+    _check(lib().bitlinear_quantize_weights(_ptr(W), n, k, eps, _ptr(packed_out), _ptr(beta_out), _ptr(codes_dbg),
+                                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_unpack_codes(packed: torch.Tensor, n_out: int, k_in: int, codes_out: torch.Tensor) -> None:
+    _check(lib().brl_unpack_codes(_ptr(packed), n_out, k_in, _ptr(codes_out), _stream()))
+
+
+def brl_bitlinear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return lib().brl_bitlinear_workspace_bytes(M, N, K)
+
+
+def bitlinear_forward(packed: torch.Tensor, beta: torch.Tensor, N: int, K: int, x: torch.Tensor, M: int, eps_act: float,
+                      y: torch.Tensor, residual: Optional[torch.Tensor], xq_dbg: Optional[torch.Tensor],
+                      absmax_dbg: Optional[torch.Tensor], acc_dbg: Optional[torch.Tensor],
+                      workspace: torch.Tensor) -> None:
+    _check(lib().bitlinear_forward(_ptr(packed), _ptr(beta), N, K, _ptr(x), _dtype_code(x), M, eps_act, _ptr(y),
+                                   _ptr(residual), _ptr(xq_dbg), _ptr(absmax_dbg), _ptr(acc_dbg), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_ffn_workspace_bytes(M: int, d: int, f: int) -> int:
+    return lib().brl_ffn_workspace_bytes(M, d, f)
+
+
+def ffn_block_forward(w: brl_ffn_weights, x: torch.Tensor, M: int, d: int, f: int, eps_norm: float, eps_act: float,
+                      y: torch.Tensor, workspace: torch.Tensor) -> None:
+    _check(lib().ffn_block_forward(C.byref(w), _ptr(x), _dtype_code(x), M, d, f, eps_norm, eps_act, _ptr(y),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_encoder_workspace_bytes(enc: brl_encoder, B: int, S: int) -> int:
+    return lib().brl_encoder_workspace_bytes(C.byref(enc), B, S)
+
+
+def encoder_forward(enc: brl_encoder, ids: torch.Tensor, B: int, S: int, lengths: Optional[torch.Tensor],
+                    h: torch.Tensor, workspace: torch.Tensor) -> None:
+    _check(lib().encoder_forward(C.byref(enc), _ptr(ids), B, S, _ptr(lengths), _ptr(h), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_head_workspace_bytes(head: brl_head, B: int) -> int:
+    return lib().brl_head_workspace_bytes(C.byref(head), B)
+
+
+def policy_value_head(head: brl_head, h: torch.Tensor, B: int, logits: torch.Tensor, value: torch.Tensor,
+                      workspace: torch.Tensor) -> None:
+    _check(lib().policy_value_head(C.byref(head), _ptr(h), B, _ptr(logits), _ptr(value), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()))
+
+
+# ------------------------------------------------ struct builders (marshalling)
+
+def make_ffn_weights(norm_g, gate_packed, gate_beta, up_packed, up_beta, subln_g, down_packed, down_beta) -> brl_ffn_weights:
+    return brl_ffn_weights(_ptr(norm_g), _ptr(gate_packed), _ptr(gate_beta), _ptr(up_packed), _ptr(up_beta),
+                           _ptr(subln_g), _ptr(down_packed), _ptr(down_beta))
+
+
+def make_mlp(weights: Sequence[torch.Tensor], biases: Sequence[torch.Tensor], act: int):
+    """Returns (brl_mlp, keepalive): the ctypes arrays must outlive the struct."""
+    n = len(weights)
+    dims = (c_int * (n + 1))(*([weights[0].shape[1]] + [w.shape[0] for w in weights]))
+    wp = (c_void_p * n)(*[_ptr(w) for w in weights])
+    bp = (c_void_p * n)(*[_ptr(b) for b in biases])
+    m = brl_mlp(n, C.cast(dims, C.POINTER(c_int)), C.cast(wp, C.POINTER(c_void_p)), C.cast(bp, C.POINTER(c_void_p)), act)
+    return m, (dims, wp, bp, list(weights), list(biases))

@@ -1,0 +1,481 @@
+// C ABI of the library (see include/bitrl.h): argument checks, workspace
+// carving and kernel sequencing.  No arithmetic of the method happens here.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.hpp"
+
+namespace brl {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    set_error("HIP error %d (%s) at %s", (int)e, hipGetErrorString(e), what);
+    return BRL_EHIP;
+}
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Carver {
+    char* base;
+    size_t off;
+    explicit Carver(void* p) : base(static_cast<char*>(p)), off(0) {}
+    template <class T>
+    T* take(size_t count) {
+        T* r = reinterpret_cast<T*>(base + off);
+        off += round_up_sz(count * sizeof(T), ALIGN);
+        return r;
+    }
+};
+
+size_t actbuf_bytes(int M, int K) {
+    const size_t Mp = round_up(M, NB), Kp = round_up(K, SBK);
+    return round_up_sz(Mp * Kp, ALIGN) + 3 * round_up_sz(Mp * 4, ALIGN);
+}
+
+ActBuf take_actbuf(Carver& c, int M, int K) {
+    const size_t Mp = round_up(M, NB), Kp = round_up(K, SBK);
+    ActBuf a;
+    a.q = c.take<int8_t>(Mp * Kp);
+    a.absmax = c.take<float>(Mp);
+    a.dscale = c.take<float>(Mp);
+    a.sumq = c.take<int32_t>(Mp);
+    return a;
+}
+
+int check_linear_shape(int N, int K, const char* who) {
+    BRL_REQUIRE(N >= 1 && K >= 1, "%s: N = %d, K = %d must be positive", who, N, K);
+    BRL_REQUIRE(K % 8 == 0, "%s: K = %d must be a multiple of 8", who, K);
+    BRL_REQUIRE(K <= MAX_K, "%s: K = %d exceeds the supported %d", who, K, MAX_K);
+    return BRL_OK;
+}
+
+WeightSegs one_seg(const void* packed, const float* beta, int N) {
+    WeightSegs w;
+    memset(&w, 0, sizeof(w));
+    w.count = 1;
+    w.packed[0] = static_cast<const uint32_t*>(packed);
+    w.beta[0] = beta;
+    w.nb_end[0] = round_up(N, NB) / NB;
+    w.n_end[0] = N;
+    return w;
+}
+
+void add_seg(WeightSegs& w, const void* packed, const float* beta, int N) {
+    const int i = w.count++;
+    w.packed[i] = static_cast<const uint32_t*>(packed);
+    w.beta[i] = beta;
+    w.nb_end[i] = (i ? w.nb_end[i - 1] : 0) + round_up(N, NB) / NB;
+    w.n_end[i] = (i ? w.n_end[i - 1] : 0) + N;
+}
+
+// tickets (kept zero between calls) | gemv partials | activation buffer
+struct BitlinearWs {
+    size_t tickets_off, partial_off, act_off, total;
+};
+
+BitlinearWs bitlinear_ws_layout(int M, int N, int K) {
+    BitlinearWs L;
+    const size_t nnb = round_up(N, NB) / NB;
+    L.tickets_off = 0;
+    L.partial_off = round_up_sz(nnb * sizeof(unsigned), ALIGN);
+    const size_t ks = (size_t)gemv_ksplit(N, K);
+    L.act_off = L.partial_off + round_up_sz(nnb * ks * 4 * 32 * sizeof(int32_t), ALIGN);
+    L.total = L.act_off + actbuf_bytes(M, K);
+    return L;
+}
+
+struct FfnWs {
+    size_t xf_off, act1_off, gu_off, act2_off, total;
+};
+
+FfnWs ffn_ws_layout(int M, int d, int f) {
+    FfnWs L;
+    L.xf_off = 0;
+    L.act1_off = round_up_sz((size_t)M * d * 4, ALIGN);
+    L.gu_off = L.act1_off + actbuf_bytes(M, d);
+    L.act2_off = L.gu_off + round_up_sz((size_t)M * 2 * f * 4, ALIGN);
+    L.total = L.act2_off + actbuf_bytes(M, f);
+    return L;
+}
+
+int check_ffn(const brl_ffn_weights* w, int d, int f, const char* who) {
+    BRL_REQUIRE(w != nullptr, "%s: null weights", who);
+    BRL_REQUIRE(w->norm_g && w->gate_packed && w->gate_beta && w->up_packed && w->up_beta && w->subln_g &&
+                    w->down_packed && w->down_beta,
+                "%s: null pointer in brl_ffn_weights", who);
+    BRL_REQUIRE(aligned16(w->norm_g) && aligned16(w->gate_packed) && aligned16(w->up_packed) && aligned16(w->subln_g) &&
+                    aligned16(w->down_packed),
+                "%s: weight pointers must be 16-byte aligned", who);
+    if (int rc = check_linear_shape(f, d, who)) return rc;
+    if (int rc = check_linear_shape(d, f, who)) return rc;
+    return BRL_OK;
+}
+
+// shared by ffn_block_forward and encoder_forward: x [M, d] fp32 -> y = x + down(...)
+int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_dtype, int M, int d, int f,
+            float eps_norm, float eps_act, float* y, const ActBuf& act1, float* gu, const ActBuf& act2, hipStream_t s) {
+    QuantArgs qa;
+    memset(&qa, 0, sizeof(qa));
+    qa.x = xin; qa.x_dtype = x_dtype; qa.gain = w->norm_g; qa.glu = 0;
+    qa.eps_norm = eps_norm; qa.eps_act = eps_act; qa.M = M; qa.K = d;
+    if (int rc = launch_act_quant(qa, act1, s)) return rc;
+    WeightSegs gu_w;
+    memset(&gu_w, 0, sizeof(gu_w));
+    add_seg(gu_w, w->gate_packed, w->gate_beta, f);
+    add_seg(gu_w, w->up_packed, w->up_beta, f);
+    if (int rc = launch_gemm(act1, gu_w, M, 2 * f, d, gu, 2 * f, nullptr, nullptr, s)) return rc;
+    QuantArgs qb;
+    memset(&qb, 0, sizeof(qb));
+    qb.x = gu; qb.x_dtype = BRL_F32; qb.gain = w->subln_g; qb.glu = 1;
+    qb.eps_norm = eps_norm; qb.eps_act = eps_act; qb.M = M; qb.K = f;
+    if (int rc = launch_act_quant(qb, act2, s)) return rc;
+    const WeightSegs dn = one_seg(w->down_packed, w->down_beta, d);
+    return launch_gemm(act2, dn, M, d, f, y, d, x32, nullptr, s);
+}
+
+struct EncWs {
+    int states_mb;      // states per micro-batch
+    size_t x_off, act_off, big_off, cos_off, sin_off, rinv_off, total;
+    int big_ld_qkv;
+};
+
+constexpr int ENC_MB_TOKENS = 32768;
+
+EncWs encoder_ws_layout(const brl_encoder* e, int B, int S) {
+    EncWs L;
+    int smb = ENC_MB_TOKENS / S;
+    if (smb < 1) smb = 1;
+    if (smb > B) smb = B;
+    L.states_mb = smb;
+    const size_t Mt = (size_t)smb * S;
+    const int dq = e->n_heads * e->head_dim, dkv = e->n_kv_heads * e->head_dim;
+    int kmax = e->d;
+    if (dq > kmax) kmax = dq;
+    if (e->f > kmax) kmax = e->f;
+    L.x_off = 0;
+    L.act_off = round_up_sz(Mt * e->d * 4, ALIGN);
+    L.big_off = L.act_off + actbuf_bytes((int)Mt, kmax);
+    const size_t attn_cols = (size_t)dq + 2 * dkv + dq;      // qkv | attention output
+    const size_t big_cols = attn_cols > (size_t)2 * e->f ? attn_cols : (size_t)2 * e->f;
+    L.cos_off = L.big_off + round_up_sz(Mt * big_cols * 4, ALIGN);
+    const size_t tbl = round_up_sz((size_t)S * (e->head_dim / 2) * 4, ALIGN);
+    L.sin_off = L.cos_off + tbl;
+    L.rinv_off = L.sin_off + tbl;
+    L.total = L.rinv_off + round_up_sz(Mt * 4, ALIGN);
+    L.big_ld_qkv = dq + 2 * dkv;
+    return L;
+}
+
+int check_encoder(const brl_encoder* e) {
+    BRL_REQUIRE(e != nullptr, "encoder: null config");
+    BRL_REQUIRE(e->n_layers >= 0 && e->d >= 8 && e->n_heads >= 1 && e->n_kv_heads >= 1 && e->f >= 8 && e->vocab >= 1,
+                "encoder: bad sizes");
+    BRL_REQUIRE(e->n_heads % e->n_kv_heads == 0, "encoder: n_heads %d not a multiple of n_kv_heads %d", e->n_heads,
+                e->n_kv_heads);
+    BRL_REQUIRE(e->head_dim == 16 || e->head_dim == 32 || e->head_dim == 64 || e->head_dim == 100 || e->head_dim == 128,
+                "encoder: head_dim %d not in {16, 32, 64, 100, 128}", e->head_dim);
+    BRL_REQUIRE(e->d % 8 == 0 && e->f % 8 == 0 && (e->n_kv_heads * e->head_dim) % 4 == 0,
+                "encoder: d and f must be multiples of 8");
+    BRL_REQUIRE(e->attn_precision == BRL_ATTN_F32, "encoder: unknown attn_precision %d", e->attn_precision);
+    const int dq = e->n_heads * e->head_dim;
+    if (int rc = check_linear_shape(dq, e->d, "encoder")) return rc;
+    if (int rc = check_linear_shape(e->d, dq, "encoder")) return rc;
+    BRL_REQUIRE(e->embedding && e->final_norm_g && aligned16(e->embedding) && aligned16(e->final_norm_g),
+                "encoder: embedding / final_norm_g null or misaligned");
+    BRL_REQUIRE(e->n_layers == 0 || e->layers != nullptr, "encoder: null layer table");
+    for (int l = 0; l < e->n_layers; ++l) {
+        const brl_layer_weights& w = e->layers[l];
+        BRL_REQUIRE(w.attn_norm_g && w.wq_packed && w.wq_beta && w.wk_packed && w.wk_beta && w.wv_packed && w.wv_beta &&
+                        w.attn_subln_g && w.wo_packed && w.wo_beta,
+                    "encoder: null pointer in layer %d", l);
+        BRL_REQUIRE(aligned16(w.attn_norm_g) && aligned16(w.wq_packed) && aligned16(w.wk_packed) &&
+                        aligned16(w.wv_packed) && aligned16(w.attn_subln_g) && aligned16(w.wo_packed),
+                    "encoder: misaligned pointer in layer %d", l);
+        if (int rc = check_ffn(&w.ffn, e->d, e->f, "encoder")) return rc;
+    }
+    return BRL_OK;
+}
+
+int check_mlp(const brl_mlp* m, const char* who, int out_expected) {
+    BRL_REQUIRE(m->n_layers >= 1 && m->n_layers <= 8, "%s: n_layers %d out of 1..8", who, m->n_layers);
+    BRL_REQUIRE(m->dims && m->W && m->b, "%s: null tables", who);
+    for (int i = 0; i <= m->n_layers; ++i) BRL_REQUIRE(m->dims[i] >= 1, "%s: dims[%d] = %d", who, i, m->dims[i]);
+    for (int i = 0; i < m->n_layers; ++i) BRL_REQUIRE(m->W[i] && m->b[i], "%s: null parameter in layer %d", who, i);
+    BRL_REQUIRE(m->act == BRL_ACT_TANH || m->act == BRL_ACT_RELU, "%s: unknown activation %d", who, m->act);
+    if (out_expected > 0)
+        BRL_REQUIRE(m->dims[m->n_layers] == out_expected, "%s: output width %d, expected %d", who, m->dims[m->n_layers],
+                    out_expected);
+    return BRL_OK;
+}
+
+size_t mlp_hidden_max(const brl_mlp* m) {
+    size_t mx = 1;
+    for (int i = 1; i < m->n_layers; ++i)
+        if ((size_t)m->dims[i] > mx) mx = (size_t)m->dims[i];
+    return mx;
+}
+
+int run_mlp(const brl_mlp* m, const float* h, int B, float* out, double* buf0, double* buf1, hipStream_t s) {
+    const double* in64 = nullptr;
+    const float* in32 = h;
+    double* bufs[2] = {buf0, buf1};
+    for (int i = 0; i < m->n_layers; ++i) {
+        const bool last = i + 1 == m->n_layers;
+        double* o64 = last ? nullptr : bufs[i & 1];
+        if (int rc = launch_mlp_layer(in64, in32, m->W[i], m->b[i], B, m->dims[i], m->dims[i + 1], m->act, o64,
+                                      last ? out : nullptr, s))
+            return rc;
+        in64 = o64;
+        in32 = nullptr;
+    }
+    return BRL_OK;
+}
+
+}  // namespace
+}  // namespace brl
+
+using namespace brl;
+
+extern "C" {
+
+const char* brl_last_error(void) { return g_err; }
+
+int brl_abi_version(void) { return 1; }
+
+int brl_workspace_init(void* workspace, size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace_init: null or misaligned workspace");
+    return launch_fill_zero(workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t brl_packed_bytes(int n_out, int k_in) {
+    if (n_out < 1 || k_in < 1) return 0;
+    return (size_t)round_up(n_out, NB) * (size_t)round_up(k_in, SBK) / 4;
+}
+
+size_t brl_quantize_workspace_bytes(int n_out, int k_in) {
+    (void)n_out; (void)k_in;
+    return 1024 * sizeof(double) + ALIGN;
+}
+
+int bitlinear_quantize_weights(const float* W, int n_out, int k_in, float eps, void* packed_out, float* beta_out,
+                               int8_t* codes_dbg, void* workspace, size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(W && packed_out && beta_out && workspace, "quantize_weights: null pointer");
+    BRL_REQUIRE(aligned16(W) && aligned16(packed_out) && aligned16(workspace), "quantize_weights: misaligned pointer");
+    BRL_REQUIRE(n_out >= 1 && k_in >= 1, "quantize_weights: bad shape %d x %d", n_out, k_in);
+    BRL_REQUIRE(eps >= 0.f, "quantize_weights: negative eps");
+    if (ws_bytes < brl_quantize_workspace_bytes(n_out, k_in)) {
+        set_error("quantize_weights: workspace %zu < %zu", ws_bytes, brl_quantize_workspace_bytes(n_out, k_in));
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver c(workspace);
+    double* partials = c.take<double>(1024);
+    int* flag = c.take<int>(1);
+    if (int rc = launch_quantize_weights(W, n_out, k_in, eps, static_cast<uint32_t*>(packed_out), beta_out, codes_dbg,
+                                         partials, flag, s))
+        return rc;
+    int bad = 0;
+    BRL_HIP_CHECK(hipMemcpyAsync(&bad, flag, sizeof(int), hipMemcpyDeviceToHost, s));
+    BRL_HIP_CHECK(hipStreamSynchronize(s));
+    BRL_REQUIRE(bad == 0, "quantize_weights: mean|W| is not finite");
+    return BRL_OK;
+}
+
+int brl_unpack_codes(const void* packed, int n_out, int k_in, int8_t* codes_out, void* stream) {
+    BRL_REQUIRE(packed && codes_out && aligned16(packed), "unpack_codes: null or misaligned pointer");
+    BRL_REQUIRE(n_out >= 1 && k_in >= 1, "unpack_codes: bad shape");
+    return launch_unpack_codes(static_cast<const uint32_t*>(packed), n_out, k_in, codes_out,
+                               static_cast<hipStream_t>(stream));
+}
+
+size_t brl_bitlinear_workspace_bytes(int M, int N, int K) {
+    if (M < 1 || N < 1 || K < 1) return 0;
+    return bitlinear_ws_layout(M, N, K).total;
+}
+
+int bitlinear_forward(const void* packed, const float* beta, int N, int K, const void* x, int x_dtype, int M,
+                      float eps_act, float* y, const float* residual, int8_t* xq_dbg, float* absmax_dbg,
+                      int32_t* acc_dbg, void* workspace, size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(packed && beta && x && y && workspace, "bitlinear_forward: null pointer");
+    BRL_REQUIRE(aligned16(packed) && aligned16(x) && aligned16(y) && aligned16(workspace) &&
+                    (!residual || aligned16(residual)),
+                "bitlinear_forward: pointers must be 16-byte aligned");
+    BRL_REQUIRE(M >= 1, "bitlinear_forward: M = %d", M);
+    BRL_REQUIRE(x_dtype == BRL_F32 || x_dtype == BRL_BF16, "bitlinear_forward: unknown x_dtype %d", x_dtype);
+    BRL_REQUIRE(eps_act > 0.f, "bitlinear_forward: eps_act must be positive");
+    if (int rc = check_linear_shape(N, K, "bitlinear_forward")) return rc;
+    const BitlinearWs L = bitlinear_ws_layout(M, N, K);
+    if (ws_bytes < L.total) {
+        set_error("bitlinear_forward: workspace %zu < %zu", ws_bytes, L.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    if (M <= 4) {
+        GemvWs g;
+        g.tickets = reinterpret_cast<unsigned*>(base + L.tickets_off);
+        g.partial = reinterpret_cast<int32_t*>(base + L.partial_off);
+        return launch_gemv(x, x_dtype, M, K, N, static_cast<const uint32_t*>(packed), beta, eps_act, y, residual, xq_dbg,
+                           absmax_dbg, acc_dbg, g, s);
+    }
+    Carver c(base + L.act_off);
+    const ActBuf act = take_actbuf(c, M, K);
+    QuantArgs qa;
+    memset(&qa, 0, sizeof(qa));
+    qa.x = x; qa.x_dtype = x_dtype; qa.gain = nullptr; qa.glu = 0; qa.eps_norm = 0.f; qa.eps_act = eps_act;
+    qa.M = M; qa.K = K; qa.xq_rowmajor = xq_dbg; qa.absmax_tap = absmax_dbg;
+    if (int rc = launch_act_quant(qa, act, s)) return rc;
+    const WeightSegs w = one_seg(packed, beta, N);
+    return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, s);
+}
+
+size_t brl_ffn_workspace_bytes(int M, int d, int f) {
+    if (M < 1 || d < 1 || f < 1) return 0;
+    return ffn_ws_layout(M, d, f).total;
+}
+
+int ffn_block_forward(const brl_ffn_weights* w, const void* x, int x_dtype, int M, int d, int f, float eps_norm,
+                      float eps_act, float* y, void* workspace, size_t ws_bytes, void* stream) {
+    if (int rc = check_ffn(w, d, f, "ffn_block_forward")) return rc;
+    BRL_REQUIRE(x && y && workspace && aligned16(x) && aligned16(y) && aligned16(workspace),
+                "ffn_block_forward: null or misaligned pointer");
+    BRL_REQUIRE(x != (const void*)y, "ffn_block_forward: y must not alias x");
+    BRL_REQUIRE(M >= 1, "ffn_block_forward: M = %d", M);
+    BRL_REQUIRE(x_dtype == BRL_F32 || x_dtype == BRL_BF16, "ffn_block_forward: unknown x_dtype %d", x_dtype);
+    BRL_REQUIRE(eps_act > 0.f && eps_norm >= 0.f, "ffn_block_forward: bad eps");
+    const FfnWs L = ffn_ws_layout(M, d, f);
+    if (ws_bytes < L.total) {
+        set_error("ffn_block_forward: workspace %zu < %zu", ws_bytes, L.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    const float* x32 = static_cast<const float*>(x);
+    if (x_dtype == BRL_BF16) {
+        float* xf = reinterpret_cast<float*>(base + L.xf_off);
+        if (int rc = launch_widen_bf16(static_cast<const uint16_t*>(x), (size_t)M * d, xf, s)) return rc;
+        x32 = xf;
+    }
+    Carver c1(base + L.act1_off);
+    const ActBuf act1 = take_actbuf(c1, M, d);
+    Carver c2(base + L.act2_off);
+    const ActBuf act2 = take_actbuf(c2, M, f);
+    float* gu = reinterpret_cast<float*>(base + L.gu_off);
+    return run_ffn(w, x32, x, x_dtype, M, d, f, eps_norm, eps_act, y, act1, gu, act2, s);
+}
+
+size_t brl_encoder_workspace_bytes(const brl_encoder* enc, int B, int S) {
+    if (!enc || B < 1 || S < 1 || enc->d < 1 || enc->f < 1 || enc->head_dim < 2) return 0;
+    return encoder_ws_layout(enc, B, S).total;
+}
+
+int encoder_forward(const brl_encoder* enc, const int32_t* ids, int B, int S, const int32_t* lengths, float* h,
+                    void* workspace, size_t ws_bytes, void* stream) {
+    if (int rc = check_encoder(enc)) return rc;
+    BRL_REQUIRE(ids && h && workspace && aligned16(h) && aligned16(workspace), "encoder_forward: null or misaligned pointer");
+    BRL_REQUIRE(B >= 1 && S >= 1, "encoder_forward: B = %d, S = %d", B, S);
+    BRL_REQUIRE((long long)S <= (1 << 20), "encoder_forward: S too large");
+    BRL_REQUIRE(enc->eps_act > 0.f && enc->eps_norm >= 0.f && enc->rope_theta > 0.f, "encoder_forward: bad eps / theta");
+    const EncWs L = encoder_ws_layout(enc, B, S);
+    if (ws_bytes < L.total) {
+        set_error("encoder_forward: workspace %zu < %zu", ws_bytes, L.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    const int d = enc->d, f = enc->f, dh = enc->head_dim;
+    const int dq = enc->n_heads * dh, dkv = enc->n_kv_heads * dh;
+    float* x = reinterpret_cast<float*>(base + L.x_off);
+    float* big = reinterpret_cast<float*>(base + L.big_off);
+    float* cos_t = reinterpret_cast<float*>(base + L.cos_off);
+    float* sin_t = reinterpret_cast<float*>(base + L.sin_off);
+    float* rinv = reinterpret_cast<float*>(base + L.rinv_off);
+    if (int rc = launch_rope_table(cos_t, sin_t, S, dh, enc->rope_theta, s)) return rc;
+
+    for (int b0 = 0; b0 < B; b0 += L.states_mb) {
+        const int nb = (B - b0 < L.states_mb) ? B - b0 : L.states_mb;
+        const int Mt = nb * S;
+        Carver c(base + L.act_off);
+        int kmax = d > dq ? d : dq;
+        if (f > kmax) kmax = f;
+        const ActBuf act = take_actbuf(c, L.states_mb * S, kmax);
+        float* qkv = big;
+        float* att = big + (size_t)Mt * L.big_ld_qkv;
+        if (int rc = launch_embed(enc->embedding, ids + (size_t)b0 * S, Mt, d, enc->vocab, x, s)) return rc;
+        for (int l = 0; l < enc->n_layers; ++l) {
+            const brl_layer_weights& w = enc->layers[l];
+            QuantArgs qa;
+            memset(&qa, 0, sizeof(qa));
+            qa.x = x; qa.x_dtype = BRL_F32; qa.gain = w.attn_norm_g; qa.eps_norm = enc->eps_norm; qa.eps_act = enc->eps_act;
+            qa.M = Mt; qa.K = d;
+            if (int rc = launch_act_quant(qa, act, s)) return rc;
+            WeightSegs wqkv;
+            memset(&wqkv, 0, sizeof(wqkv));
+            add_seg(wqkv, w.wq_packed, w.wq_beta, dq);
+            add_seg(wqkv, w.wk_packed, w.wk_beta, dkv);
+            add_seg(wqkv, w.wv_packed, w.wv_beta, dkv);
+            if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, s)) return rc;
+            if (int rc = launch_attention_f32(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t, sin_t,
+                                              att, s))
+                return rc;
+            QuantArgs qo;
+            memset(&qo, 0, sizeof(qo));
+            qo.x = att; qo.x_dtype = BRL_F32; qo.gain = w.attn_subln_g; qo.eps_norm = enc->eps_norm; qo.eps_act = enc->eps_act;
+            qo.M = Mt; qo.K = dq;
+            if (int rc = launch_act_quant(qo, act, s)) return rc;
+            const WeightSegs wo = one_seg(w.wo_packed, w.wo_beta, d);
+            if (int rc = launch_gemm(act, wo, Mt, d, dq, x, d, x, nullptr, s)) return rc;
+            if (int rc = run_ffn(&w.ffn, x, x, BRL_F32, Mt, d, f, enc->eps_norm, enc->eps_act, x, act, big, act, s))
+                return rc;
+        }
+        if (int rc = launch_final_pool(x, enc->final_norm_g, nb, S, d, lengths ? lengths + b0 : nullptr, enc->eps_norm,
+                                       rinv, h + (size_t)b0 * d, s))
+            return rc;
+    }
+    return BRL_OK;
+}
+
+size_t brl_head_workspace_bytes(const brl_head* head, int B) {
+    if (!head || B < 1) return 0;
+    if (!head->policy.dims || !head->value.dims || head->policy.n_layers < 1 || head->value.n_layers < 1 ||
+        head->policy.n_layers > 8 || head->value.n_layers > 8)
+        return 0;
+    size_t mx = mlp_hidden_max(&head->policy);
+    const size_t mv = mlp_hidden_max(&head->value);
+    if (mv > mx) mx = mv;
+    return 2 * round_up_sz((size_t)B * mx * sizeof(double), ALIGN);
+}
+
+int policy_value_head(const brl_head* head, const float* h, int B, float* logits, float* value, void* workspace,
+                      size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(head && h && logits && value && workspace, "policy_value_head: null pointer");
+    BRL_REQUIRE(B >= 1, "policy_value_head: B = %d", B);
+    if (int rc = check_mlp(&head->policy, "policy head", 0)) return rc;
+    if (int rc = check_mlp(&head->value, "value head", 1)) return rc;
+    BRL_REQUIRE(head->policy.dims[0] == head->value.dims[0], "policy_value_head: heads disagree on input width");
+    const size_t need = brl_head_workspace_bytes(head, B);
+    if (ws_bytes < need) {
+        set_error("policy_value_head: workspace %zu < %zu", ws_bytes, need);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    double* buf0 = static_cast<double*>(workspace);
+    double* buf1 = reinterpret_cast<double*>(static_cast<char*>(workspace) + need / 2);
+    if (int rc = run_mlp(&head->policy, h, B, logits, buf0, buf1, s)) return rc;
+    return run_mlp(&head->value, h, B, value, buf0, buf1, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Shared declarations of the gfx950 kernels: layouts, launch helpers, errors.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bitrl.h"
+
+namespace brl {
+
+// ---- error plumbing (host) ----
+void set_error(const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what);
+
+#define BRL_HIP_CHECK(expr)                                   \
+    do {                                                      \
+        hipError_t e__ = (expr);                              \
+        if (e__ != hipSuccess) return ::brl::hip_fail(e__, #expr); \
+    } while (0)
+
+#define BRL_LAUNCH_CHECK(name)                                \
+    do {                                                      \
+        hipError_t e__ = hipGetLastError();                   \
+        if (e__ != hipSuccess) return ::brl::hip_fail(e__, name); \
+    } while (0)
+
+#define BRL_REQUIRE(cond, ...)                                \
+    do {                                                      \
+        if (!(cond)) { ::brl::set_error(__VA_ARGS__); return BRL_EINVAL; } \
+    } while (0)
+
+// ---- sizes ----
+constexpr int WAVE = 64;
+constexpr int NB = 32;        // rows of one weight block / tokens of one activation block
+constexpr int SBK = 128;      // columns of one super-block (four MFMA k-steps of 32)
+constexpr int MAX_K = 9216;   // one token row is held in one wavefront's registers
+
+__host__ __device__ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+__host__ __device__ inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+// Offset of the 32-bit word holding weights (row n, columns 16*kk .. 16*kk+15)
+// in the packed blob; nsb = Kp / 128.
+__host__ __device__ inline size_t packed_word_index(int n, int kk, int nsb) {
+    int nb = n >> 5, r = n & 31;
+    int sb = kk >> 3, dd = (kk >> 1) & 3, hh = kk & 1;
+    return (((size_t)nb * nsb + sb) * 64 + (hh * 32 + r)) * 4 + dd;
+}
+
+// Byte offset of activation (token m, column k) in the tiled int8 buffer: a
+// token block of 32 rows x 128 columns is 4 KB, made of four 1 KB fragments
+// (one per MFMA k-step) in which lane (m & 31) + 32 * ((k >> 4) & 1) owns 16
+// consecutive bytes.
+__host__ __device__ inline size_t tiled_act_offset(int m, int k, int nsb) {
+    int mb = m >> 5, r = m & 31;
+    int sb = k >> 7, dd = (k >> 5) & 3, hh = (k >> 4) & 1, i = k & 15;
+    return ((((size_t)mb * nsb + sb) * 4 + dd) * 64 + (hh * 32 + r)) * 16 + i;
+}
+
+// ---- quantised activations of one GEMM input (device buffers in a workspace) ----
+struct ActBuf {
+    int8_t* q;        // tiled int8 [Mp/32][nsb][4][64][16]
+    float* absmax;    // [Mp] clamped absmax a'
+    float* dscale;    // [Mp] a' / 127
+    int32_t* sumq;    // [Mp] sum_k q (for the offset-code correction)
+};
+
+// ---- up to three weight matrices sharing one activation (q|k|v, gate|up) ----
+struct WeightSegs {
+    const uint32_t* packed[3];
+    const float* beta[3];
+    int nb_end[3];    // exclusive end, in 32-row blocks, of each segment
+    int n_end[3];     // exclusive end, in rows
+    int count;
+};
+
+// ---- kernel launchers (host) ----
+// weight ternarisation
+int launch_quantize_weights(const float* W, int N, int K, float eps, uint32_t* packed, float* beta,
+                            int8_t* codes_dbg, double* partials, int* flag, hipStream_t s);
+int launch_unpack_codes(const uint32_t* packed, int N, int K, int8_t* codes, hipStream_t s);
+int quantize_partials_count(int N, int K);
+
+// activation quantisation (mode: plain / RMSNorm / GLU + RMSNorm)
+struct QuantArgs {
+    const void* x;          // [M, K] fp32 or bf16; for GLU: [M, 2K] fp32 (gate | up)
+    int x_dtype;
+    const float* gain;      // RMSNorm gain [K] or nullptr (no norm)
+    int glu;                // 1: h = sqrelu(x[:, :K]) * x[:, K:] first
+    float eps_norm, eps_act;
+    int M, K;
+    int8_t* xq_rowmajor;    // optional tap [M, K]
+    float* absmax_tap;      // optional tap [M]
+};
+int launch_act_quant(const QuantArgs& a, const ActBuf& out, hipStream_t s);
+
+// int8 MFMA GEMM with fused dequant epilogue
+int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K,
+                float* y, int ldy, const float* residual, int32_t* acc_dbg, hipStream_t s);
+
+// bandwidth-bound GEMV (M <= 4), activation quantisation fused
+struct GemvWs { int32_t* partial; unsigned* tickets; };
+int gemv_ksplit(int N, int K);
+int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t* packed, const float* beta,
+                float eps_act, float* y, const float* residual, int8_t* xq_dbg, float* absmax_dbg,
+                int32_t* acc_dbg, const GemvWs& ws, hipStream_t s);
+
+// attention, embedding, pooling, heads
+int launch_rope_table(float* cos_t, float* sin_t, int S, int head_dim, float theta, hipStream_t s);
+int launch_attention_f32(const float* qkv, int ld, int B, int S, int n_heads, int n_kv_heads, int head_dim,
+                         const float* cos_t, const float* sin_t, float* out, hipStream_t s);
+int launch_embed(const uint16_t* table, const int32_t* ids, int M, int d, int vocab, float* x, hipStream_t s);
+int launch_final_pool(const float* x, const float* gain, int B, int S, int d, const int32_t* lengths,
+                      float eps_norm, float* rinv, float* h, hipStream_t s);
+int launch_mlp_layer(const double* in64, const float* in32, const float* W, const float* b, int B, int in_dim,
+                     int out_dim, int act, double* out64, float* out32, hipStream_t s);
+int launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s);   // n % 8 == 0
+
+}  // namespace brl

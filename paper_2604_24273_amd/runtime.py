@@ -1,0 +1,156 @@
+"""Convenience holders around the C ABI: device buffers, packed weights, encoder tables.
+
+Nothing here computes anything of the method: tensors are allocated with
+torch, filled by the library's kernels, and handed back to the library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import synth
+
+DEV = "cuda"
+
+
+def device_bytes(n: int) -> torch.Tensor:
+    return torch.empty(max(int(n), 16), dtype=torch.uint8, device=DEV)
+
+
+class Workspace:
+    """A caller-owned scratch buffer, initialised once as the ABI requires."""
+
+    def __init__(self, nbytes: int):
+        self.buf = device_bytes(nbytes)
+        B.brl_workspace_init(self.buf)
+
+    def ensure(self, nbytes: int) -> "Workspace":
+        if self.buf.numel() < nbytes:
+            self.buf = device_bytes(nbytes)
+            B.brl_workspace_init(self.buf)
+        return self
+
+
+@dataclass
+class PackedLinear:
+    packed: torch.Tensor        # uint8 [brl_packed_bytes]
+    beta: torch.Tensor          # float32 [1]
+    n_out: int
+    k_in: int
+    codes: Optional[torch.Tensor] = None   # int8 [n_out, k_in] debug tap
+
+
+_qws: Optional[torch.Tensor] = None
+
+
+def quantize_linear(W, eps: float = 1e-5, want_codes: bool = False) -> PackedLinear:
+    """fp32 master weights (numpy or torch, host or device) -> packed ternary weights on the GPU."""
+    global _qws
+    if isinstance(W, np.ndarray):
+        W = torch.from_numpy(np.ascontiguousarray(W, dtype=np.float32))
+    Wd = W.to(DEV, dtype=torch.float32).contiguous()
+    n, k = Wd.shape
+    packed = device_bytes(B.brl_packed_bytes(n, k))
+    beta = torch.empty(1, dtype=torch.float32, device=DEV)
+    codes = torch.empty((n, k), dtype=torch.int8, device=DEV) if want_codes else None
+    need = B.brl_quantize_workspace_bytes(n, k)
+    if _qws is None or _qws.numel() < need:
+        _qws = device_bytes(need)
+    B.bitlinear_quantize_weights(Wd, eps, packed, beta, codes, _qws)
+    return PackedLinear(packed, beta, n, k, codes)
+
+
+def dev(a: np.ndarray, dtype=None) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV).contiguous()
+
+
+def bf16_from_bits(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on the GPU (a reinterpretation, no rounding)."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(DEV)
+    return t.view(torch.bfloat16).contiguous()
+
+
+class FFNHandle:
+    def __init__(self, norm_g, W_gate, W_up, subln_g, W_down, eps: float = 1e-5):
+        self.d, self.f = W_down.shape[0], W_gate.shape[0]
+        self.norm_g = dev(norm_g)
+        self.subln_g = dev(subln_g)
+        self.gate = quantize_linear(W_gate, eps)
+        self.up = quantize_linear(W_up, eps)
+        self.down = quantize_linear(W_down, eps)
+        self.struct = B.make_ffn_weights(self.norm_g, self.gate.packed, self.gate.beta, self.up.packed, self.up.beta,
+                                         self.subln_g, self.down.packed, self.down.beta)
+
+
+class EncoderHandle:
+    """Device-resident packed encoder: embedding, per-layer packed weights, the ABI structs."""
+
+    def __init__(self, shape: synth.EncoderShape, seed: int = 0, eps_norm: float = 1e-5, eps_act: float = 1e-5,
+                 layer_sink=None, n_layers: Optional[int] = None):
+        self.shape = shape
+        L = shape.n_layers if n_layers is None else n_layers
+        self.keep: List[object] = []
+        self.embedding = torch.from_numpy(synth.embedding_bf16(seed, shape).view(np.int16)).to(DEV)
+        self.final_norm_g = dev(synth.final_norm_gain(seed, shape))
+        self.layer_structs = (B.brl_layer_weights * max(L, 1))()
+        with ThreadPoolExecutor(max_workers=2) as ex:
+            fut = ex.submit(synth.encoder_layer, seed, shape, 0) if L > 0 else None
+            for l in range(L):
+                w = fut.result()
+                fut = ex.submit(synth.encoder_layer, seed, shape, l + 1) if l + 1 < L else None
+                if layer_sink is not None:
+                    layer_sink(l, w)
+                t = {k: (dev(v) if v.ndim == 1 else quantize_linear(v, eps_act)) for k, v in w.items()}
+                self.keep.append(t)
+                s = self.layer_structs[l]
+                s.attn_norm_g = t["attn_norm_g"].data_ptr()
+                s.wq_packed, s.wq_beta = t["Wq"].packed.data_ptr(), t["Wq"].beta.data_ptr()
+                s.wk_packed, s.wk_beta = t["Wk"].packed.data_ptr(), t["Wk"].beta.data_ptr()
+                s.wv_packed, s.wv_beta = t["Wv"].packed.data_ptr(), t["Wv"].beta.data_ptr()
+                s.attn_subln_g = t["attn_subln_g"].data_ptr()
+                s.wo_packed, s.wo_beta = t["Wo"].packed.data_ptr(), t["Wo"].beta.data_ptr()
+                s.ffn = B.make_ffn_weights(t["ffn_norm_g"], t["W_gate"].packed, t["W_gate"].beta, t["W_up"].packed,
+                                           t["W_up"].beta, t["ffn_subln_g"], t["W_down"].packed, t["W_down"].beta)
+        self.struct = B.brl_encoder(L, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f, shape.vocab,
+                                    shape.rope_theta, eps_norm, eps_act, B.BRL_ATTN_F32,
+                                    self.embedding.data_ptr(), self.final_norm_g.data_ptr(),
+                                    C.cast(self.layer_structs, C.POINTER(B.brl_layer_weights)))
+        self.ws: Optional[Workspace] = None
+
+    def forward(self, ids: torch.Tensor, lengths: Optional[torch.Tensor] = None) -> torch.Tensor:
+        b, s = ids.shape
+        need = B.brl_encoder_workspace_bytes(self.struct, b, s)
+        self.ws = Workspace(need) if self.ws is None else self.ws.ensure(need)
+        h = torch.empty((b, self.shape.d), dtype=torch.float32, device=DEV)
+        B.encoder_forward(self.struct, ids, b, s, lengths, h, self.ws.buf)
+        return h
+
+
+class HeadHandle:
+    def __init__(self, shape: synth.EncoderShape, seed: int = 0, act: int = B.BRL_ACT_TANH):
+        pw, pb = synth.head_params(seed, shape, "policy")
+        vw, vb = synth.head_params(seed, shape, "value")
+        self.host = {"policy": (pw, pb), "value": (vw, vb)}
+        self.pol, self._k1 = B.make_mlp([dev(w) for w in pw], [dev(b) for b in pb], act)
+        self.val, self._k2 = B.make_mlp([dev(w) for w in vw], [dev(b) for b in vb], act)
+        self.struct = B.brl_head(self.pol, self.val)
+        self.n_actions = shape.n_actions
+        self.ws: Optional[Workspace] = None
+
+    def forward(self, h: torch.Tensor):
+        b = h.shape[0]
+        need = B.brl_head_workspace_bytes(self.struct, b)
+        self.ws = Workspace(need) if self.ws is None else self.ws.ensure(need)
+        logits = torch.empty((b, self.n_actions), dtype=torch.float32, device=DEV)
+        value = torch.empty((b,), dtype=torch.float32, device=DEV)
+        B.policy_value_head(self.struct, h, b, logits, value, self.ws.buf)
+        return logits, value

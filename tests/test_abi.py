@@ -1,0 +1,105 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the
+header declares, answers its size queries and rejects bad arguments before any
+kernel would be enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2604_24273_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2604_24273_amd import build
+        build.build()
+    binding.lib()
+    return binding
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "bitrl.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{}]*\)\s*;", src)
+    return sorted(set(names))
+
+
+def test_header_symbols_are_exported_and_bound(B):
+    names = _declared_functions()
+    assert {"bitlinear_quantize_weights", "bitlinear_forward", "ffn_block_forward", "encoder_forward",
+            "policy_value_head"} <= set(names)
+    handle = B.lib()
+    for n in names:
+        assert hasattr(handle, n), n
+    assert set(names) == set(B.EXPORTS)
+    assert B.brl_abi_version() == 1
+
+
+def test_struct_layouts_match_the_header(B):
+    p = C.sizeof(C.c_void_p)
+    assert C.sizeof(B.brl_ffn_weights) == 8 * p
+    assert C.sizeof(B.brl_layer_weights) == 10 * p + 8 * p
+    assert C.sizeof(B.brl_encoder) == 7 * 4 + 3 * 4 + 4 + 4 + 3 * p    # 7 ints, 3 floats, 1 int, pad, 3 pointers
+    assert C.sizeof(B.brl_mlp) == 8 + 3 * p + 8
+
+
+def test_size_queries(B):
+    assert B.brl_packed_bytes(2048, 2048) == 2048 * 2048 // 4
+    assert B.brl_packed_bytes(6912, 2560) == 4423680            # 2-bit packed decode-shape matrix
+    assert B.brl_packed_bytes(70, 200) == 96 * 256 // 4          # rows pad to 32, columns to 128
+    assert B.brl_packed_bytes(0, 5) == 0
+    assert B.brl_bitlinear_workspace_bytes(1, 6912, 2560) > 0
+    assert B.brl_bitlinear_workspace_bytes(256, 6912, 2560) >= 256 * 2560
+    assert B.brl_ffn_workspace_bytes(256, 2560, 6912) >= 256 * 2 * 6912 * 4
+    assert B.brl_quantize_workspace_bytes(10, 10) >= 8192
+
+
+def test_bad_arguments_are_rejected_on_the_host(B):
+    lib = B.lib()
+    fake = C.c_void_p(0x1000)          # aligned, never dereferenced: checks fail first
+    odd = C.c_void_p(0x1004)
+
+    def err():
+        return lib.brl_last_error().decode()
+
+    # null / misaligned pointers
+    assert lib.bitlinear_forward(None, fake, 32, 128, fake, 0, 1, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert "null" in err()
+    assert lib.bitlinear_forward(fake, fake, 32, 128, odd, 0, 1, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert "aligned" in err()
+    # shapes
+    assert lib.bitlinear_forward(fake, fake, 32, 100, fake, 0, 1, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert "multiple of 8" in err()
+    assert lib.bitlinear_forward(fake, fake, 32, 16384, fake, 0, 1, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert lib.bitlinear_forward(fake, fake, 32, 128, fake, 0, 0, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert lib.bitlinear_forward(fake, fake, 32, 128, fake, 7, 1, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    # workspace too small
+    assert lib.bitlinear_forward(fake, fake, 32, 128, fake, 0, 64, 1e-5, fake, None, None, None, None, fake, 16, None) == B.BRL_ENOSPC
+    assert "workspace" in err()
+    assert lib.bitlinear_quantize_weights(fake, 4, 4, 1e-5, fake, fake, None, fake, 8, None) == B.BRL_ENOSPC
+    assert lib.bitlinear_quantize_weights(fake, 0, 4, 1e-5, fake, fake, None, fake, 1 << 20, None) == B.BRL_EINVAL
+    # ffn / encoder / head tables
+    w = B.brl_ffn_weights()
+    assert lib.ffn_block_forward(C.byref(w), fake, 0, 4, 128, 256, 1e-5, 1e-5, fake, fake, 1 << 30, None) == B.BRL_EINVAL
+    enc = B.brl_encoder()
+    assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
+    enc = B.brl_encoder(0, 256, 4, 3, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
+    assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert "n_kv_heads" in err()
+    enc = B.brl_encoder(0, 256, 4, 2, 48, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
+    assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert "head_dim" in err()
+    head = B.brl_head()
+    assert lib.policy_value_head(C.byref(head), fake, 1, fake, fake, fake, 1 << 20, None) == B.BRL_EINVAL
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2604_24273_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith(".py"):
+                txt = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in txt.replace("CPU oracle's tests", ""), fn
