@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the frozen ternary-encoder hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of seeded synthetic
+states: token ids -> embedding -> 30 x (RMSNorm, int8 quant, q|k|v BitLinear,
+rotary causal GQA attention, subLN, o BitLinear, RMSNorm, gate|up BitLinear,
+squared-ReLU GLU, subLN, down BitLinear) -> final norm -> mean-pool -> fp32
+policy / value heads, at the 2B BitNet shape with 64 states x 128 tokens.
+Weights, embedding and ids are resident in HBM before the timed region.
+
+Prints ONE JSON line (see README for the fields).  Besides the
+headline states/s it carries the roofline of the dominant kernel (the int8
+MFMA GEMM, durations from HIP events recorded by the library around every
+launch in a second, identically sized region), the 1-token GEMV pair figures
+and the CPU oracle timed on a bounded sample as context.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, TOP/s
+HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
+
+
+def linear_macs_per_token(shape) -> int:
+    dq = shape.n_heads * shape.head_dim
+    dkv = shape.n_kv_heads * shape.head_dim
+    per_layer = shape.d * (dq + 2 * dkv) + dq * shape.d + 2 * shape.f * shape.d + shape.d * shape.f
+    return per_layer * shape.n_layers
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--states", type=int, default=64)
+    ap.add_argument("--tokens", type=int, default=128)
+    ap.add_argument("--layers", type=int, default=None, help="debug only: fewer layers (invalidates the metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gemv", action="store_true")
+    ap.add_argument("--cpu-sample-states", type=int, default=2)
+    ap.add_argument("--gemv-calls", type=int, default=1000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2604_24273_amd import binding as B
+    from paper_2604_24273_amd import build as BUILD
+    from paper_2604_24273_amd import runtime as R
+    from paper_2604_24273_amd import synth
+
+    if not os.path.exists(B.LIB_PATH):
+        BUILD.build()
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    shape = synth.SHAPE_2B
+    n_layers = shape.n_layers if args.layers is None else args.layers
+    Bn, S = args.states, args.tokens
+    want_cpu = not args.no_cpu_baseline
+
+    # ---- weights: seeded host draws -> packed on the GPU; the oracle's copy is quantised on the side
+    oracle_jobs = []
+    pool = ThreadPoolExecutor(max_workers=4) if want_cpu else None
+    if want_cpu:
+        from oracle import bitrl_oracle as O
+
+        def _oracle_layer(w):
+            T = O.TernaryLinear.from_fp32
+            return O.LayerWeights(w["attn_norm_g"], T(w["Wq"]), T(w["Wk"]), T(w["Wv"]), w["attn_subln_g"], T(w["Wo"]),
+                                  O.FFNWeights(w["ffn_norm_g"], T(w["W_gate"]), T(w["W_up"]), w["ffn_subln_g"],
+                                               T(w["W_down"])))
+
+    def sink(l, w):
+        if want_cpu:
+            oracle_jobs.append(pool.submit(_oracle_layer, w))
+
+    t0 = time.time()
+    enc = R.EncoderHandle(shape, seed=0, layer_sink=sink, n_layers=n_layers)
+    head = R.HeadHandle(shape, seed=0)
+    ids_host = synth.token_ids(0, 500, (Bn, S), shape.vocab)
+    ids = R.dev(ids_host)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step():
+        h = enc.forward(ids)
+        return head.forward(h)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    states_per_s = Bn / (ms_per_step / 1e3)
+
+    # ---- per-kernel durations: same region again with the library's event timing on
+    B.brl_timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    B.brl_timing_enable(False)
+    classes = {}
+    for kc, name in enumerate(B.KERNEL_CLASSES):
+        n, ms = B.brl_timing_read(kc)
+        classes[name] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps}
+    gemm = classes["gemm"]
+    macs_tok = linear_macs_per_token(shape) * n_layers // shape.n_layers
+    ops_step = 2.0 * macs_tok * Bn * S
+    gemm_launches = max(gemm["launches_per_step"], 1)
+    gemm_avg_ms = gemm["ms_per_step"] / gemm_launches
+    ops_per_launch = ops_step / gemm_launches
+    achieved_tops = ops_per_launch / (gemm_avg_ms * 1e-3) / 1e12 if gemm_avg_ms > 0 else 0.0
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel<4,2,2,2,1> (int8 MFMA BitLinear)",
+                "achieved": round(achieved_tops, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": round(achieved_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                "avg_launch_ms": round(gemm_avg_ms, 5), "launches_per_step": gemm_launches,
+                "ops_per_launch": ops_per_launch}
+
+    # ---- 1-token GEMV pair (decode shape), 1000 calls
+    gemv = None
+    if not args.no_gemv:
+        gemv = bench_gemv(torch, B, R, synth, args.gemv_calls)
+
+    # ---- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if want_cpu:
+        from oracle import bitrl_oracle as O
+        layers = [j.result() for j in oracle_jobs]
+        pool.shutdown()
+        cfg = O.EncoderConfig(n_layers, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f,
+                              shape.vocab, shape.rope_theta)
+        emb = synth.embedding_bf16(0, shape)
+        gfin = synth.final_norm_gain(0, shape)
+        pol = O.MLP(*head.host["policy"], "tanh")
+        val = O.MLP(*head.host["value"], "tanh")
+        ns = max(1, min(args.cpu_sample_states, Bn))
+        t0 = time.perf_counter()
+        h_ref = O.encoder_forward(ids_host[:ns], emb, layers, gfin, cfg)
+        l_ref, v_ref = O.policy_value_head(h_ref, pol, val)
+        cpu_s = time.perf_counter() - t0
+        h_gpu = enc.forward(ids)[:ns].cpu().numpy().astype(np.float64)
+        cosines = [float(h_gpu[i] @ h_ref[i] / np.linalg.norm(h_gpu[i]) / np.linalg.norm(h_ref[i])) for i in range(ns)]
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        cpu = {"value": round(ns / cpu_s, 4), "unit": "states/s", "cores": int(cores), "kind": "oracle",
+               "sample": "%d of the %d states (%d tokens each, all %d layers + heads), NumPy oracle, fp64 BLAS integer matmul"
+                         % (ns, Bn, S, n_layers),
+               "seconds": round(cpu_s, 2), "min_cosine_gpu_vs_oracle": round(min(cosines), 6)}
+
+    out = {
+        "metric": "encoded RL states/sec at 2B shape (BitLinear int8 TOPS as % of roofline alongside)",
+        "value": round(states_per_s, 2), "unit": "states/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 (ternary x int8 -> int32, fp32 rescale)", "data": "synthetic",
+        "config": {"workload": "frozen 2B-shape ternary encoder + fp32 heads: %d layers, hidden %d, %d/%d heads, FFN %d, "
+                               "vocab %d; batch %d states x %d tokens, seed 0"
+                               % (n_layers, shape.d, shape.n_heads, shape.n_kv_heads, shape.f, shape.vocab, Bn, S),
+                   "states": Bn, "tokens_per_state": S, "int8_ops_per_step": ops_step},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernel_classes_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in classes.items()},
+        "linear_tops_wall": round(ops_step / (ms_per_step * 1e-3) / 1e12, 2),
+        "int8_ceiling_states_per_s": round(Bn / (ops_step / (INT8_MFMA_PEAK_TOPS * 1e12)), 1),
+        "gemv_pair": gemv,
+        "paper_context": {"hardware": "Raspberry Pi 4 (Cortex-A72 @ 1.5 GHz), bitnet.cpp", "steps_per_s": 40.3,
+                          "median_latency_ms": 24.8, "note": "one 15-40 token state per step; context only"},
+        "setup_seconds": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+def bench_gemv(torch, B, R, synth, calls: int):
+    """Decode-shape pair x[1,2560] -> up[6912] -> down[2560]: streaming over a pool of
+    distinct weight pairs larger than the on-chip caches, and resident on one pair."""
+    d, f = 2560, 6912
+    n_pairs = 64
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    pairs = []
+    for _ in range(n_pairs):
+        wu = torch.randn((f, d), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+        wd = torch.randn((d, f), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+        pairs.append((R.quantize_linear(wu), R.quantize_linear(wd)))
+        del wu, wd
+    x = R.dev(synth.normal(0, 10, (1, d)))
+    h = torch.empty((1, f), dtype=torch.float32, device="cuda")
+    y = torch.empty((1, d), dtype=torch.float32, device="cuda")
+    ws = R.Workspace(max(B.brl_bitlinear_workspace_bytes(1, f, d), B.brl_bitlinear_workspace_bytes(1, d, f)))
+    bytes_pair = 2 * B.brl_packed_bytes(f, d) + (d + f) + 4 * (d + f)     # packed W + int8 x + fp32 y
+
+    def run(pool_size, n):
+        for i in range(n):
+            up, dn = pairs[i % pool_size]
+            B.bitlinear_forward(up.packed, up.beta, f, d, x, 1, 1e-5, h, None, None, None, None, ws.buf)
+            B.bitlinear_forward(dn.packed, dn.beta, d, f, h, 1, 1e-5, y, None, None, None, None, ws.buf)
+
+    res = {"bytes_per_pair": bytes_pair, "calls": calls, "pool_pairs": n_pairs,
+           "pool_bytes": n_pairs * 2 * B.brl_packed_bytes(f, d)}
+    for mode, pool_size in (("streaming", n_pairs), ("resident", 1)):
+        run(pool_size, 50)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(pool_size, calls)
+        torch.cuda.synchronize()
+        wall_us = (time.perf_counter() - t0) / calls * 1e6
+        B.brl_timing_enable(True)
+        run(pool_size, calls)
+        torch.cuda.synchronize()
+        B.brl_timing_enable(False)
+        n, ms = B.brl_timing_read(B.BRL_KC_GEMV)
+        kern_us_pair = ms / max(n, 1) * 2 * 1e3
+        gbs = bytes_pair / (kern_us_pair * 1e-6) / 1e9 if kern_us_pair > 0 else 0.0
+        res[mode] = {"wall_us_per_pair": round(wall_us, 3), "kernel_us_per_pair": round(kern_us_pair, 3),
+                     "kernel_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                     "wall_GBps": round(bytes_pair / (wall_us * 1e-6) / 1e9, 1)}
+    res["roofline"] = {"bound": "hbm", "kernel": "gemv_kernel<1>", "achieved": res["streaming"]["kernel_GBps"],
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["streaming"]["frac_of_hbm_peak"], "traffic": None}
+    return res
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -204,6 +204,25 @@ int policy_value_head(const brl_head* head /* HOST */, const float* h, int B,
                       float* logits, float* value,
                       void* workspace, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Per-kernel timing with HIP events, for measurement harnesses (off by
+ * default; not a paper operation).  While enabled, every kernel launch of the
+ * library is bracketed by two events recorded on the launch stream.
+ * brl_timing_read() waits for the events recorded so far in one class, returns
+ * their number and summed elapsed milliseconds, and forgets them.  Enabling
+ * costs two event records per launch; do not enable under graph capture.
+ * ------------------------------------------------------------------------ */
+#define BRL_KC_QUANTIZE_WEIGHTS 0
+#define BRL_KC_ACT_QUANT        1   /* activation quantisation incl. fused norm / GLU */
+#define BRL_KC_GEMM             2   /* int8 MFMA BitLinear */
+#define BRL_KC_GEMV             3   /* 1..4 token BitLinear */
+#define BRL_KC_ATTENTION        4
+#define BRL_KC_OTHER            5   /* embedding, pooling, heads, fills */
+#define BRL_KC_COUNT            6
+
+int brl_timing_enable(int on);
+int brl_timing_read(int kernel_class, long long* launches, double* total_ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -87,6 +87,8 @@ _SIGNATURES = {
     "brl_head_workspace_bytes": (c_size_t, [C.POINTER(brl_head), c_int]),
     "policy_value_head": (c_int, [C.POINTER(brl_head), c_void_p, c_int, c_void_p, c_void_p,
                                   c_void_p, c_size_t, c_void_p]),
+    "brl_timing_enable": (c_int, [c_int]),
+    "brl_timing_read": (c_int, [c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
 }
 
 EXPORTS = tuple(_SIGNATURES)
@@ -203,6 +205,20 @@ def policy_value_head(head: brl_head, h: torch.Tensor, B: int, logits: torch.Ten
                       workspace: torch.Tensor) -> None:
     _check(lib().policy_value_head(C.byref(head), _ptr(h), B, _ptr(logits), _ptr(value), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+BRL_KC_QUANTIZE_WEIGHTS, BRL_KC_ACT_QUANT, BRL_KC_GEMM, BRL_KC_GEMV, BRL_KC_ATTENTION, BRL_KC_OTHER = range(6)
+KERNEL_CLASSES = ("quantize_weights", "act_quant", "gemm", "gemv", "attention", "other")
+
+
+def brl_timing_enable(on: bool) -> None:
+    _check(lib().brl_timing_enable(1 if on else 0))
+
+
+def brl_timing_read(kernel_class: int):
+    n, ms = C.c_longlong(0), C.c_double(0.0)
+    _check(lib().brl_timing_read(kernel_class, C.byref(n), C.byref(ms)))
+    return n.value, ms.value
 
 
 # ------------------------------------------------ struct builders (marshalling)

@@ -152,6 +152,7 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     const int nmb = a.Mp / NB;
     const int grid = ((nmb + 7) / 8) * 64;
     const int v4 = a.Kp / 256 + ((a.Kp % 256) ? 1 : 0);
+    LaunchTimer tm(BRL_KC_ACT_QUANT, s);
     if (v4 <= 4) {
         hipLaunchKernelGGL(act_quant_kernel<4>, dim3(grid), dim3(256), 0, s, a);
     } else if (v4 <= 12) {

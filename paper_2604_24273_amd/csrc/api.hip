@@ -3,6 +3,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <utility>
+#include <vector>
 
 #include "common.hpp"
 
@@ -20,6 +23,40 @@ void set_error(const char* fmt, ...) {
 int hip_fail(hipError_t e, const char* what) {
     set_error("HIP error %d (%s) at %s", (int)e, hipGetErrorString(e), what);
     return BRL_EHIP;
+}
+
+// ---- launch timing ----
+namespace {
+std::mutex g_tm_mu;
+bool g_tm_on = false;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_tm_events[BRL_KC_COUNT];
+std::vector<hipEvent_t> g_tm_free;
+
+hipEvent_t tm_get_event() {
+    if (!g_tm_free.empty()) {
+        hipEvent_t e = g_tm_free.back();
+        g_tm_free.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+LaunchTimer::LaunchTimer(int kernel_class, hipStream_t s) : stop_(nullptr), s_(s), on_(false) {
+    std::lock_guard<std::mutex> lk(g_tm_mu);
+    if (!g_tm_on) return;
+    hipEvent_t a = tm_get_event(), b = tm_get_event();
+    if (!a || !b) return;
+    (void)hipEventRecord(a, s);
+    g_tm_events[kernel_class].push_back(std::make_pair(a, b));
+    stop_ = b;
+    on_ = true;
+}
+
+LaunchTimer::~LaunchTimer() {
+    if (on_) (void)hipEventRecord(stop_, s_);
 }
 
 namespace {
@@ -258,6 +295,41 @@ int brl_abi_version(void) { return 1; }
 int brl_workspace_init(void* workspace, size_t ws_bytes, void* stream) {
     BRL_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace_init: null or misaligned workspace");
     return launch_fill_zero(workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int brl_timing_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_tm_mu);
+    g_tm_on = on != 0;
+    return BRL_OK;
+}
+
+int brl_timing_read(int kernel_class, long long* launches, double* total_ms) {
+    BRL_REQUIRE(kernel_class >= 0 && kernel_class < BRL_KC_COUNT, "timing_read: unknown class %d", kernel_class);
+    BRL_REQUIRE(launches && total_ms, "timing_read: null pointer");
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> evs;
+    {
+        std::lock_guard<std::mutex> lk(g_tm_mu);
+        evs.swap(g_tm_events[kernel_class]);
+    }
+    double sum = 0.0;
+    int rc = BRL_OK;
+    for (auto& pr : evs) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(pr.second);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, pr.first, pr.second);
+        if (e != hipSuccess && rc == BRL_OK) rc = hip_fail(e, "timing_read");
+        sum += (double)ms;
+    }
+    {
+        std::lock_guard<std::mutex> lk(g_tm_mu);
+        for (auto& pr : evs) {
+            g_tm_free.push_back(pr.first);
+            g_tm_free.push_back(pr.second);
+        }
+    }
+    *launches = (long long)evs.size();
+    *total_ms = sum;
+    return rc;
 }
 
 size_t brl_packed_bytes(int n_out, int k_in) {

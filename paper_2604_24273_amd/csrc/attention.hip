@@ -153,6 +153,7 @@ __global__ __launch_bounds__(AT_THREADS) void attention_f32_kernel(AttnArgs a) {
 int launch_rope_table(float* cos_t, float* sin_t, int S, int head_dim, float theta, hipStream_t s) {
     const int half = head_dim / 2;
     const int n = S * half;
+    LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, cos_t, sin_t, S, half, head_dim,
                        (double)theta);
     BRL_LAUNCH_CHECK("rope_table_kernel");
@@ -168,6 +169,7 @@ int launch_attention_f32(const float* qkv, int ld, int B, int S, int n_heads, in
     const int group = n_heads / n_kv_heads;
     const int chunks = (group * S + AT_THREADS - 1) / AT_THREADS;
     const dim3 grid((unsigned)((size_t)B * n_kv_heads * chunks));
+    LaunchTimer tm(BRL_KC_ATTENTION, s);
     switch (head_dim) {
         case 16: hipLaunchKernelGGL(attention_f32_kernel<16>, grid, dim3(AT_THREADS), 0, s, a); break;
         case 32: hipLaunchKernelGGL(attention_f32_kernel<32>, grid, dim3(AT_THREADS), 0, s, a); break;

@@ -30,6 +30,18 @@ int hip_fail(hipError_t e, const char* what);
         if (!(cond)) { ::brl::set_error(__VA_ARGS__); return BRL_EINVAL; } \
     } while (0)
 
+// ---- optional per-launch timing (host): brackets a launch with two events ----
+struct LaunchTimer {
+    LaunchTimer(int kernel_class, hipStream_t s);
+    ~LaunchTimer();
+    LaunchTimer(const LaunchTimer&) = delete;
+    LaunchTimer& operator=(const LaunchTimer&) = delete;
+  private:
+    hipEvent_t stop_;
+    hipStream_t s_;
+    bool on_;
+};
+
 // ---- sizes ----
 constexpr int WAVE = 64;
 constexpr int NB = 32;        // rows of one weight block / tokens of one activation block

@@ -12,6 +12,14 @@
 //     epilogue subtracts sum_k q (from the quantisation kernel) to get acc.
 // Integer sums are order independent, so the k-order inside a fragment only
 // has to agree between the two operands - it does, by construction of the layouts.
+//
+// Two kernels:
+//   gemm_lds_kernel    many tokens: the activation tile of a workgroup (up to
+//                      256 tokens x 128 k) is staged in LDS with direct
+//                      global->LDS loads, double buffered; the tiny packed weight
+//                      fragments go straight from L2 to registers.
+//   gemm_direct_kernel few tokens (weight streaming bound): no LDS staging, the
+//                      four wavefronts of a workgroup may split k.
 #include "common.hpp"
 
 namespace brl {
@@ -36,6 +44,7 @@ struct GemmArgs {
     int ldy;
     const float* residual;
     int32_t* acc_dbg;
+    int fast_epilogue;       // every segment a multiple of 32 rows, ldy % 4 == 0, no debug tap
 };
 
 __device__ inline v4i expand_codes(uint32_t p) {
@@ -51,58 +60,306 @@ __device__ inline uint32_t pick(const uint4& v, int dd) {
     return dd == 0 ? v.x : dd == 1 ? v.y : dd == 2 ? v.z : v.w;
 }
 
-// TM x TN 32x32 accumulator tiles per wavefront; WM x WN x WK wavefronts per
-// workgroup (WK > 1 splits the k range between wavefronts for skinny problems).
+__device__ inline v4i as_v4i(const uint4& u) {
+    v4i r;
+    r.x = (int)u.x; r.y = (int)u.y; r.z = (int)u.z; r.w = (int)u.w;
+    return r;
+}
+
+// XCD-aware tile order: workgroup w runs on XCD (w & 7); each XCD gets a
+// contiguous run of tiles, walked in groups of `group_m` row tiles so that the
+// tiles resident on one XCD share activation and weight panels in its L2.
+__device__ inline bool tile_of_block(const GemmArgs& g, int& tile_m, int& tile_n) {
+    const int total = g.tiles_m * g.tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return false;
+    const int gsz = g.group_m * g.tiles_n;
+    const int grp = T / gsz;
+    const int first_m = grp * g.group_m;
+    const int rows_in_grp = min(g.group_m, g.tiles_m - first_m);
+    tile_m = first_m + (T - grp * gsz) % rows_in_grp;
+    tile_n = (T - grp * gsz) / rows_in_grp;
+    return true;
+}
+
+// Where the TN weight blocks of a wavefront live: segment, packed pointer, output columns.
+template <int TN>
+struct BCols {
+    const uint4* ptr[TN];
+    int seg[TN], col0[TN], ncols[TN];
+    __device__ inline void init(const GemmArgs& g, int nb0, int lane) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int gnb = min(nb0 + j, g.nnb - 1);      // clamped blocks are computed but never stored
+            int s = 0;
+            if (g.nseg > 1 && gnb >= g.nb_end[0]) s = 1;
+            if (g.nseg > 2 && gnb >= g.nb_end[1]) s = 2;
+            const int nb_begin = s == 0 ? 0 : g.nb_end[s - 1];
+            const int n_begin = s == 0 ? 0 : g.n_end[s - 1];
+            const int lnb = gnb - nb_begin;
+            seg[j] = s;
+            col0[j] = n_begin + lnb * 32;
+            ncols[j] = (nb0 + j < g.nnb) ? min(32, g.n_end[s] - col0[j]) : 0;
+            ptr[j] = g.wp[s] + (size_t)lnb * g.nsb * 64 + lane;
+        }
+    }
+};
+
+// Output column and scale of global weight block gnb (runtime lookup, edge path only).
+__device__ inline void block_columns(const GemmArgs& g, int gnb, int& seg, int& col0, int& ncols) {
+    int s = 0;
+    if (g.nseg > 1 && gnb >= g.nb_end[0]) s = 1;
+    if (g.nseg > 2 && gnb >= g.nb_end[1]) s = 2;
+    const int nb_begin = s == 0 ? 0 : g.nb_end[s - 1];
+    const int n_begin = s == 0 ? 0 : g.n_end[s - 1];
+    seg = s;
+    col0 = n_begin + (gnb - nb_begin) * 32;
+    ncols = gnb < g.nnb ? min(32, g.n_end[s] - col0) : 0;
+}
+
+// Epilogue.  In a 32x32 accumulator tile a lane holds column (lane & 31) and rows
+// 8*(v/4) + 4*(lane/32) + v%4.  Each half token block of the wavefront (16 rows x
+// TN*32 columns; accumulator registers v < 8 or v >= 8) is turned through a
+// private LDS region into row-major order, so that the rescale reads 4
+// consecutive columns of one row per lane and the result leaves as 16-byte
+// stores (512-byte runs per row for TN = 4):
+//     y = (float(acc - sum_q[m]) * dscale[m]) * beta[n] (+ residual)
+// Interior tiles take the unguarded 16-byte path; tiles on the M / N edge (or with
+// debug taps, or unaligned rows) take a compact per-element loop.
+template <int TN>
+struct Epi {
+    static constexpr int W = TN * 32, LD = W + 4;
+    static constexpr int REGION = 16 * LD;        // ints of LDS per wavefront
+};
+
+template <int TM, int TN>
+__device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, const float (&beta)[TN],
+                                int lane, int* scr) {
+    constexpr int W = Epi<TN>::W, LD = Epi<TN>::LD;
+    constexpr int LPR = TN * 8;                  // lanes per row when each lane takes 4 columns
+    constexpr int RPP = 64 / LPR;                // rows per pass
+    const int cl = lane & 31, rh = (lane >> 5) * 4;
+    const bool interior = g.fast_epilogue && (mb0 + TM) * 32 <= g.M && nb0 + TN <= g.nnb;
+    const int c4 = lane % LPR, r0 = lane / LPR;
+    float my_beta = beta[0];
+#pragma unroll
+    for (int j = 1; j < TN; ++j)
+        if ((c4 >> 3) == j) my_beta = beta[j];
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if (mb0 + i >= g.nmb) break;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int mbase = (mb0 + i) * 32 + half * 16;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    scr[(8 * (v >> 2) + rh + (v & 3)) * LD + j * 32 + cl] = acc[i][j][half * 8 + v];
+            __builtin_amdgcn_wave_barrier();
+            if (interior) {
+                const int col_base = nb0 * 32 + 4 * c4;
+#pragma unroll
+                for (int p = 0; p < TN * 2; ++p) {
+                    const int row = p * RPP + r0;
+                    const int4 a = *reinterpret_cast<const int4*>(&scr[row * LD + 4 * c4]);
+                    const float d = g.dscale[mbase + row];
+                    const int sq = g.sumq[mbase + row];
+                    const size_t o = (size_t)(mbase + row) * g.ldy + col_base;
+                    float4 val;
+                    val.x = ((float)(a.x - sq) * d) * my_beta;
+                    val.y = ((float)(a.y - sq) * d) * my_beta;
+                    val.z = ((float)(a.z - sq) * d) * my_beta;
+                    val.w = ((float)(a.w - sq) * d) * my_beta;
+                    if (g.residual) {
+                        const float4 r = *reinterpret_cast<const float4*>(g.residual + o);
+                        val.x = val.x + r.x; val.y = val.y + r.y; val.z = val.z + r.z; val.w = val.w + r.w;
+                    }
+                    *reinterpret_cast<float4*>(g.y + o) = val;
+                }
+            } else {
+#pragma unroll 1
+                for (int e = lane; e < 16 * W; e += 64) {
+                    const int row = e / W, c = e % W;
+                    const int m = mbase + row;
+                    int seg, col0, ncols;
+                    block_columns(g, nb0 + (c >> 5), seg, col0, ncols);
+                    if (m < g.M && (c & 31) < ncols) {
+                        const int a = scr[row * LD + c] - g.sumq[m];
+                        const size_t o = (size_t)m * g.ldy + col0 + (c & 31);
+                        float val = ((float)a * g.dscale[m]) * (*g.beta[seg]);
+                        if (g.residual) val = val + g.residual[o];
+                        g.y[o] = val;
+                        if (g.acc_dbg) g.acc_dbg[o] = a;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Many-token kernel: WM x WN wavefronts, each TM x TN tiles; both operands staged
+// through LDS with direct global->LDS loads, double buffered.
+// ---------------------------------------------------------------------------
+template <int TM, int TN, int WM, int WN>
+struct LdsTile {
+    static constexpr int NW = WM * WN;
+    static constexpr int AFR = WM * TM * 4;           // 1 KB activation fragments per stage
+    static constexpr int BFR = WN * TN;               // 1 KB packed weight blocks per stage
+    static constexpr int STAGE = (AFR + BFR) * 64;    // uint4 elements per stage
+    static constexpr int APW = (AFR + NW - 1) / NW, BPW = (BFR + NW - 1) / NW;   // pieces copied per wavefront
+
+    // Request super-block sb of this wavefront's share of a stage: piece c of
+    // wavefront w is fragment c*NW + w (lane i's 16 bytes land at offset 16 i).
+    static __device__ inline void issue(const uint4* const (&asrc)[APW], const uint4* const (&bsrc)[BPW], int sb,
+                                        uint4* st, int wave) {
+#pragma unroll
+        for (int c = 0; c < APW; ++c)
+            if (AFR % NW == 0 || c * NW + wave < AFR)
+                __builtin_amdgcn_global_load_lds(asrc[c] + (size_t)sb * 256, st + (c * NW + wave) * 64, 16, 0, 0);
+#pragma unroll
+        for (int c = 0; c < BPW; ++c)
+            if (BFR % NW == 0 || c * NW + wave < BFR)
+                __builtin_amdgcn_global_load_lds(bsrc[c] + (size_t)sb * 64, st + (AFR + c * NW + wave) * 64, 16, 0, 0);
+    }
+
+    // One super-block (128 k) of MFMAs from one stage.  The next activation
+    // fragment is requested from LDS before the MFMAs of the current one issue.
+    static __device__ inline void compute(v16i (&acc)[TM][TN], const uint4* st, int wm, int wn, int lane) {
+        const uint4* sa = st + (wm * TM * 4) * 64 + lane;
+        const uint4* sbp = st + (AFR + wn * TN) * 64 + lane;
+        uint4 bq[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bq[j] = sbp[j * 64];
+        uint4 a_cur = sa[0];
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd) {
+            v4i bf[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bf[j] = expand_codes(pick(bq[j], dd));
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int nxt = (i + 1 < TM) ? (i + 1) * 4 + dd : (dd + 1 < 4 ? dd + 1 : dd);
+                const uint4 a_nxt = sa[nxt * 64];
+                const v4i af = as_v4i(a_cur);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[j], acc[i][j], 0, 0, 0);
+                a_cur = a_nxt;
+            }
+        }
+    }
+};
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_lds_kernel(GemmArgs g) {
+    using Tile = LdsTile<TM, TN, WM, WN>;
+    constexpr int NW = Tile::NW;
+    __shared__ __attribute__((aligned(1024))) uint4 stage0[Tile::STAGE];
+    __shared__ __attribute__((aligned(1024))) uint4 stage1[Tile::STAGE];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wn = wave % WN, wm = wave / WN;
+    int tile_m, tile_n;
+    if (!tile_of_block(g, tile_m, tile_n)) return;
+
+    const int mb_tile0 = tile_m * WM * TM;
+    const int mb0 = mb_tile0 + wm * TM;
+    const int nb_tile0 = tile_n * WN * TN;
+    const int nb0 = nb_tile0 + wn * TN;
+
+    // sources of the stage pieces this wavefront copies (clamped: padding is never stored)
+    const uint4* asrc[Tile::APW];
+#pragma unroll
+    for (int c = 0; c < Tile::APW; ++c) {
+        const int f = c * NW + wave;                              // fragment = (token block, k-step)
+        const int mb = min(mb_tile0 + (f >> 2), g.nmb - 1);
+        asrc[c] = g.A + ((size_t)mb * g.nsb * 4 + (f & 3)) * 64 + lane;
+    }
+    const uint4* bsrc[Tile::BPW];
+#pragma unroll
+    for (int c = 0; c < Tile::BPW; ++c) {
+        BCols<1> one;
+        one.init(g, nb_tile0 + c * NW + wave, lane);
+        bsrc[c] = one.ptr[0];
+    }
+
+    float beta[TN];
+    {
+        BCols<TN> bc;
+        bc.init(g, nb0, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) beta[j] = *g.beta[bc.seg[j]];
+    }
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    // Double buffering with two distinct LDS objects: while one is read, the
+    // other is filled.  A stage requested in one step is waited for (vmcnt 0)
+    // at the top of the next, so its latency hides behind 4*TM*TN MFMAs.
+    Tile::issue(asrc, bsrc, 0, stage0, wave);
+    int sb = 0;
+    for (; sb + 1 < g.nsb; sb += 2) {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        Tile::issue(asrc, bsrc, sb + 1, stage1, wave);
+        Tile::compute(acc, stage0, wm, wn, lane);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (sb + 2 < g.nsb) Tile::issue(asrc, bsrc, sb + 2, stage0, wave);
+        Tile::compute(acc, stage1, wm, wn, lane);
+    }
+    if (sb < g.nsb) {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        Tile::compute(acc, stage0, wm, wn, lane);
+    }
+
+    // the stages are free once every wavefront has left the k loop: reuse them for the epilogue
+    __syncthreads();
+    static_assert((NW / 2) * Epi<TN>::REGION * 4 <= Tile::STAGE * 16, "half of the epilogue regions per stage");
+    int* scr = reinterpret_cast<int*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * Epi<TN>::REGION;
+    epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
+}
+
+// ---------------------------------------------------------------------------
+// Few-token kernel: operands straight from L2 to registers; WK wavefronts split k.
+// ---------------------------------------------------------------------------
 template <int TM, int TN, int WM, int WN, int WK>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs g) {
     static_assert(WM * WN * WK == 4, "four wavefronts per workgroup");
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wk = wave % WK;
     const int wn = (wave / WK) % WN;
     const int wm = wave / (WK * WN);
-
-    // XCD-aware tile order: workgroup w runs on XCD (w & 7); give each XCD a
-    // contiguous run of tiles, walked in groups of `group_m` row tiles so the
-    // tiles resident on one XCD share activation and weight panels in its L2.
-    const int total = g.tiles_m * g.tiles_n;
-    const int per_xcd = (total + 7) / 8;
-    const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return;
-    const int gsz = g.group_m * g.tiles_n;
-    const int grp = T / gsz;
-    const int first_m = grp * g.group_m;
-    const int rows_in_grp = min(g.group_m, g.tiles_m - first_m);
-    const int tile_m = first_m + (T - grp * gsz) % rows_in_grp;
-    const int tile_n = (T - grp * gsz) / rows_in_grp;
+    int tile_m, tile_n;
+    if (!tile_of_block(g, tile_m, tile_n)) return;
 
     const int mb0 = (tile_m * WM + wm) * TM;
     const int nb0 = (tile_n * WN + wn) * TN;
-
-    // operand base pointers (clamped to the last valid block: results of clamped
-    // blocks are never stored)
     const uint4* aptr[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int mb = min(mb0 + i, g.nmb - 1);
         aptr[i] = g.A + (size_t)mb * g.nsb * 256 + lane;
     }
-    const uint4* bptr[TN];
-    int seg_of[TN], col0[TN], ncols[TN];
+    BCols<TN> bc;
+    bc.init(g, nb0, lane);
+    float beta[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int gnb = min(nb0 + j, g.nnb - 1);
-        int s = 0;
-        if (g.nseg > 1 && gnb >= g.nb_end[0]) s = 1;
-        if (g.nseg > 2 && gnb >= g.nb_end[1]) s = 2;
-        const int nb_begin = s == 0 ? 0 : g.nb_end[s - 1];
-        const int n_begin = s == 0 ? 0 : g.n_end[s - 1];
-        const int lnb = gnb - nb_begin;
-        seg_of[j] = s;
-        col0[j] = n_begin + lnb * 32;
-        ncols[j] = (nb0 + j < g.nnb) ? min(32, g.n_end[s] - col0[j]) : 0;
-        bptr[j] = g.wp[s] + (size_t)lnb * g.nsb * 64 + lane;
-    }
+    for (int j = 0; j < TN; ++j) beta[j] = *g.beta[bc.seg[j]];
 
     v16i acc[TM][TN];
 #pragma unroll
@@ -124,13 +381,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) aq[dd][i] = aptr[i][((size_t)sb_begin * 4 + dd) * 64];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bq[j] = bptr[j][(size_t)sb_begin * 64];
+        for (int j = 0; j < TN; ++j) bq[j] = bc.ptr[j][(size_t)sb_begin * 64];
 
         for (int sb = sb_begin; sb < sb_end; ++sb) {
             const int nxt = min(sb + 1, sb_end - 1);
             uint4 bnext[TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bnext[j] = bptr[j][(size_t)nxt * 64];
+            for (int j = 0; j < TN; ++j) bnext[j] = bc.ptr[j][(size_t)nxt * 64];
 #pragma unroll
             for (int dd = 0; dd < 4; ++dd) {
                 v4i bf[TN];
@@ -138,9 +395,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
                 for (int j = 0; j < TN; ++j) bf[j] = expand_codes(pick(bq[j], dd));
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
-                    const uint4 araw = aq[dd][i];
-                    v4i af;
-                    af.x = (int)araw.x; af.y = (int)araw.y; af.z = (int)araw.z; af.w = (int)araw.w;
+                    const v4i af = as_v4i(aq[dd][i]);
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[j], acc[i][j], 0, 0, 0);
@@ -154,9 +409,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         }
     }
 
-    if (WK > 1) {
+    if constexpr (WK > 1) {
         // reduce the k-split partial accumulators through LDS into wavefront wk == 0
-        __shared__ int red[(WK > 1 ? (WK - 1) : 1) * WM * WN * TM * TN * 16 * 64];
+        __shared__ int red[(WK - 1) * WM * WN * TM * TN * 16 * 64];
         const int slot = ((wm * WN + wn) * (WK - 1) + (wk - 1)) * TM * TN * 16 * 64;
         if (wk > 0) {
 #pragma unroll
@@ -179,51 +434,33 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         }
     }
 
-    // epilogue: a lane holds column (lane & 31) and rows 8*(v/4) + 4*(lane/32) + v%4 of each tile
-    const int cl = lane & 31;
-    const int rh = (lane >> 5) * 4;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int mbase = (mb0 + i) * 32;
-        if (mb0 + i >= g.nmb) continue;
-        float ds[16];
-        int sq[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = mbase + 8 * (v >> 2) + rh + (v & 3);   // < Mp: buffers are padded
-            ds[v] = g.dscale[m];
-            sq[v] = g.sumq[m];
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            if (cl >= ncols[j]) continue;
-            const float beta = *g.beta[seg_of[j]];
-            const int col = col0[j] + cl;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mbase + 8 * (v >> 2) + rh + (v & 3);
-                if (m < g.M) {
-                    const int a = acc[i][j][v] - sq[v];
-                    const size_t o = (size_t)m * g.ldy + col;
-                    float val = ((float)a * ds[v]) * beta;
-                    if (g.residual) val = val + g.residual[o];
-                    g.y[o] = val;
-                    if (g.acc_dbg) g.acc_dbg[o] = a;
-                }
-            }
-        }
-    }
+    __shared__ __attribute__((aligned(16))) int escr[(WK > 1 ? WM * WN : 4) * Epi<TN>::REGION];
+    epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, escr + ((WK > 1) ? (wm * WN + wn) : wave) * Epi<TN>::REGION);
 }
 
 template <int TM, int TN, int WM, int WN, int WK>
-int launch_cfg(GemmArgs& g, hipStream_t s) {
+int launch_direct(GemmArgs& g, hipStream_t s) {
     g.tiles_m = (g.nmb + WM * TM - 1) / (WM * TM);
     g.tiles_n = (g.nnb + WN * TN - 1) / (WN * TN);
     g.group_m = 4;
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_kernel<TM, TN, WM, WN, WK>), dim3(grid), dim3(256), 0, s, g);
-    BRL_LAUNCH_CHECK("gemm_kernel");
+    LaunchTimer tm(BRL_KC_GEMM, s);
+    hipLaunchKernelGGL((gemm_direct_kernel<TM, TN, WM, WN, WK>), dim3(grid), dim3(256), 0, s, g);
+    BRL_LAUNCH_CHECK("gemm_direct_kernel");
+    return BRL_OK;
+}
+
+template <int TM, int TN, int WM, int WN>
+int launch_lds(GemmArgs& g, hipStream_t s) {
+    g.tiles_m = (g.nmb + WM * TM - 1) / (WM * TM);
+    g.tiles_n = (g.nnb + WN * TN - 1) / (WN * TN);
+    g.group_m = 4;
+    const int total = g.tiles_m * g.tiles_n;
+    const int grid = ((total + 7) / 8) * 8;
+    LaunchTimer tm(BRL_KC_GEMM, s);
+    hipLaunchKernelGGL((gemm_lds_kernel<TM, TN, WM, WN>), dim3(grid), dim3(WM * WN * 64), 0, s, g);
+    BRL_LAUNCH_CHECK("gemm_lds_kernel");
     return BRL_OK;
 }
 
@@ -250,15 +487,29 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     g.ldy = ldy;
     g.residual = residual;
     g.acc_dbg = acc_dbg;
+    g.fast_epilogue = (acc_dbg == nullptr && ldy % 4 == 0) ? 1 : 0;
+    for (int i = 0; i < w.count; ++i)
+        if ((w.n_end[i] - (i ? w.n_end[i - 1] : 0)) % 32 != 0) g.fast_epilogue = 0;
     (void)N;
-    // Tile choice: big tiles once the grid fills the chip; k-split wavefronts
-    // for skinny (few-token) problems, where weight streaming bounds the time.
-    const long blocks_big = (long)((g.nmb + 7) / 8) * ((g.nnb + 3) / 4);
-    if (g.nmb <= 1) return launch_cfg<1, 1, 1, 1, 4>(g, s);
-    if (g.nmb <= 2) return launch_cfg<2, 1, 1, 1, 4>(g, s);
-    if (g.nmb <= 4) return launch_cfg<2, 1, 2, 2, 1>(g, s);
-    if (blocks_big >= 512) return launch_cfg<4, 2, 2, 2, 1>(g, s);
-    return launch_cfg<2, 2, 2, 2, 1>(g, s);
+    // Tile choice: k-split wavefronts for skinny (few-token) problems, where weight
+    // streaming bounds the time; LDS-staged big tiles once the grid fills the chip.
+    if (g.nmb <= 1) return launch_direct<1, 1, 1, 1, 4>(g, s);
+    if (g.nmb <= 2) return launch_direct<2, 1, 1, 1, 4>(g, s);
+    if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
+    static const char* force = getenv("BRL_GEMM_TILE");
+    if (force) {
+        if (force[0] == 'a') return launch_lds<4, 4, 2, 2>(g, s);
+        if (force[0] == 'c') return launch_lds<2, 2, 2, 2>(g, s);
+        if (force[0] == 'e') return launch_lds<2, 4, 4, 2>(g, s);
+        if (force[0] == 'f') return launch_lds<4, 2, 2, 4>(g, s);
+        if (force[0] == 'g') return launch_lds<2, 2, 4, 2>(g, s);
+        if (force[0] == 'h') return launch_lds<2, 2, 2, 4>(g, s);
+    }
+    // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64) once they fill the chip twice over,
+    // else 128 x 128 tiles (4 wavefronts)
+    const long t_wide = (long)((g.nmb + 3) / 4) * ((g.nnb + 7) / 8);
+    if (t_wide >= 512) return launch_lds<2, 2, 2, 4>(g, s);
+    return launch_lds<2, 2, 2, 2>(g, s);
 }
 
 }  // namespace brl

@@ -229,6 +229,7 @@ int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t*
     g.partial = ws.partial; g.tickets = ws.tickets;
     const int nnb = round_up(N, NB) / NB;
     const int grid = nnb * g.ksplit;
+    LaunchTimer tm(BRL_KC_GEMV, s);
     switch (M) {
         case 1: hipLaunchKernelGGL(gemv_kernel<1>, dim3(grid), dim3(GV_THREADS), 0, s, g); break;
         case 2: hipLaunchKernelGGL(gemv_kernel<2>, dim3(grid), dim3(GV_THREADS), 0, s, g); break;

@@ -118,6 +118,7 @@ int launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
+    LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16,
                        reinterpret_cast<unsigned char*>(p) + n16 * 16, bytes - n16 * 16);
     BRL_LAUNCH_CHECK("fill_zero_kernel");
@@ -126,6 +127,7 @@ int launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
 
 int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s) {
     const size_t n8 = n / 8;
+    LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(widen_bf16_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, in, n8, out);
     BRL_LAUNCH_CHECK("widen_bf16_kernel");
     return BRL_OK;
@@ -133,6 +135,7 @@ int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s) {
 
 int launch_embed(const uint16_t* table, const int32_t* ids, int M, int d, int vocab, float* x, hipStream_t s) {
     const size_t n = (size_t)M * (d / 8);
+    LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(embed_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, table, ids, M, d, vocab, x);
     BRL_LAUNCH_CHECK("embed_kernel");
     return BRL_OK;
@@ -141,6 +144,7 @@ int launch_embed(const uint16_t* table, const int32_t* ids, int M, int d, int vo
 int launch_final_pool(const float* x, const float* gain, int B, int S, int d, const int32_t* lengths, float eps_norm,
                       float* rinv, float* h, hipStream_t s) {
     const int M = B * S;
+    LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(row_rinv_kernel, dim3((M + 3) / 4), dim3(256), 0, s, x, M, d, eps_norm, rinv);
     BRL_LAUNCH_CHECK("row_rinv_kernel");
     const size_t n = (size_t)B * d;
@@ -153,6 +157,7 @@ int launch_mlp_layer(const double* in64, const float* in32, const float* W, cons
                      int out_dim, int act, double* out64, float* out32, hipStream_t s) {
     const size_t waves = (size_t)B * out_dim;
     const int last = out32 != nullptr;
+    LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(mlp_layer_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, in64, in32, W, b, B, in_dim,
                        out_dim, act, last, out64, out32);
     BRL_LAUNCH_CHECK("mlp_layer_kernel");

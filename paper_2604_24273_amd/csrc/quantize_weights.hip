@@ -131,6 +131,7 @@ int launch_quantize_weights(const float* W, int N, int K, float eps, uint32_t* p
     const int g = quantize_partials_count(N, K);
     size_t chunk = (total + g - 1) / g;
     chunk = (chunk + 3) / 4 * 4;
+    LaunchTimer tm(BRL_KC_QUANTIZE_WEIGHTS, s);
     hipLaunchKernelGGL(absum_partials_kernel, dim3(g), dim3(QW_THREADS), 0, s, W, total, chunk, partials);
     BRL_LAUNCH_CHECK("absum_partials_kernel");
     const int nsb = round_up(K, SBK) / SBK;
@@ -146,6 +147,7 @@ int launch_unpack_codes(const uint32_t* packed, int N, int K, int8_t* codes, hip
     const int nsb = round_up(K, SBK) / SBK;
     const size_t n_words = (size_t)(round_up(N, NB) / NB) * nsb * 256;
     const size_t blocks = (n_words + QW_THREADS - 1) / QW_THREADS;
+    LaunchTimer tm(BRL_KC_QUANTIZE_WEIGHTS, s);
     hipLaunchKernelGGL(unpack_codes_kernel, dim3((unsigned)blocks), dim3(QW_THREADS), 0, s, packed, N, K, nsb, n_words,
                        codes);
     BRL_LAUNCH_CHECK("unpack_codes_kernel");

@@ -100,6 +100,7 @@ def _run_bitlinear(B, R, pl, X, residual=None, taps=True):
     (1, 6912, 2560), (1, 2560, 6912), (2, 2560, 6912), (3, 200, 264), (4, 6912, 2560),   # GEMV path
     (5, 96, 128), (33, 200, 264), (64, 2560, 2560), (100, 640, 2560), (300, 1000, 520),
     (256, 6912, 2560), (257, 2560, 6912), (1100, 3200, 3200),
+    (2050, 8192, 264), (2048, 8200, 128),      # enough tiles for the 8-wavefront kernel, ragged edges
 ])
 def test_bitlinear_forward_parity(m, n, k):
     B, R = _mods()
