@@ -58,6 +58,9 @@ extern "C" {
 
 /* ---- attention arithmetic ---- */
 #define BRL_ATTN_F32  0   /* fp32 FMA on the vector ALUs */
+#define BRL_ATTN_MFMA 1   /* matrix cores: every operand as fp16 hi + lo pair (three MFMAs per product,
+                             about 21 mantissa bits), fp32 softmax and accumulation; q, k, v must lie
+                             within the fp16 range (|x| < 65504) */
 
 const char* brl_last_error(void);
 int         brl_abi_version(void);

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libbitrl.so")
 BRL_OK, BRL_EINVAL, BRL_ENOSPC, BRL_EHIP = 0, 1, 2, 3
 BRL_F32, BRL_BF16 = 0, 1
 BRL_ACT_TANH, BRL_ACT_RELU = 0, 1
-BRL_ATTN_F32 = 0
+BRL_ATTN_F32, BRL_ATTN_MFMA = 0, 1
 
 c_void_p, c_int, c_float, c_size_t = C.c_void_p, C.c_int, C.c_float, C.c_size_t
 

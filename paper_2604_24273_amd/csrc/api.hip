@@ -226,7 +226,8 @@ int check_encoder(const brl_encoder* e) {
                 "encoder: head_dim %d not in {16, 32, 64, 100, 128}", e->head_dim);
     BRL_REQUIRE(e->d % 8 == 0 && e->f % 8 == 0 && (e->n_kv_heads * e->head_dim) % 4 == 0,
                 "encoder: d and f must be multiples of 8");
-    BRL_REQUIRE(e->attn_precision == BRL_ATTN_F32, "encoder: unknown attn_precision %d", e->attn_precision);
+    BRL_REQUIRE(e->attn_precision == BRL_ATTN_F32 || e->attn_precision == BRL_ATTN_MFMA,
+                "encoder: unknown attn_precision %d", e->attn_precision);
     const int dq = e->n_heads * e->head_dim;
     if (int rc = check_linear_shape(dq, e->d, "encoder")) return rc;
     if (int rc = check_linear_shape(e->d, dq, "encoder")) return rc;
@@ -500,9 +501,15 @@ int encoder_forward(const brl_encoder* enc, const int32_t* ids, int B, int S, co
             add_seg(wqkv, w.wk_packed, w.wk_beta, dkv);
             add_seg(wqkv, w.wv_packed, w.wv_beta, dkv);
             if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, s)) return rc;
-            if (int rc = launch_attention_f32(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t, sin_t,
-                                              att, s))
-                return rc;
+            if (enc->attn_precision == BRL_ATTN_MFMA) {
+                if (int rc = launch_attention_mfma(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t,
+                                                  sin_t, att, s))
+                    return rc;
+            } else {
+                if (int rc = launch_attention_f32(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t,
+                                                  sin_t, att, s))
+                    return rc;
+            }
             QuantArgs qo;
             memset(&qo, 0, sizeof(qo));
             qo.x = att; qo.x_dtype = BRL_F32; qo.gain = w.attn_subln_g; qo.eps_norm = enc->eps_norm; qo.eps_act = enc->eps_act;

@@ -95,7 +95,8 @@ class EncoderHandle:
     """Device-resident packed encoder: embedding, per-layer packed weights, the ABI structs."""
 
     def __init__(self, shape: synth.EncoderShape, seed: int = 0, eps_norm: float = 1e-5, eps_act: float = 1e-5,
-                 layer_sink=None, n_layers: Optional[int] = None):
+                 layer_sink=None, n_layers: Optional[int] = None,
+                 attn_precision: int = B.BRL_ATTN_MFMA):
         self.shape = shape
         L = shape.n_layers if n_layers is None else n_layers
         self.keep: List[object] = []
@@ -121,7 +122,7 @@ class EncoderHandle:
                 s.ffn = B.make_ffn_weights(t["ffn_norm_g"], t["W_gate"].packed, t["W_gate"].beta, t["W_up"].packed,
                                            t["W_up"].beta, t["ffn_subln_g"], t["W_down"].packed, t["W_down"].beta)
         self.struct = B.brl_encoder(L, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f, shape.vocab,
-                                    shape.rope_theta, eps_norm, eps_act, B.BRL_ATTN_F32,
+                                    shape.rope_theta, eps_norm, eps_act, attn_precision,
                                     self.embedding.data_ptr(), self.final_norm_g.data_ptr(),
                                     C.cast(self.layer_structs, C.POINTER(B.brl_layer_weights)))
         self.ws: Optional[Workspace] = None
