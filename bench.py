@@ -131,7 +131,7 @@ def main() -> int:
     gemm_avg_ms = gemm["ms_per_step"] / gemm_launches
     ops_per_launch = ops_step / gemm_launches
     achieved_tops = ops_per_launch / (gemm_avg_ms * 1e-3) / 1e12 if gemm_avg_ms > 0 else 0.0
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel<4,2,2,2,1> (int8 MFMA BitLinear)",
+    roofline = {"bound": "mfma", "kernel": "gemm_lds_kernel<2,2,2,4> (int8 MFMA BitLinear)",
                 "achieved": round(achieved_tops, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
                 "avg_launch_ms": round(gemm_avg_ms, 5), "launches_per_step": gemm_launches,

@@ -20,9 +20,8 @@
  *  - The caller owns all memory.  The library never allocates or frees device
  *    memory: scratch space comes in through `workspace` / `ws_bytes`, whose
  *    minimum size the matching brl_*_workspace_bytes() query returns.  A
- *    workspace must be passed once through brl_workspace_init() after it is
- *    allocated; forward calls leave it initialised.  Calls that share a
- *    workspace must be ordered on one stream.
+ *    workspace carries no state between calls (its contents may be anything on
+ *    entry); calls that share a workspace must be ordered on one stream.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    *_forward calls only enqueue kernels: no host synchronisation, no
  *    device-to-host copy.  bitlinear_quantize_weights (an offline step)
@@ -64,10 +63,6 @@ extern "C" {
 
 const char* brl_last_error(void);
 int         brl_abi_version(void);
-
-/* Fill a freshly allocated workspace with the state the forward calls expect
- * (all zero).  Enqueued on `stream`. */
-int brl_workspace_init(void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * BitLinear weights (Sec. 3.1, Eq. 2: Q(W) = sign(W) * 1[|W| > tau]).

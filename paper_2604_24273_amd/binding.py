@@ -69,7 +69,6 @@ _lib = None
 _SIGNATURES = {
     "brl_last_error": (C.c_char_p, []),
     "brl_abi_version": (c_int, []),
-    "brl_workspace_init": (c_int, [c_void_p, c_size_t, c_void_p]),
     "brl_packed_bytes": (c_size_t, [c_int, c_int]),
     "brl_quantize_workspace_bytes": (c_size_t, [c_int, c_int]),
     "bitlinear_quantize_weights": (c_int, [c_void_p, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p,
@@ -139,10 +138,6 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 def brl_abi_version() -> int:
     return lib().brl_abi_version()
-
-
-def brl_workspace_init(workspace: torch.Tensor) -> None:
-    _check(lib().brl_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def brl_packed_bytes(n_out: int, k_in: int) -> int:

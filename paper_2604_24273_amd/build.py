@@ -55,6 +55,23 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+MICRO = os.path.join(PKG, "microbench")
+
+
+def build_microbench(verbose: bool = False) -> None:
+    """Stand-alone probes (pure MFMA rate, HBM stream) under microbench/bin/."""
+    out = os.path.join(MICRO, "bin")
+    os.makedirs(out, exist_ok=True)
+    for name in ("mfma_i8_peak", "stream_copy"):
+        cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-o", os.path.join(out, name), os.path.join(MICRO, name + ".hip")]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (name, r.stderr[-4000:]))
+        if verbose:
+            print("built", os.path.join(out, name))
+
+
 if __name__ == "__main__":
     build(verbose=True)
+    build_microbench(verbose=True)
     sys.exit(0)

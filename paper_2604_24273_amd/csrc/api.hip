@@ -118,18 +118,15 @@ void add_seg(WeightSegs& w, const void* packed, const float* beta, int N) {
     w.n_end[i] = (i ? w.n_end[i - 1] : 0) + N;
 }
 
-// tickets (kept zero between calls) | gemv partials | activation buffer
+// the quantised activations of the MFMA path (the 1..4 token path needs no scratch)
 struct BitlinearWs {
-    size_t tickets_off, partial_off, act_off, total;
+    size_t act_off, total;
 };
 
 BitlinearWs bitlinear_ws_layout(int M, int N, int K) {
     BitlinearWs L;
-    const size_t nnb = round_up(N, NB) / NB;
-    L.tickets_off = 0;
-    L.partial_off = round_up_sz(nnb * sizeof(unsigned), ALIGN);
-    const size_t ks = (size_t)gemv_ksplit(N, K);
-    L.act_off = L.partial_off + round_up_sz(nnb * ks * 4 * 32 * sizeof(int32_t), ALIGN);
+    (void)N;
+    L.act_off = 0;
     L.total = L.act_off + actbuf_bytes(M, K);
     return L;
 }
@@ -293,11 +290,6 @@ const char* brl_last_error(void) { return g_err; }
 
 int brl_abi_version(void) { return 1; }
 
-int brl_workspace_init(void* workspace, size_t ws_bytes, void* stream) {
-    BRL_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace_init: null or misaligned workspace");
-    return launch_fill_zero(workspace, ws_bytes, static_cast<hipStream_t>(stream));
-}
-
 int brl_timing_enable(int on) {
     std::lock_guard<std::mutex> lk(g_tm_mu);
     g_tm_on = on != 0;
@@ -398,11 +390,8 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K, const
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* base = static_cast<char*>(workspace);
     if (M <= 4) {
-        GemvWs g;
-        g.tickets = reinterpret_cast<unsigned*>(base + L.tickets_off);
-        g.partial = reinterpret_cast<int32_t*>(base + L.partial_off);
         return launch_gemv(x, x_dtype, M, K, N, static_cast<const uint32_t*>(packed), beta, eps_act, y, residual, xq_dbg,
-                           absmax_dbg, acc_dbg, g, s);
+                           absmax_dbg, acc_dbg, s);
     }
     Carver c(base + L.act_off);
     const ActBuf act = take_actbuf(c, M, K);

@@ -1,28 +1,30 @@
 // Bandwidth-bound BitLinear for 1..4 tokens: y = dequant(codes . quant(x)).
 //
+// One workgroup of 16 wavefronts owns one block of 32 output rows over the whole
+// k range, so no partial sums ever cross workgroups (no atomics, no fences).
 // The packed weights are streamed once with 16-byte-per-lane loads (a wavefront
-// reads one contiguous 1 KB block of 32 rows x 128 columns), expanded in
-// registers to offset codes c = code + 1 and contracted with v_dot4_i32_i8
-// against the int8 activations held in LDS.  A workgroup owns one 32-row block
-// and one slice of k; its weight loads are issued before anything else, and the
-// activation quantisation (every workgroup redoes the cheap absmax of the few
-// token rows, and quantises only its own k-slice) runs while they are in flight.
-// Slices of one row block meet through a self-resetting ticket: the workgroup
-// that arrives last adds the integer partials (order free, exact) and applies
-// the fp32 rescale.
+// reads contiguous 1 KB blocks of 32 rows x 128 columns), all of them issued
+// before anything else: the whole matrix is in flight while the activation
+// rows are quantised (every workgroup redoes that cheap step on its own).
+// The 2-bit fields are expanded in registers to offset codes c = code + 1 and
+// contracted with v_dot4_i32_i8 against the int8 activations held in LDS;
+// sum_k q is subtracted at the end.
 #include "common.hpp"
 
 namespace brl {
 
 namespace {
 
-constexpr int GV_THREADS = 256;
-constexpr int GV_MAX_SB = 8;      // super-blocks per workgroup slice (two per wavefront)
+constexpr int GV_THREADS = 1024;
+constexpr int GV_WAVES = GV_THREADS / 64;
+constexpr int GV_MAX_SB = MAX_K / SBK;                                   // 72 super-blocks
+constexpr int GV_SB_PER_WAVE = (GV_MAX_SB + GV_WAVES - 1) / GV_WAVES;    // 5
+constexpr int GV_X4 = (MAX_K / 4 + GV_THREADS - 1) / GV_THREADS;         // float4 of one row per thread: 3
 
 struct GemvArgs {
     const void* x;
     int x_dtype;
-    int M, K, N, nsb, ksplit, sb_per;
+    int M, K, N, nsb;
     const uint4* packed;
     const float* beta;
     float eps_act;
@@ -31,8 +33,6 @@ struct GemvArgs {
     int8_t* xq_dbg;
     float* absmax_dbg;
     int32_t* acc_dbg;
-    int32_t* partial;
-    unsigned* tickets;
 };
 
 __device__ inline float4 load_x4(const void* x, int dtype, size_t idx) {
@@ -46,83 +46,78 @@ __device__ inline float4 load_x4(const void* x, int dtype, size_t idx) {
 
 template <int MT>
 __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvArgs g) {
-    __shared__ __attribute__((aligned(16))) int xq[MT][GV_MAX_SB * 128 / 4];       // int8 activations of this k-slice, as dwords
-    __shared__ float wmax[MT][GV_THREADS / 64];
-    __shared__ int wsum[MT][GV_THREADS / 64];
-    __shared__ int red[GV_THREADS / 64][MT][32];
-    __shared__ unsigned last_flag;
+    __shared__ __attribute__((aligned(16))) int xq[MT][MAX_K / 4];     // int8 activations as dwords (zero padded)
+    __shared__ float wmax[MT][GV_WAVES];
+    __shared__ int wsum[MT][GV_WAVES];
+    __shared__ int red[GV_WAVES][MT][32];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nb = blockIdx.x / g.ksplit, ks = blockIdx.x % g.ksplit;
-    const int sb_lo = ks * g.sb_per;
-    const int sb_hi = min(g.nsb, sb_lo + g.sb_per);
+    const int nb = blockIdx.x;
+    const int K = g.K, Kp = g.nsb * SBK;
 
     // 1. weight loads first: they do not depend on the activations
-    uint4 wreg[2];
-    bool have[2];
+    uint4 wreg[GV_SB_PER_WAVE];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int sb = sb_lo + wave + 4 * u;
-        have[u] = sb < sb_hi;
+    for (int u = 0; u < GV_SB_PER_WAVE; ++u) {
+        const int sb = wave + GV_WAVES * u;
         wreg[u] = make_uint4(0x55555555u, 0x55555555u, 0x55555555u, 0x55555555u);   // code 0 everywhere
-        if (have[u]) wreg[u] = g.packed[((size_t)nb * g.nsb + sb) * 64 + lane];
+        if (sb < g.nsb) wreg[u] = g.packed[((size_t)nb * g.nsb + sb) * 64 + lane];
     }
 
-    // 2. per-token absmax over the whole row
-    const int K = g.K;
+    // 2. activation rows into registers, per-token absmax
+    float4 xv[MT][GV_X4];
     float tmax[MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) tmax[t] = 0.f;
-    for (int k = 4 * threadIdx.x; k < K; k += 4 * GV_THREADS) {
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            if (t < g.M) {
-                const float4 v = load_x4(g.x, g.x_dtype, (size_t)t * K + k);
-                tmax[t] = fmaxf(tmax[t], fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-            }
-        }
-    }
-#pragma unroll
     for (int t = 0; t < MT; ++t) {
+        tmax[t] = 0.f;
+#pragma unroll
+        for (int u = 0; u < GV_X4; ++u) {
+            const int k = 4 * ((int)threadIdx.x + GV_THREADS * u);
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < g.M && k < K) v = load_x4(g.x, g.x_dtype, (size_t)t * K + k);
+            xv[t][u] = v;
+            tmax[t] = fmaxf(tmax[t], fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) tmax[t] = fmaxf(tmax[t], __shfl_xor(tmax[t], off, 64));
         if (lane == 0) wmax[t][wave] = tmax[t];
     }
     __syncthreads();
-    float ac[MT], sc[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const float m = fmaxf(fmaxf(wmax[t][0], wmax[t][1]), fmaxf(wmax[t][2], wmax[t][3]));
-        ac[t] = fmaxf(m, g.eps_act);
-        sc[t] = 127.0f / ac[t];
-    }
 
-    // 3. quantise this workgroup's k-slice into LDS (thread -> 4 consecutive k)
-    const int k_lo = sb_lo * 128;
-    int qsum[MT];
+    // 3. quantise into LDS
+    float ac[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-        qsum[t] = 0;
-        const int k = k_lo + 4 * threadIdx.x;
-        int word = 0;
-        if (t < g.M && 4 * (int)threadIdx.x < (sb_hi - sb_lo) * 128 && k < K) {
-            const float4 v = load_x4(g.x, g.x_dtype, (size_t)t * K + k);
-            const int q0 = (int)fminf(fmaxf(rintf(v.x * sc[t]), -127.f), 127.f);
-            const int q1 = (int)fminf(fmaxf(rintf(v.y * sc[t]), -127.f), 127.f);
-            const int q2 = (int)fminf(fmaxf(rintf(v.z * sc[t]), -127.f), 127.f);
-            const int q3 = (int)fminf(fmaxf(rintf(v.w * sc[t]), -127.f), 127.f);
-            qsum[t] = q0 + q1 + q2 + q3;
-            word = (q0 & 0xff) | ((q1 & 0xff) << 8) | ((q2 & 0xff) << 16) | ((q3 & 0xff) << 24);
-            if (g.xq_dbg && nb == 0) *reinterpret_cast<int*>(g.xq_dbg + (size_t)t * K + k) = word;
-        }
-        xq[t][threadIdx.x] = word;
+        float m = wmax[t][0];
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) qsum[t] += __shfl_xor(qsum[t], off, 64);
-        if (lane == 0) wsum[t][wave] = qsum[t];
+        for (int w = 1; w < GV_WAVES; ++w) m = fmaxf(m, wmax[t][w]);
+        ac[t] = fmaxf(m, g.eps_act);
+        const float sc = 127.0f / ac[t];
+        int qsum = 0;
+#pragma unroll
+        for (int u = 0; u < GV_X4; ++u) {
+            const int k = 4 * ((int)threadIdx.x + GV_THREADS * u);
+            if (k < Kp) {
+                const float4 v = xv[t][u];
+                const int q0 = (int)fminf(fmaxf(rintf(v.x * sc), -127.f), 127.f);
+                const int q1 = (int)fminf(fmaxf(rintf(v.y * sc), -127.f), 127.f);
+                const int q2 = (int)fminf(fmaxf(rintf(v.z * sc), -127.f), 127.f);
+                const int q3 = (int)fminf(fmaxf(rintf(v.w * sc), -127.f), 127.f);
+                qsum += q0 + q1 + q2 + q3;
+                const int word = (q0 & 0xff) | ((q1 & 0xff) << 8) | ((q2 & 0xff) << 16) | ((q3 & 0xff) << 24);
+                xq[t][k >> 2] = word;
+                if (g.xq_dbg && nb == 0 && t < g.M && k < K) *reinterpret_cast<int*>(g.xq_dbg + (size_t)t * K + k) = word;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) qsum += __shfl_xor(qsum, off, 64);
+        if (lane == 0) wsum[t][wave] = qsum;
     }
-    if (g.absmax_dbg && blockIdx.x == 0 && threadIdx.x < MT && (int)threadIdx.x < g.M)
-        g.absmax_dbg[threadIdx.x] = fmaxf(fmaxf(fmaxf(wmax[threadIdx.x][0], wmax[threadIdx.x][1]),
-                                                fmaxf(wmax[threadIdx.x][2], wmax[threadIdx.x][3])), g.eps_act);
+    if (g.absmax_dbg && nb == 0 && threadIdx.x == 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+            if (t < g.M) g.absmax_dbg[t] = ac[t];
+    }
     __syncthreads();
 
     // 4. contract: lane (r, hh) holds row 32 nb + r, k-half hh of each 32-column step
@@ -131,23 +126,23 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvArgs g) {
     for (int t = 0; t < MT; ++t) acc[t] = 0;
     const int hh = lane >> 5;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        if (!have[u]) continue;
-        const int sbl = wave + 4 * u;                 // super-block index inside the slice
+    for (int u = 0; u < GV_SB_PER_WAVE; ++u) {
+        const int sb = wave + GV_WAVES * u;
+        if (sb >= g.nsb) continue;
         const uint32_t wd[4] = {wreg[u].x, wreg[u].y, wreg[u].z, wreg[u].w};
 #pragma unroll
         for (int dd = 0; dd < 4; ++dd) {
             const uint32_t p = wd[dd];
             const int c0 = (int)(p & 0x03030303u), c1 = (int)((p >> 2) & 0x03030303u);
             const int c2 = (int)((p >> 4) & 0x03030303u), c3 = (int)((p >> 6) & 0x03030303u);
-            const int xoff = (sbl * 128 + dd * 32 + hh * 16) / 4;
+            const int xoff = (sb * 128 + dd * 32 + hh * 16) / 4;
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                const int4 xv = *reinterpret_cast<const int4*>(&xq[t][xoff]);
-                acc[t] = __builtin_amdgcn_sdot4(c0, xv.x, acc[t], false);
-                acc[t] = __builtin_amdgcn_sdot4(c1, xv.y, acc[t], false);
-                acc[t] = __builtin_amdgcn_sdot4(c2, xv.z, acc[t], false);
-                acc[t] = __builtin_amdgcn_sdot4(c3, xv.w, acc[t], false);
+                const int4 xw = *reinterpret_cast<const int4*>(&xq[t][xoff]);
+                acc[t] = __builtin_amdgcn_sdot4(c0, xw.x, acc[t], false);
+                acc[t] = __builtin_amdgcn_sdot4(c1, xw.y, acc[t], false);
+                acc[t] = __builtin_amdgcn_sdot4(c2, xw.z, acc[t], false);
+                acc[t] = __builtin_amdgcn_sdot4(c3, xw.w, acc[t], false);
             }
         }
     }
@@ -158,37 +153,22 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvArgs g) {
     }
     __syncthreads();
 
-    // 5. workgroup partial for (row block, k-slice), offset-code correction included
-    const int t_of = threadIdx.x >> 5, r_of = threadIdx.x & 31;     // threads 0 .. 32*MT-1 finish
-    int part = 0;
-    if (t_of < MT) {
-        part = red[0][t_of][r_of] + red[1][t_of][r_of] + red[2][t_of][r_of] + red[3][t_of][r_of];
-        part -= wsum[t_of][0] + wsum[t_of][1] + wsum[t_of][2] + wsum[t_of][3];
-    }
-    if (g.ksplit > 1) {
-        if (t_of < MT) g.partial[((size_t)blockIdx.x * MT + t_of) * 32 + r_of] = part;
-        __threadfence();
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            const unsigned old = atomicInc(&g.tickets[nb], (unsigned)(g.ksplit - 1));   // wraps back to 0
-            last_flag = (old == (unsigned)(g.ksplit - 1)) ? 1u : 0u;
-        }
-        __syncthreads();
-        if (!last_flag) return;
-        __threadfence();
-        if (t_of < MT) {
-            part = 0;
-            for (int s = 0; s < g.ksplit; ++s)
-                part += g.partial[(((size_t)nb * g.ksplit + s) * MT + t_of) * 32 + r_of];
-        }
-    }
-
-    // 6. rescale
+    // 5. finish: threads 0 .. 32 MT - 1 each own one (token, row)
+    const int t_of = threadIdx.x >> 5, r_of = threadIdx.x & 31;
     if (t_of < MT && t_of < g.M) {
+        int part = 0, sq = 0;
+#pragma unroll
+        for (int w = 0; w < GV_WAVES; ++w) {
+            part += red[w][t_of][r_of];
+            sq += wsum[t_of][w];
+        }
+        part -= sq;
         const int n = nb * 32 + r_of;
         if (n < g.N) {
-            const float m = fmaxf(fmaxf(fmaxf(wmax[t_of][0], wmax[t_of][1]), fmaxf(wmax[t_of][2], wmax[t_of][3])), g.eps_act);
-            const float d = m / 127.0f;
+            float m = wmax[t_of][0];
+#pragma unroll
+            for (int w = 1; w < GV_WAVES; ++w) m = fmaxf(m, wmax[t_of][w]);
+            const float d = fmaxf(m, g.eps_act) / 127.0f;
             const size_t o = (size_t)t_of * g.N + n;
             float val = ((float)part * d) * (*g.beta);
             if (g.residual) val = val + g.residual[o];
@@ -200,35 +180,20 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvArgs g) {
 
 }  // namespace
 
-int gemv_ksplit(int N, int K) {
-    const int nsb = round_up(K, SBK) / SBK;
-    const int nnb = round_up(N, NB) / NB;
-    int ks = (nsb + GV_MAX_SB - 1) / GV_MAX_SB;
-    const int want = (512 + nnb - 1) / nnb;
-    if (want > ks) ks = want;
-    if (ks > nsb) ks = nsb;
-    if (ks < 1) ks = 1;
-    return ks;
-}
-
 int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t* packed, const float* beta,
                 float eps_act, float* y, const float* residual, int8_t* xq_dbg, float* absmax_dbg,
-                int32_t* acc_dbg, const GemvWs& ws, hipStream_t s) {
+                int32_t* acc_dbg, hipStream_t s) {
     GemvArgs g;
     g.x = x; g.x_dtype = x_dtype; g.M = M; g.K = K; g.N = N;
     g.nsb = round_up(K, SBK) / SBK;
-    g.ksplit = gemv_ksplit(N, K);
-    g.sb_per = (g.nsb + g.ksplit - 1) / g.ksplit;
-    if (g.sb_per > GV_MAX_SB) {
-        set_error("gemv: k-slice of %d super-blocks exceeds %d", g.sb_per, GV_MAX_SB);
+    if (g.nsb > GV_MAX_SB) {
+        set_error("gemv: K = %d exceeds the supported %d", K, MAX_K);
         return BRL_EINVAL;
     }
     g.packed = reinterpret_cast<const uint4*>(packed);
     g.beta = beta; g.eps_act = eps_act; g.y = y; g.residual = residual;
     g.xq_dbg = xq_dbg; g.absmax_dbg = absmax_dbg; g.acc_dbg = acc_dbg;
-    g.partial = ws.partial; g.tickets = ws.tickets;
-    const int nnb = round_up(N, NB) / NB;
-    const int grid = nnb * g.ksplit;
+    const int grid = round_up(N, NB) / NB;
     LaunchTimer tm(BRL_KC_GEMV, s);
     switch (M) {
         case 1: hipLaunchKernelGGL(gemv_kernel<1>, dim3(grid), dim3(GV_THREADS), 0, s, g); break;

@@ -24,16 +24,14 @@ def device_bytes(n: int) -> torch.Tensor:
 
 
 class Workspace:
-    """A caller-owned scratch buffer, initialised once as the ABI requires."""
+    """A caller-owned scratch buffer (no state is kept in it between calls)."""
 
     def __init__(self, nbytes: int):
         self.buf = device_bytes(nbytes)
-        B.brl_workspace_init(self.buf)
 
     def ensure(self, nbytes: int) -> "Workspace":
         if self.buf.numel() < nbytes:
             self.buf = device_bytes(nbytes)
-            B.brl_workspace_init(self.buf)
         return self
 
 
