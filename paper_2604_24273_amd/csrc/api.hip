@@ -140,7 +140,7 @@ FfnWs ffn_ws_layout(int M, int d, int f) {
     L.xf_off = 0;
     L.act1_off = round_up_sz((size_t)M * d * 4, ALIGN);
     L.gu_off = L.act1_off + actbuf_bytes(M, d);
-    L.act2_off = L.gu_off + round_up_sz((size_t)M * 2 * f * 4, ALIGN);
+    L.act2_off = L.gu_off + round_up_sz((size_t)M * f * 4, ALIGN);
     L.total = L.act2_off + actbuf_bytes(M, f);
     return L;
 }
@@ -170,14 +170,15 @@ int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_d
     memset(&gu_w, 0, sizeof(gu_w));
     add_seg(gu_w, w->gate_packed, w->gate_beta, f);
     add_seg(gu_w, w->up_packed, w->up_beta, f);
-    if (int rc = launch_gemm(act1, gu_w, M, 2 * f, d, gu, 2 * f, nullptr, nullptr, s)) return rc;
+    // gate | up GEMM with the squared-ReLU GLU in its epilogue: gu receives h [M, f]
+    if (int rc = launch_gemm(act1, gu_w, M, 2 * f, d, gu, f, nullptr, nullptr, 1, s)) return rc;
     QuantArgs qb;
     memset(&qb, 0, sizeof(qb));
-    qb.x = gu; qb.x_dtype = BRL_F32; qb.gain = w->subln_g; qb.glu = 1;
+    qb.x = gu; qb.x_dtype = BRL_F32; qb.gain = w->subln_g; qb.glu = 0;
     qb.eps_norm = eps_norm; qb.eps_act = eps_act; qb.M = M; qb.K = f;
     if (int rc = launch_act_quant(qb, act2, s)) return rc;
     const WeightSegs dn = one_seg(w->down_packed, w->down_beta, d);
-    return launch_gemm(act2, dn, M, d, f, y, d, x32, nullptr, s);
+    return launch_gemm(act2, dn, M, d, f, y, d, x32, nullptr, 0, s);
 }
 
 struct EncWs {
@@ -203,7 +204,7 @@ EncWs encoder_ws_layout(const brl_encoder* e, int B, int S) {
     L.act_off = round_up_sz(Mt * e->d * 4, ALIGN);
     L.big_off = L.act_off + actbuf_bytes((int)Mt, kmax);
     const size_t attn_cols = (size_t)dq + 2 * dkv + dq;      // qkv | attention output
-    const size_t big_cols = attn_cols > (size_t)2 * e->f ? attn_cols : (size_t)2 * e->f;
+    const size_t big_cols = attn_cols > (size_t)e->f ? attn_cols : (size_t)e->f;
     L.cos_off = L.big_off + round_up_sz(Mt * big_cols * 4, ALIGN);
     const size_t tbl = round_up_sz((size_t)S * (e->head_dim / 2) * 4, ALIGN);
     L.sin_off = L.cos_off + tbl;
@@ -401,7 +402,7 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K, const
     qa.M = M; qa.K = K; qa.xq_rowmajor = xq_dbg; qa.absmax_tap = absmax_dbg;
     if (int rc = launch_act_quant(qa, act, s)) return rc;
     const WeightSegs w = one_seg(packed, beta, N);
-    return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, s);
+    return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, 0, s);
 }
 
 size_t brl_ffn_workspace_bytes(int M, int d, int f) {
@@ -489,7 +490,7 @@ int encoder_forward(const brl_encoder* enc, const int32_t* ids, int B, int S, co
             add_seg(wqkv, w.wq_packed, w.wq_beta, dq);
             add_seg(wqkv, w.wk_packed, w.wk_beta, dkv);
             add_seg(wqkv, w.wv_packed, w.wv_beta, dkv);
-            if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, s)) return rc;
+            if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, 0, s)) return rc;
             if (enc->attn_precision == BRL_ATTN_MFMA) {
                 if (int rc = launch_attention_mfma(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t,
                                                   sin_t, att, s))
@@ -505,7 +506,7 @@ int encoder_forward(const brl_encoder* enc, const int32_t* ids, int B, int S, co
             qo.M = Mt; qo.K = dq;
             if (int rc = launch_act_quant(qo, act, s)) return rc;
             const WeightSegs wo = one_seg(w.wo_packed, w.wo_beta, d);
-            if (int rc = launch_gemm(act, wo, Mt, d, dq, x, d, x, nullptr, s)) return rc;
+            if (int rc = launch_gemm(act, wo, Mt, d, dq, x, d, x, nullptr, 0, s)) return rc;
             if (int rc = run_ffn(&w.ffn, x, x, BRL_F32, Mt, d, f, enc->eps_norm, enc->eps_act, x, act, big, act, s))
                 return rc;
         }

@@ -107,8 +107,9 @@ struct QuantArgs {
 int launch_act_quant(const QuantArgs& a, const ActBuf& out, hipStream_t s);
 
 // int8 MFMA GEMM with fused dequant epilogue
+// glu = 1: w holds (gate, up); y [M, N/2] receives (max(G,0) * max(G,0)) * U
 int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K,
-                float* y, int ldy, const float* residual, int32_t* acc_dbg, hipStream_t s);
+                float* y, int ldy, const float* residual, int32_t* acc_dbg, int glu, hipStream_t s);
 
 // bandwidth-bound GEMV (M <= 4), activation quantisation fused
 int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t* packed, const float* beta,

@@ -45,6 +45,8 @@ struct GemmArgs {
     const float* residual;
     int32_t* acc_dbg;
     int fast_epilogue;       // every segment a multiple of 32 rows, ldy % 4 == 0, no debug tap
+    int glu;                 // 1: segments are (gate, up) of equal size, interleaved block by block;
+                             //    the epilogue emits h = (max(G,0) * max(G,0)) * U, one column per pair
 };
 
 __device__ inline v4i expand_codes(uint32_t p) {
@@ -83,31 +85,16 @@ __device__ inline bool tile_of_block(const GemmArgs& g, int& tile_m, int& tile_n
     return true;
 }
 
-// Where the TN weight blocks of a wavefront live: segment, packed pointer, output columns.
-template <int TN>
-struct BCols {
-    const uint4* ptr[TN];
-    int seg[TN], col0[TN], ncols[TN];
-    __device__ inline void init(const GemmArgs& g, int nb0, int lane) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int gnb = min(nb0 + j, g.nnb - 1);      // clamped blocks are computed but never stored
-            int s = 0;
-            if (g.nseg > 1 && gnb >= g.nb_end[0]) s = 1;
-            if (g.nseg > 2 && gnb >= g.nb_end[1]) s = 2;
-            const int nb_begin = s == 0 ? 0 : g.nb_end[s - 1];
-            const int n_begin = s == 0 ? 0 : g.n_end[s - 1];
-            const int lnb = gnb - nb_begin;
-            seg[j] = s;
-            col0[j] = n_begin + lnb * 32;
-            ncols[j] = (nb0 + j < g.nnb) ? min(32, g.n_end[s] - col0[j]) : 0;
-            ptr[j] = g.wp[s] + (size_t)lnb * g.nsb * 64 + lane;
-        }
-    }
-};
-
-// Output column and scale of global weight block gnb (runtime lookup, edge path only).
+// Segment, first output column and number of valid columns of global weight block gnb.
+// In GLU mode block 2 n is gate block n and block 2 n + 1 is up block n; both map to
+// output columns 32 n ...
 __device__ inline void block_columns(const GemmArgs& g, int gnb, int& seg, int& col0, int& ncols) {
+    if (g.glu) {
+        seg = gnb & 1;
+        col0 = (gnb >> 1) * 32;
+        ncols = gnb < g.nnb ? min(32, g.n_end[0] - col0) : 0;
+        return;
+    }
     int s = 0;
     if (g.nseg > 1 && gnb >= g.nb_end[0]) s = 1;
     if (g.nseg > 2 && gnb >= g.nb_end[1]) s = 2;
@@ -117,6 +104,26 @@ __device__ inline void block_columns(const GemmArgs& g, int gnb, int& seg, int& 
     col0 = n_begin + (gnb - nb_begin) * 32;
     ncols = gnb < g.nnb ? min(32, g.n_end[s] - col0) : 0;
 }
+
+// Where the TN weight blocks of a wavefront live: segment, packed pointer, output columns.
+template <int TN>
+struct BCols {
+    const uint4* ptr[TN];
+    int seg[TN], col0[TN], ncols[TN];
+    __device__ inline void init(const GemmArgs& g, int nb0, int lane) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int gnb = min(nb0 + j, g.nnb - 1);      // clamped blocks are computed but never stored
+            int s, c0, nc;
+            block_columns(g, gnb, s, c0, nc);
+            const int lnb = g.glu ? (gnb >> 1) : gnb - (s == 0 ? 0 : g.nb_end[s - 1]);
+            seg[j] = s;
+            col0[j] = c0;
+            ncols[j] = (nb0 + j < g.nnb) ? nc : 0;
+            ptr[j] = g.wp[s] + (size_t)lnb * g.nsb * 64 + lane;
+        }
+    }
+};
 
 // Epilogue.  In a 32x32 accumulator tile a lane holds column (lane & 31) and rows
 // 8*(v/4) + 4*(lane/32) + v%4.  Each half token block of the wavefront (16 rows x
@@ -160,7 +167,36 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
                 for (int v = 0; v < 8; ++v)
                     scr[(8 * (v >> 2) + rh + (v & 3)) * LD + j * 32 + cl] = acc[i][j][half * 8 + v];
             __builtin_amdgcn_wave_barrier();
-            if (interior) {
+            if (interior && g.glu) {
+                if constexpr (TN % 2 == 0) {
+                    constexpr int LPRG = (TN / 2) * 8, RPPG = 64 / LPRG;
+                    const int cg = lane % LPRG, rg = lane / LPRG;
+                    const int jj = cg >> 3, cc = 4 * (cg & 7);
+                    float bg = beta[0], bu = beta[1];
+#pragma unroll
+                    for (int q = 1; q < TN / 2; ++q)
+                        if (jj == q) { bg = beta[2 * q]; bu = beta[2 * q + 1]; }
+#pragma unroll
+                    for (int p = 0; p < 16 / RPPG; ++p) {
+                        const int row = p * RPPG + rg;
+                        const int4 ga = *reinterpret_cast<const int4*>(&scr[row * LD + (2 * jj) * 32 + cc]);
+                        const int4 ua = *reinterpret_cast<const int4*>(&scr[row * LD + (2 * jj + 1) * 32 + cc]);
+                        const float d = g.dscale[mbase + row];
+                        const int sq = g.sumq[mbase + row];
+                        const size_t o = (size_t)(mbase + row) * g.ldy + (nb0 / 2 + jj) * 32 + cc;
+                        const int gi[4] = {ga.x, ga.y, ga.z, ga.w}, ui[4] = {ua.x, ua.y, ua.z, ua.w};
+                        float hv[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float G = ((float)(gi[q] - sq) * d) * bg;
+                            const float U = ((float)(ui[q] - sq) * d) * bu;
+                            const float pz = fmaxf(G, 0.f);
+                            hv[q] = (pz * pz) * U;
+                        }
+                        *reinterpret_cast<float4*>(g.y + o) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+                    }
+                }
+            } else if (interior) {
                 const int col_base = nb0 * 32 + 4 * c4;
 #pragma unroll
                 for (int p = 0; p < TN * 2; ++p) {
@@ -179,6 +215,23 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
                         val.x = val.x + r.x; val.y = val.y + r.y; val.z = val.z + r.z; val.w = val.w + r.w;
                     }
                     *reinterpret_cast<float4*>(g.y + o) = val;
+                }
+            } else if (g.glu) {
+#pragma unroll 1
+                for (int e = lane; e < 16 * (W / 2); e += 64) {
+                    const int row = e / (W / 2), c = e % (W / 2);
+                    const int m = mbase + row;
+                    const int jj = c >> 5, cc = c & 31;
+                    int seg, col0, ncols;
+                    block_columns(g, nb0 + 2 * jj, seg, col0, ncols);
+                    if (m < g.M && cc < ncols) {
+                        const int sq = g.sumq[m];
+                        const float d = g.dscale[m];
+                        const float G = ((float)(scr[row * LD + (2 * jj) * 32 + cc] - sq) * d) * (*g.beta[0]);
+                        const float U = ((float)(scr[row * LD + (2 * jj + 1) * 32 + cc] - sq) * d) * (*g.beta[1]);
+                        const float pz = fmaxf(G, 0.f);
+                        g.y[(size_t)m * g.ldy + col0 + cc] = (pz * pz) * U;
+                    }
                 }
             } else {
 #pragma unroll 1
@@ -467,7 +520,7 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
 }  // namespace
 
 int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float* y, int ldy,
-                const float* residual, int32_t* acc_dbg, hipStream_t s) {
+                const float* residual, int32_t* acc_dbg, int glu, hipStream_t s) {
     GemmArgs g;
     g.A = reinterpret_cast<const uint4*>(a.q);
     g.dscale = a.dscale;
@@ -482,6 +535,14 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     g.M = M;
     g.nmb = round_up(M, NB) / NB;
     g.nnb = w.nb_end[w.count - 1];
+    g.glu = glu;
+    if (glu) {
+        if (w.count != 2 || w.n_end[1] != 2 * w.n_end[0] || residual || acc_dbg) {
+            set_error("gemm: GLU mode needs two equal segments, no residual, no tap");
+            return BRL_EINVAL;
+        }
+        g.nnb = 2 * w.nb_end[0];
+    }
     g.nsb = round_up(K, SBK) / SBK;
     g.y = y;
     g.ldy = ldy;
@@ -493,9 +554,14 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     (void)N;
     // Tile choice: k-split wavefronts for skinny (few-token) problems, where weight
     // streaming bounds the time; LDS-staged big tiles once the grid fills the chip.
-    if (g.nmb <= 1) return launch_direct<1, 1, 1, 1, 4>(g, s);
-    if (g.nmb <= 2) return launch_direct<2, 1, 1, 1, 4>(g, s);
-    if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
+    if (glu) {   // a wavefront needs the gate and the up block of a column pair: even TN only
+        if (g.nmb <= 1) return launch_direct<1, 2, 1, 1, 4>(g, s);
+        if (g.nmb <= 2) return launch_direct<2, 2, 1, 1, 4>(g, s);
+    } else {
+        if (g.nmb <= 1) return launch_direct<1, 1, 1, 1, 4>(g, s);
+        if (g.nmb <= 2) return launch_direct<2, 1, 1, 1, 4>(g, s);
+        if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
+    }
     static const char* force = getenv("BRL_GEMM_TILE");
     if (force) {
         if (force[0] == 'a') return launch_lds<4, 4, 2, 2>(g, s);

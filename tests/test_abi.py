@@ -53,7 +53,7 @@ def test_size_queries(B):
     assert B.brl_packed_bytes(0, 5) == 0
     assert B.brl_bitlinear_workspace_bytes(1, 6912, 2560) > 0
     assert B.brl_bitlinear_workspace_bytes(256, 6912, 2560) >= 256 * 2560
-    assert B.brl_ffn_workspace_bytes(256, 2560, 6912) >= 256 * 2 * 6912 * 4
+    assert B.brl_ffn_workspace_bytes(256, 2560, 6912) >= 256 * 6912 * 4
     assert B.brl_quantize_workspace_bytes(10, 10) >= 8192
 
 
