@@ -1,27 +1,32 @@
-// Per-token absmax int8 activation quantisation, with the producers that sit in
-// front of it in the blocks fused in: RMSNorm / sub-layer norm, and the
-// squared-ReLU GLU.  One wavefront owns one token row and keeps it in
-// registers, so the row is read from HBM once: statistic, absmax and the
-// quantised store all come from the same registers.
+// Per-token absmax int8 activation quantisation, with the RMSNorm / sub-layer
+// norm that sits in front of it in the blocks fused in.  One wavefront owns one
+// token row and keeps it in registers, so the row is read from HBM once:
+// statistic, absmax and the quantised values all come from the same registers.
 //
-//   (GLU)   h_k = (max(g_k,0) * max(g_k,0)) * u_k
 //   (norm)  r = fp32(1 / sqrt(mean_k x_k^2 + eps_n))  [fp64 statistic];  x_k <- (x_k * r) * gain_k
 //   a = max(max_k |x_k|, eps);  s = 127 / a;  q_k = clamp(rne(x_k * s), -127, 127)
 //
 // Output goes to the tiled int8 layout the MFMA GEMM reads (see common.hpp),
-// plus per-token a, a / 127 and sum_k q_k.
+// plus per-token a, a / 127 and sum_k q_k.  In that layout 16 consecutive k of
+// one token are 16 bytes, and the same 16 k of the next token follow directly:
+// a workgroup therefore takes 8 consecutive tokens, parks their int8 rows in
+// LDS and writes the tile out in full 128-byte runs.  Two wavefronts share a token
+// (half a row of registers each) and meet through LDS for the three reductions.
 #include "common.hpp"
 
 namespace brl {
 
 namespace {
 
+constexpr int AQ_ROWS = 8;                 // tokens per workgroup
+constexpr int AQ_THREADS = AQ_ROWS * 128;  // two wavefronts per token: each keeps half of the row in registers
+
 struct QK {
     const void* x;
     const float* gain;
-    int x_dtype, glu;
+    int x_dtype;
     float eps_norm, eps_act;
-    int M, Mp, K, Kp, nsb;
+    int M, K, Kp, nsb;
     int8_t* q_tiled;
     float* absmax;
     float* dscale;
@@ -32,36 +37,30 @@ struct QK {
 
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-template <int MAXV4>
-__global__ __launch_bounds__(256) void act_quant_kernel(QK a) {
-    // Workgroups with the same (blockIdx & 7) tend to share an XCD and its L2: give
-    // the 8 workgroups that fill one 32-token block the same residue so that their
-    // 16-byte pieces of each output line meet in one L2.
-    const int w = blockIdx.x;
-    const int xcd = w & 7, t = w >> 3;
-    const int part = t & 7, mb = (t >> 3) * 8 + xcd;
+// HV4: float4 chunks per lane; the two wavefronts of a token interleave their chunks
+// (chunk c = 2 i + half covers k = 4 (lane + 64 c) .. + 3), so every load stays coalesced.
+template <int HV4>
+__global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // AQ_ROWS x (Kp + 16) bytes
+    __shared__ double red_ss[AQ_ROWS][2];
+    __shared__ float red_max[AQ_ROWS][2];
+    __shared__ int red_sum[AQ_ROWS][2];
+
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int row = mb * 32 + part * 4 + wave;
-    if (row >= a.Mp) return;
+    const int rl = wave >> 1, half = wave & 1;
+    const int row0 = blockIdx.x * AQ_ROWS;
+    const int row = row0 + rl;
     const int K = a.K;
     const bool live = row < a.M;
+    const int stride = a.Kp + 16;          // the 16-byte skew keeps the 8 rows on different LDS banks
 
-    float4 v[MAXV4];
+    float4 v[HV4];
 #pragma unroll
-    for (int i = 0; i < MAXV4; ++i) {
-        const int k = 4 * (lane + 64 * i);
+    for (int i = 0; i < HV4; ++i) {
+        const int k = 4 * (lane + 64 * (2 * i + half));
         float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
         if (live && k < K) {
-            if (a.glu) {
-                const float* base = reinterpret_cast<const float*>(a.x) + (size_t)row * (2 * (size_t)K);
-                const float4 g = *reinterpret_cast<const float4*>(base + k);
-                const float4 u = *reinterpret_cast<const float4*>(base + K + k);
-                float p;
-                p = fmaxf(g.x, 0.f); e.x = (p * p) * u.x;
-                p = fmaxf(g.y, 0.f); e.y = (p * p) * u.y;
-                p = fmaxf(g.z, 0.f); e.z = (p * p) * u.z;
-                p = fmaxf(g.w, 0.f); e.w = (p * p) * u.w;
-            } else if (a.x_dtype == BRL_BF16) {
+            if (a.x_dtype == BRL_BF16) {
                 const uint16_t* base = reinterpret_cast<const uint16_t*>(a.x) + (size_t)row * K;
                 const uint2 raw = *reinterpret_cast<const uint2*>(base + k);
                 e.x = bf16_to_f32((uint16_t)(raw.x & 0xffffu));
@@ -79,7 +78,7 @@ __global__ __launch_bounds__(256) void act_quant_kernel(QK a) {
     if (a.gain) {
         double ss = 0.0;
 #pragma unroll
-        for (int i = 0; i < MAXV4; ++i) {
+        for (int i = 0; i < HV4; ++i) {
             ss += (double)v[i].x * (double)v[i].x;
             ss += (double)v[i].y * (double)v[i].y;
             ss += (double)v[i].z * (double)v[i].z;
@@ -87,11 +86,13 @@ __global__ __launch_bounds__(256) void act_quant_kernel(QK a) {
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
-        const double ms = ss / (double)K;
+        if (lane == 0) red_ss[rl][half] = ss;
+        __syncthreads();
+        const double ms = (red_ss[rl][0] + red_ss[rl][1]) / (double)K;
         const float r = (float)(1.0 / sqrt(ms + (double)a.eps_norm));
 #pragma unroll
-        for (int i = 0; i < MAXV4; ++i) {
-            const int k = 4 * (lane + 64 * i);
+        for (int i = 0; i < HV4; ++i) {
+            const int k = 4 * (lane + 64 * (2 * i + half));
             if (k < K) {
                 const float4 g = *reinterpret_cast<const float4*>(a.gain + k);
                 v[i].x = (v[i].x * r) * g.x;
@@ -104,18 +105,21 @@ __global__ __launch_bounds__(256) void act_quant_kernel(QK a) {
 
     float amax = 0.f;
 #pragma unroll
-    for (int i = 0; i < MAXV4; ++i) {
+    for (int i = 0; i < HV4; ++i) {
         amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[i].x), fabsf(v[i].y)), fmaxf(fabsf(v[i].z), fabsf(v[i].w))));
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-    const float ac = fmaxf(amax, a.eps_act);
+    if (lane == 0) red_max[rl][half] = amax;
+    __syncthreads();
+    const float ac = fmaxf(fmaxf(red_max[rl][0], red_max[rl][1]), a.eps_act);
     const float s = 127.0f / ac;
 
     int sum = 0;
+    uint32_t* myrow = reinterpret_cast<uint32_t*>(rowbuf + (size_t)rl * stride);
 #pragma unroll
-    for (int i = 0; i < MAXV4; ++i) {
-        const int k = 4 * (lane + 64 * i);
+    for (int i = 0; i < HV4; ++i) {
+        const int k = 4 * (lane + 64 * (2 * i + half));
         if (k < a.Kp) {
             int q0 = (int)fminf(fmaxf(rintf(v[i].x * s), -127.f), 127.f);
             int q1 = (int)fminf(fmaxf(rintf(v[i].y * s), -127.f), 127.f);
@@ -124,19 +128,31 @@ __global__ __launch_bounds__(256) void act_quant_kernel(QK a) {
             sum += q0 + q1 + q2 + q3;
             const uint32_t word = (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) | ((uint32_t)(q2 & 0xff) << 16) |
                                   ((uint32_t)(q3 & 0xff) << 24);
-            *reinterpret_cast<uint32_t*>(a.q_tiled + tiled_act_offset(row, k, a.nsb)) = word;
-            if (a.xq_rowmajor && live && k < K) {
-                *reinterpret_cast<uint32_t*>(a.xq_rowmajor + (size_t)row * K + k) = word;
-            }
+            myrow[k >> 2] = word;
+            if (a.xq_rowmajor && live && k < K) *reinterpret_cast<uint32_t*>(a.xq_rowmajor + (size_t)row * K + k) = word;
         }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
-    if (lane == 0) {
+    if (lane == 0) red_sum[rl][half] = sum;
+    __syncthreads();
+    if (lane == 0 && half == 0 && live) {
         a.absmax[row] = ac;
         a.dscale[row] = ac / 127.0f;
-        a.sumq[row] = sum;
-        if (a.absmax_tap && live) a.absmax_tap[row] = ac;
+        a.sumq[row] = red_sum[rl][0] + red_sum[rl][1];
+        if (a.absmax_tap) a.absmax_tap[row] = ac;
+    }
+
+    // tiled write-out: thread (token t8, chunk kc) moves the 16 bytes of k = 16 kc .. 16 kc + 15;
+    // the 8 tokens of one chunk are 128 contiguous bytes of the tile
+    const int t8 = threadIdx.x & 7;
+    const int mb = row0 >> 5, r0 = row0 & 31;
+    const int nchunks = a.Kp >> 4;
+    for (int kc = threadIdx.x >> 3; kc < nchunks; kc += AQ_THREADS / 8) {
+        const uint4 val = *reinterpret_cast<const uint4*>(rowbuf + (size_t)t8 * stride + 16 * kc);
+        const int sb = kc >> 3, dd = (kc >> 1) & 3, hh = kc & 1;
+        const size_t off = ((((size_t)mb * a.nsb + sb) * 4 + dd) * 64 + (hh * 32 + r0 + t8)) * 16;
+        *reinterpret_cast<uint4*>(a.q_tiled + off) = val;
     }
 }
 
@@ -144,23 +160,29 @@ __global__ __launch_bounds__(256) void act_quant_kernel(QK a) {
 
 int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     QK a;
-    a.x = in.x; a.gain = in.gain; a.x_dtype = in.x_dtype; a.glu = in.glu;
+    a.x = in.x; a.gain = in.gain; a.x_dtype = in.x_dtype;
     a.eps_norm = in.eps_norm; a.eps_act = in.eps_act;
-    a.M = in.M; a.Mp = round_up(in.M, NB); a.K = in.K; a.Kp = round_up(in.K, SBK); a.nsb = a.Kp / SBK;
+    a.M = in.M; a.K = in.K; a.Kp = round_up(in.K, SBK); a.nsb = a.Kp / SBK;
     a.q_tiled = out.q; a.absmax = out.absmax; a.dscale = out.dscale; a.sumq = out.sumq;
     a.xq_rowmajor = in.xq_rowmajor; a.absmax_tap = in.absmax_tap;
-    const int nmb = a.Mp / NB;
-    const int grid = ((nmb + 7) / 8) * 64;
-    const int v4 = a.Kp / 256 + ((a.Kp % 256) ? 1 : 0);
+    const int grid = (in.M + AQ_ROWS - 1) / AQ_ROWS;
+    const size_t lds = (size_t)AQ_ROWS * (a.Kp + 16);
+    const int hv4 = (a.Kp + 511) / 512;      // float4 chunks per lane of each of the two wavefronts
     LaunchTimer tm(BRL_KC_ACT_QUANT, s);
-    if (v4 <= 4) {
-        hipLaunchKernelGGL(act_quant_kernel<4>, dim3(grid), dim3(256), 0, s, a);
-    } else if (v4 <= 12) {
-        hipLaunchKernelGGL(act_quant_kernel<12>, dim3(grid), dim3(256), 0, s, a);
-    } else if (v4 <= 28) {
-        hipLaunchKernelGGL(act_quant_kernel<28>, dim3(grid), dim3(256), 0, s, a);
-    } else if (v4 <= 36) {
-        hipLaunchKernelGGL(act_quant_kernel<36>, dim3(grid), dim3(256), 0, s, a);
+    if (hv4 <= 2) {
+        hipLaunchKernelGGL(act_quant_kernel<2>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    } else if (hv4 <= 6) {
+        hipLaunchKernelGGL(act_quant_kernel<6>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    } else if (hv4 <= 14) {
+        hipLaunchKernelGGL(act_quant_kernel<14>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    } else if (hv4 <= 18) {
+        static bool raised = false;     // this instantiation needs more than the default 64 KB of dynamic LDS
+        if (!raised) {
+            BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<18>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, AQ_ROWS * (MAX_K + 16)));
+            raised = true;
+        }
+        hipLaunchKernelGGL(act_quant_kernel<18>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
     } else {
         set_error("act_quant: K = %d exceeds the supported %d", in.K, MAX_K);
         return BRL_EINVAL;

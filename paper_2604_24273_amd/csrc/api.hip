@@ -163,7 +163,7 @@ int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_d
             float eps_norm, float eps_act, float* y, const ActBuf& act1, float* gu, const ActBuf& act2, hipStream_t s) {
     QuantArgs qa;
     memset(&qa, 0, sizeof(qa));
-    qa.x = xin; qa.x_dtype = x_dtype; qa.gain = w->norm_g; qa.glu = 0;
+    qa.x = xin; qa.x_dtype = x_dtype; qa.gain = w->norm_g;
     qa.eps_norm = eps_norm; qa.eps_act = eps_act; qa.M = M; qa.K = d;
     if (int rc = launch_act_quant(qa, act1, s)) return rc;
     WeightSegs gu_w;
@@ -174,7 +174,7 @@ int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_d
     if (int rc = launch_gemm(act1, gu_w, M, 2 * f, d, gu, f, nullptr, nullptr, 1, s)) return rc;
     QuantArgs qb;
     memset(&qb, 0, sizeof(qb));
-    qb.x = gu; qb.x_dtype = BRL_F32; qb.gain = w->subln_g; qb.glu = 0;
+    qb.x = gu; qb.x_dtype = BRL_F32; qb.gain = w->subln_g;
     qb.eps_norm = eps_norm; qb.eps_act = eps_act; qb.M = M; qb.K = f;
     if (int rc = launch_act_quant(qb, act2, s)) return rc;
     const WeightSegs dn = one_seg(w->down_packed, w->down_beta, d);
@@ -398,7 +398,7 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K, const
     const ActBuf act = take_actbuf(c, M, K);
     QuantArgs qa;
     memset(&qa, 0, sizeof(qa));
-    qa.x = x; qa.x_dtype = x_dtype; qa.gain = nullptr; qa.glu = 0; qa.eps_norm = 0.f; qa.eps_act = eps_act;
+    qa.x = x; qa.x_dtype = x_dtype; qa.gain = nullptr; qa.eps_norm = 0.f; qa.eps_act = eps_act;
     qa.M = M; qa.K = K; qa.xq_rowmajor = xq_dbg; qa.absmax_tap = absmax_dbg;
     if (int rc = launch_act_quant(qa, act, s)) return rc;
     const WeightSegs w = one_seg(packed, beta, N);

@@ -93,12 +93,11 @@ int launch_quantize_weights(const float* W, int N, int K, float eps, uint32_t* p
 int launch_unpack_codes(const uint32_t* packed, int N, int K, int8_t* codes, hipStream_t s);
 int quantize_partials_count(int N, int K);
 
-// activation quantisation (mode: plain / RMSNorm / GLU + RMSNorm)
+// activation quantisation (plain, or RMSNorm first)
 struct QuantArgs {
-    const void* x;          // [M, K] fp32 or bf16; for GLU: [M, 2K] fp32 (gate | up)
+    const void* x;          // [M, K] fp32 or bf16
     int x_dtype;
     const float* gain;      // RMSNorm gain [K] or nullptr (no norm)
-    int glu;                // 1: h = sqrelu(x[:, :K]) * x[:, K:] first
     float eps_norm, eps_act;
     int M, K;
     int8_t* xq_rowmajor;    // optional tap [M, K]
