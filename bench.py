@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--no-gemv", action="store_true")
     ap.add_argument("--cpu-sample-states", type=int, default=2)
     ap.add_argument("--gemv-calls", type=int, default=1000)
+    ap.add_argument("--streams", type=int, default=1,
+                    help="extra leg: also time the batch as this many concurrent micro-batches on separate HIP streams")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -137,6 +139,37 @@ def main() -> int:
                 "avg_launch_ms": round(gemm_avg_ms, 5), "launches_per_step": gemm_launches,
                 "ops_per_launch": ops_per_launch}
 
+    # ---- optional extra leg: the same batch as concurrent micro-batches on separate streams
+    concurrent = None
+    if args.streams > 1:
+        parts = [p.contiguous() for p in torch.chunk(ids, args.streams, dim=0)]
+        wss = [R.Workspace(B.brl_encoder_workspace_bytes(enc.struct, p.shape[0], S)) for p in parts]
+        h_all = torch.empty((Bn, shape.d), dtype=torch.float32, device="cuda")
+        hs = list(torch.split(h_all, [p.shape[0] for p in parts], dim=0))     # contiguous row slices
+        sts = [torch.cuda.Stream() for _ in parts]
+
+        def cstep():
+            main = torch.cuda.current_stream()
+            for p, w, hh, st in zip(parts, wss, hs, sts):
+                st.wait_stream(main)
+                with torch.cuda.stream(st):
+                    B.encoder_forward(enc.struct, p, p.shape[0], S, None, hh, w.buf)
+            for st in sts:
+                main.wait_stream(st)
+            return head.forward(h_all)
+
+        for _ in range(args.warmup):
+            cstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            cstep()
+        torch.cuda.synchronize()
+        cms = (time.perf_counter() - t0) / args.steps * 1e3
+        same = bool(torch.equal(h_all, enc.forward(ids)))
+        concurrent = {"streams": args.streams, "ms_per_step": round(cms, 4), "states_per_s": round(Bn / cms * 1e3, 1),
+                      "bit_identical_to_single_call": same}
+
     # ---- 1-token GEMV pair (decode shape), 1000 calls
     gemv = None
     if not args.no_gemv:
@@ -186,6 +219,7 @@ def main() -> int:
         "linear_tops_wall": round(ops_step / (ms_per_step * 1e-3) / 1e12, 2),
         "int8_ceiling_states_per_s": round(Bn / (ops_step / (INT8_MFMA_PEAK_TOPS * 1e12)), 1),
         "gemv_pair": gemv,
+        "concurrent_microbatches": concurrent,
         "paper_context": {"hardware": "Raspberry Pi 4 (Cortex-A72 @ 1.5 GHz), bitnet.cpp", "steps_per_s": 40.3,
                           "median_latency_ms": 24.8, "note": "one 15-40 token state per step; context only"},
         "setup_seconds": round(setup_s, 1),

@@ -223,7 +223,7 @@ __device__ inline void rope_store(_Float16* dst_hi, _Float16* dst_lo, const floa
 }
 
 template <int DHP>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a, int dh) {
+__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a, int dh) {
     constexpr int KS = DHP / 16;          // k-steps of the score MFMAs
     constexpr int DB = DHP / 32;          // 32-row blocks of O^T
     constexpr int KLD = DHP + 8;          // halfs per K row (padding spreads the 16-byte reads over banks)

@@ -562,15 +562,6 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
         if (g.nmb <= 2) return launch_direct<2, 1, 1, 1, 4>(g, s);
         if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
     }
-    static const char* force = getenv("BRL_GEMM_TILE");
-    if (force) {
-        if (force[0] == 'a') return launch_lds<4, 4, 2, 2>(g, s);
-        if (force[0] == 'c') return launch_lds<2, 2, 2, 2>(g, s);
-        if (force[0] == 'e') return launch_lds<2, 4, 4, 2>(g, s);
-        if (force[0] == 'f') return launch_lds<4, 2, 2, 4>(g, s);
-        if (force[0] == 'g') return launch_lds<2, 2, 4, 2>(g, s);
-        if (force[0] == 'h') return launch_lds<2, 2, 2, 4>(g, s);
-    }
     // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64) once they fill the chip twice over,
     // else 128 x 128 tiles (4 wavefronts)
     const long t_wide = (long)((g.nmb + 3) / 4) * ((g.nnb + 7) / 8);
