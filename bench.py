@@ -43,8 +43,11 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--states", type=int, default=64)
-    ap.add_argument("--tokens", type=int, default=128)
+    ap.add_argument("--workload", choices=["encoder-2b", "prefill-3b"], default="encoder-2b",
+                    help="encoder-2b: 64 states x 128 tokens at the 2B shape (the headline); "
+                         "prefill-3b: 1024 states x 512 tokens at the 3B shape (large-batch regime)")
+    ap.add_argument("--states", type=int, default=None)
+    ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="debug only: fewer layers (invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemv", action="store_true")
@@ -72,9 +75,10 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
 
-    shape = synth.SHAPE_2B
+    shape = synth.SHAPE_2B if args.workload == "encoder-2b" else synth.SHAPE_3B
     n_layers = shape.n_layers if args.layers is None else args.layers
-    Bn, S = args.states, args.tokens
+    Bn = args.states if args.states is not None else (64 if args.workload == "encoder-2b" else 1024)
+    S = args.tokens if args.tokens is not None else (128 if args.workload == "encoder-2b" else 512)
     want_cpu = not args.no_cpu_baseline
 
     # ---- weights: seeded host draws -> packed on the GPU; the oracle's copy is quantised on the side
@@ -205,13 +209,15 @@ def main() -> int:
                "seconds": round(cpu_s, 2), "min_cosine_gpu_vs_oracle": round(min(cosines), 6)}
 
     out = {
-        "metric": "encoded RL states/sec at 2B shape (BitLinear int8 TOPS as % of roofline alongside)",
+        "metric": "encoded RL states/sec at %s shape (BitLinear int8 TOPS as %% of roofline alongside)"
+                  % ("2B" if args.workload == "encoder-2b" else "3B"),
         "value": round(states_per_s, 2), "unit": "states/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (ternary x int8 -> int32, fp32 rescale)", "data": "synthetic",
-        "config": {"workload": "frozen 2B-shape ternary encoder + fp32 heads: %d layers, hidden %d, %d/%d heads, FFN %d, "
+        "config": {"workload": "frozen %s-shape ternary encoder + fp32 heads: %d layers, hidden %d, %d/%d heads, FFN %d, "
                                "vocab %d; batch %d states x %d tokens, seed 0"
-                               % (n_layers, shape.d, shape.n_heads, shape.n_kv_heads, shape.f, shape.vocab, Bn, S),
+                               % ("2B" if args.workload == "encoder-2b" else "3B", n_layers, shape.d, shape.n_heads,
+                                  shape.n_kv_heads, shape.f, shape.vocab, Bn, S),
                    "states": Bn, "tokens_per_state": S, "int8_ops_per_step": ops_step},
         "roofline": roofline,
         "cpu_baseline": cpu,

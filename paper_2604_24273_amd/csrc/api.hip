@@ -183,7 +183,7 @@ int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_d
 
 struct EncWs {
     int states_mb;      // states per micro-batch
-    size_t x_off, act_off, big_off, cos_off, sin_off, rinv_off, total;
+    size_t x_off, act_off, big_off, cos_off, sin_off, rinv_off, frag_off, total;
     int big_ld_qkv;
 };
 
@@ -209,7 +209,8 @@ EncWs encoder_ws_layout(const brl_encoder* e, int B, int S) {
     const size_t tbl = round_up_sz((size_t)S * (e->head_dim / 2) * 4, ALIGN);
     L.sin_off = L.cos_off + tbl;
     L.rinv_off = L.sin_off + tbl;
-    L.total = L.rinv_off + round_up_sz(Mt * 4, ALIGN);
+    L.frag_off = L.rinv_off + round_up_sz(Mt * 4, ALIGN);
+    L.total = L.frag_off + round_up_sz(attention_mfma_ws_bytes(smb, S, e->n_heads, e->n_kv_heads, e->head_dim), ALIGN);
     L.big_ld_qkv = dq + 2 * dkv;
     return L;
 }
@@ -493,7 +494,7 @@ int encoder_forward(const brl_encoder* enc, const int32_t* ids, int B, int S, co
             if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, 0, s)) return rc;
             if (enc->attn_precision == BRL_ATTN_MFMA) {
                 if (int rc = launch_attention_mfma(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t,
-                                                  sin_t, att, s))
+                                                   sin_t, base + L.frag_off, att, s))
                     return rc;
             } else {
                 if (int rc = launch_attention_f32(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t,

@@ -119,8 +119,9 @@ int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t*
 int launch_rope_table(float* cos_t, float* sin_t, int S, int head_dim, float theta, hipStream_t s);
 int launch_attention_f32(const float* qkv, int ld, int B, int S, int n_heads, int n_kv_heads, int head_dim,
                          const float* cos_t, const float* sin_t, float* out, hipStream_t s);
+size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim);
 int launch_attention_mfma(const float* qkv, int ld, int B, int S, int n_heads, int n_kv_heads, int head_dim,
-                         const float* cos_t, const float* sin_t, float* out, hipStream_t s);
+                          const float* cos_t, const float* sin_t, void* frag_ws, float* out, hipStream_t s);
 int launch_embed(const uint16_t* table, const int32_t* ids, int M, int d, int vocab, float* x, hipStream_t s);
 int launch_final_pool(const float* x, const float* gain, int B, int S, int d, const int32_t* lengths,
                       float eps_norm, float* rinv, float* h, hipStream_t s);
