@@ -134,89 +134,163 @@ struct BCols {
 //     y = (float(acc - sum_q[m]) * dscale[m]) * beta[n] (+ residual)
 // Interior tiles take the unguarded 16-byte path; tiles on the M / N edge (or with
 // debug taps, or unaligned rows) take a compact per-element loop.
-template <int TN>
+template <int TM, int TN>
 struct Epi {
     static constexpr int W = TN * 32, LD = W + 4;
-    static constexpr int REGION = 16 * LD;        // ints of LDS per wavefront
+    static constexpr int ROWS = TM * 32;          // token rows of a wavefront: (dscale, sum_q) pairs parked after the turn area
+    static constexpr int REGION = 16 * LD + 2 * ROWS;   // ints of LDS per wavefront
 };
 
+// accumulator registers half*8 .. half*8+7 of the TN tiles of token block i -> row-major 16 x TN*32 ints in scr
 template <int TM, int TN>
-__device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, const float (&beta)[TN],
-                                int lane, int* scr) {
-    constexpr int W = Epi<TN>::W, LD = Epi<TN>::LD;
-    constexpr int LPR = TN * 8;                  // lanes per row when each lane takes 4 columns
-    constexpr int RPP = 64 / LPR;                // rows per pass
+__device__ inline void scatter_half(v16i (&acc)[TM][TN], int i, int half, int lane, int* scr) {
+    constexpr int LD = Epi<TM, TN>::LD;
     const int cl = lane & 31, rh = (lane >> 5) * 4;
-    const bool interior = g.fast_epilogue && (mb0 + TM) * 32 <= g.M && nb0 + TN <= g.nnb;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 8; ++v) scr[(8 * (v >> 2) + rh + (v & 3)) * LD + j * 32 + cl] = acc[i][j][half * 8 + v];
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The per-token scale and code sum of the wavefront's rows are fetched once (one row per lane)
+// and parked in LDS behind the turn area, so that the passes below wait on LDS only.
+template <int TM, int TN>
+__device__ inline const int2* park_rows(const GemmArgs& g, int mb0, int lane, int* scr) {
+    int2* rows = reinterpret_cast<int2*>(scr + 16 * Epi<TM, TN>::LD);
+#pragma unroll
+    for (int r = lane; r < TM * 32; r += 64) {
+        const int m = min(mb0 * 32 + r, g.M - 1);
+        rows[r] = make_int2(__float_as_int(g.dscale[m]), g.sumq[m]);
+    }
+    return rows;
+}
+
+// h = (max(G,0) * max(G,0)) * U from the gate / up column pairs; 4 columns of one row per lane
+template <int TM, int TN>
+__device__ inline void epilogue_glu(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, const float (&beta)[TN],
+                                    int lane, int* scr) {
+    constexpr int LD = Epi<TM, TN>::LD;
+    constexpr int LPR = (TN / 2) * 8;            // lanes per row
+    constexpr int RPP = 64 / LPR;
+    constexpr int NP = 16 / RPP;                 // passes per half token block
+    static_assert(64 % LPR == 0, "TN / 2 must be a power of two");
+    const int cg = lane % LPR, r0 = lane / LPR;
+    const int jj = cg >> 3, cc = 4 * (cg & 7);
+    int row[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) row[p] = p * RPP + r0;
+    float bg = beta[0], bu = beta[1];
+#pragma unroll
+    for (int q = 1; q < TN / 2; ++q)
+        if (jj == q) { bg = beta[2 * q]; bu = beta[2 * q + 1]; }
+    const int col = (nb0 / 2 + jj) * 32 + cc;
+    const int2* rows = park_rows<TM, TN>(g, mb0, lane, scr);
+#pragma unroll
+    for (int idx = 0; idx < 2 * TM; ++idx) {
+        const int mbase = (mb0 + (idx >> 1)) * 32 + (idx & 1) * 16;
+        scatter_half<TM, TN>(acc, idx >> 1, idx & 1, lane, scr);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int2 rw = rows[idx * 16 + row[p]];
+            const float d = __int_as_float(rw.x);
+            const int sq = rw.y;
+            const int4 ga = *reinterpret_cast<const int4*>(&scr[row[p] * LD + (2 * jj) * 32 + cc]);
+            const int4 ua = *reinterpret_cast<const int4*>(&scr[row[p] * LD + (2 * jj + 1) * 32 + cc]);
+            const int gi[4] = {ga.x, ga.y, ga.z, ga.w}, ui[4] = {ua.x, ua.y, ua.z, ua.w};
+            float hv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float G = ((float)(gi[q] - sq) * d) * bg;
+                const float U = ((float)(ui[q] - sq) * d) * bu;
+                const float pz = fmaxf(G, 0.f);
+                hv[q] = (pz * pz) * U;
+            }
+            *reinterpret_cast<float4*>(g.y + (size_t)(mbase + row[p]) * g.ldy + col) =
+                make_float4(hv[0], hv[1], hv[2], hv[3]);
+        }
+        __builtin_amdgcn_sched_barrier(0);       // keeps the requests of later half blocks from piling up here
+    }
+}
+
+// y = (float(acc - sum_q) * dscale) * beta (+ residual); 4 columns of one row per lane
+template <int TM, int TN, bool RES>
+__device__ inline void epilogue_plain(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0,
+                                      const float (&beta)[TN], int lane, int* scr) {
+    constexpr int LD = Epi<TM, TN>::LD;
+    constexpr int LPR = TN * 8;
+    constexpr int RPP = 64 / LPR;                // rows per pass (TN a power of two)
+    constexpr int NP = 16 / RPP;
+    static_assert(64 % LPR == 0, "TN must be a power of two");
     const int c4 = lane % LPR, r0 = lane / LPR;
+    int row[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) row[p] = p * RPP + r0;
     float my_beta = beta[0];
 #pragma unroll
     for (int j = 1; j < TN; ++j)
         if ((c4 >> 3) == j) my_beta = beta[j];
+    const int col = nb0 * 32 + 4 * c4;
+    const int2* rows = park_rows<TM, TN>(g, mb0, lane, scr);
+#pragma unroll
+    for (int idx = 0; idx < 2 * TM; ++idx) {
+        const int mbase = (mb0 + (idx >> 1)) * 32 + (idx & 1) * 16;
+        // the residual is requested before the LDS turn of this half block and used after it
+        constexpr int NPRE = RES ? NP : 1;
+        float4 res[NPRE];
+        const float* rbase = g.residual + (size_t)mbase * g.ldy + col;
+        if constexpr (RES) {
+#pragma unroll
+            for (int p = 0; p < NPRE; ++p) res[p] = *reinterpret_cast<const float4*>(rbase + (size_t)row[p] * g.ldy);
+        }
+        scatter_half<TM, TN>(acc, idx >> 1, idx & 1, lane, scr);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int2 rw = rows[idx * 16 + row[p]];
+            const float d = __int_as_float(rw.x);
+            const int sq = rw.y;
+            const int4 a = *reinterpret_cast<const int4*>(&scr[row[p] * LD + 4 * c4]);
+            float4 val;
+            val.x = ((float)(a.x - sq) * d) * my_beta;
+            val.y = ((float)(a.y - sq) * d) * my_beta;
+            val.z = ((float)(a.z - sq) * d) * my_beta;
+            val.w = ((float)(a.w - sq) * d) * my_beta;
+            if constexpr (RES) {
+                const float4 r = p < NPRE ? res[p] : *reinterpret_cast<const float4*>(rbase + (size_t)row[p] * g.ldy);
+                val.x = val.x + r.x; val.y = val.y + r.y; val.z = val.z + r.z; val.w = val.w + r.w;
+            }
+            *reinterpret_cast<float4*>(g.y + (size_t)(mbase + row[p]) * g.ldy + col) = val;
+        }
+        __builtin_amdgcn_sched_barrier(0);       // keeps the requests of later half blocks from piling up here
+    }
+}
 
+template <int TM, int TN>
+__device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, const float (&beta)[TN],
+                                int lane, int* scr) {
+    constexpr int W = Epi<TM, TN>::W, LD = Epi<TM, TN>::LD;
+    const bool interior = g.fast_epilogue && (mb0 + TM) * 32 <= g.M && nb0 + TN <= g.nnb;
+    if (interior) {
+        if (g.glu) {
+            if constexpr (TN % 2 == 0) epilogue_glu<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
+        } else if (g.residual) {
+            epilogue_plain<TM, TN, true>(g, acc, mb0, nb0, beta, lane, scr);
+        } else {
+            epilogue_plain<TM, TN, false>(g, acc, mb0, nb0, beta, lane, scr);
+        }
+        return;
+    }
+
+    // tiles on the M / N edge, debug taps, unaligned rows: compact per-element loops
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         if (mb0 + i >= g.nmb) break;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int mbase = (mb0 + i) * 32 + half * 16;
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 8; ++v)
-                    scr[(8 * (v >> 2) + rh + (v & 3)) * LD + j * 32 + cl] = acc[i][j][half * 8 + v];
-            __builtin_amdgcn_wave_barrier();
-            if (interior && g.glu) {
-                if constexpr (TN % 2 == 0) {
-                    constexpr int LPRG = (TN / 2) * 8, RPPG = 64 / LPRG;
-                    const int cg = lane % LPRG, rg = lane / LPRG;
-                    const int jj = cg >> 3, cc = 4 * (cg & 7);
-                    float bg = beta[0], bu = beta[1];
-#pragma unroll
-                    for (int q = 1; q < TN / 2; ++q)
-                        if (jj == q) { bg = beta[2 * q]; bu = beta[2 * q + 1]; }
-#pragma unroll
-                    for (int p = 0; p < 16 / RPPG; ++p) {
-                        const int row = p * RPPG + rg;
-                        const int4 ga = *reinterpret_cast<const int4*>(&scr[row * LD + (2 * jj) * 32 + cc]);
-                        const int4 ua = *reinterpret_cast<const int4*>(&scr[row * LD + (2 * jj + 1) * 32 + cc]);
-                        const float d = g.dscale[mbase + row];
-                        const int sq = g.sumq[mbase + row];
-                        const size_t o = (size_t)(mbase + row) * g.ldy + (nb0 / 2 + jj) * 32 + cc;
-                        const int gi[4] = {ga.x, ga.y, ga.z, ga.w}, ui[4] = {ua.x, ua.y, ua.z, ua.w};
-                        float hv[4];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float G = ((float)(gi[q] - sq) * d) * bg;
-                            const float U = ((float)(ui[q] - sq) * d) * bu;
-                            const float pz = fmaxf(G, 0.f);
-                            hv[q] = (pz * pz) * U;
-                        }
-                        *reinterpret_cast<float4*>(g.y + o) = make_float4(hv[0], hv[1], hv[2], hv[3]);
-                    }
-                }
-            } else if (interior) {
-                const int col_base = nb0 * 32 + 4 * c4;
-#pragma unroll
-                for (int p = 0; p < TN * 2; ++p) {
-                    const int row = p * RPP + r0;
-                    const int4 a = *reinterpret_cast<const int4*>(&scr[row * LD + 4 * c4]);
-                    const float d = g.dscale[mbase + row];
-                    const int sq = g.sumq[mbase + row];
-                    const size_t o = (size_t)(mbase + row) * g.ldy + col_base;
-                    float4 val;
-                    val.x = ((float)(a.x - sq) * d) * my_beta;
-                    val.y = ((float)(a.y - sq) * d) * my_beta;
-                    val.z = ((float)(a.z - sq) * d) * my_beta;
-                    val.w = ((float)(a.w - sq) * d) * my_beta;
-                    if (g.residual) {
-                        const float4 r = *reinterpret_cast<const float4*>(g.residual + o);
-                        val.x = val.x + r.x; val.y = val.y + r.y; val.z = val.z + r.z; val.w = val.w + r.w;
-                    }
-                    *reinterpret_cast<float4*>(g.y + o) = val;
-                }
-            } else if (g.glu) {
+            scatter_half<TM, TN>(acc, i, half, lane, scr);
+            if (g.glu) {
 #pragma unroll 1
                 for (int e = lane; e < 16 * (W / 2); e += 64) {
                     const int row = e / (W / 2), c = e % (W / 2);
@@ -309,7 +383,7 @@ struct LdsTile {
 };
 
 template <int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_lds_kernel(GemmArgs g) {
+__global__ __launch_bounds__(WM * WN * 64, WM * WN / 2) void gemm_lds_kernel(GemmArgs g) {
     using Tile = LdsTile<TM, TN, WM, WN>;
     constexpr int NW = Tile::NW;
     __shared__ __attribute__((aligned(1024))) uint4 stage0[Tile::STAGE];
@@ -381,8 +455,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lds_kernel(GemmArgs g) {
 
     // the stages are free once every wavefront has left the k loop: reuse them for the epilogue
     __syncthreads();
-    static_assert((NW / 2) * Epi<TN>::REGION * 4 <= Tile::STAGE * 16, "half of the epilogue regions per stage");
-    int* scr = reinterpret_cast<int*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * Epi<TN>::REGION;
+    static_assert((NW / 2) * Epi<TM, TN>::REGION * 4 <= Tile::STAGE * 16, "half of the epilogue regions per stage");
+    int* scr = reinterpret_cast<int*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * Epi<TM, TN>::REGION;
     epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
 }
 
@@ -487,8 +561,8 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs g) {
         }
     }
 
-    __shared__ __attribute__((aligned(16))) int escr[(WK > 1 ? WM * WN : 4) * Epi<TN>::REGION];
-    epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, escr + ((WK > 1) ? (wm * WN + wn) : wave) * Epi<TN>::REGION);
+    __shared__ __attribute__((aligned(16))) int escr[(WK > 1 ? WM * WN : 4) * Epi<TM, TN>::REGION];
+    epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, escr + ((WK > 1) ? (wm * WN + wn) : wave) * Epi<TM, TN>::REGION);
 }
 
 template <int TM, int TN, int WM, int WN, int WK>
