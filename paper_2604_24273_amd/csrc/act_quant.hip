@@ -1,6 +1,6 @@
 // Per-token absmax int8 activation quantisation, with the RMSNorm / sub-layer
-// norm that sits in front of it in the blocks fused in.  One wavefront owns one
-// token row and keeps it in registers, so the row is read from HBM once:
+// norm that sits in front of it in the blocks fused in.  A token row is kept in the
+// registers of the 2 or 4 wavefronts that share it, so it is read from HBM once:
 // statistic, absmax and the quantised values all come from the same registers.
 //
 //   (norm)  r = fp32(1 / sqrt(mean_k x_k^2 + eps_n))  [fp64 statistic];  x_k <- (x_k * r) * gain_k
@@ -9,9 +9,10 @@
 // Output goes to the tiled int8 layout the MFMA GEMM reads (see common.hpp),
 // plus per-token a, a / 127 and sum_k q_k.  In that layout 16 consecutive k of
 // one token are 16 bytes, and the same 16 k of the next token follow directly:
-// a workgroup therefore takes 8 consecutive tokens, parks their int8 rows in
-// LDS and writes the tile out in full 128-byte runs.  Two wavefronts share a token
-// (half a row of registers each) and meet through LDS for the three reductions.
+// a workgroup therefore takes 8 consecutive tokens at a time, parks their int8 rows
+// in LDS and writes the tile out in full 128-byte runs.  The workgroups are
+// persistent and request the rows of their next tokens before working on the
+// current ones, so that HBM stays busy through the reductions and the write-out.
 #include "common.hpp"
 
 namespace brl {
@@ -37,27 +38,15 @@ struct QK {
 
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// HV4: float4 chunks per lane; the two wavefronts of a token interleave their chunks
-// (chunk c = 2 i + half covers k = 4 (lane + 64 c) .. + 3), so every load stays coalesced.
-template <int HV4>
-__global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // AQ_ROWS x (Kp + 16) bytes
-    __shared__ double red_ss[AQ_ROWS][2];
-    __shared__ float red_max[AQ_ROWS][2];
-    __shared__ int red_sum[AQ_ROWS][2];
-
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rl = wave >> 1, half = wave & 1;
-    const int row0 = blockIdx.x * AQ_ROWS;
-    const int row = row0 + rl;
+// HV4: float4 chunks per lane; WPT: wavefronts per token.  The wavefronts of a token interleave
+// their chunks (chunk c = WPT i + part covers k = 4 (lane + 64 c) .. + 3), so every load stays coalesced.
+template <int HV4, int WPT>
+__device__ inline void load_rows(const QK& a, int row, int lane, int part, float4 (&v)[HV4]) {
     const int K = a.K;
     const bool live = row < a.M;
-    const int stride = a.Kp + 16;          // the 16-byte skew keeps the 8 rows on different LDS banks
-
-    float4 v[HV4];
 #pragma unroll
     for (int i = 0; i < HV4; ++i) {
-        const int k = 4 * (lane + 64 * (2 * i + half));
+        const int k = 4 * (lane + 64 * (WPT * i + part));
         float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
         if (live && k < K) {
             if (a.x_dtype == BRL_BF16) {
@@ -74,86 +63,173 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
         }
         v[i] = e;
     }
+}
 
+// The 16 wavefronts of a workgroup take 16 / WPT tokens per round; WPT / 2 rounds fill the 8-token
+// group that is written out together.  A workgroup walks the groups g = blockIdx.x, + gridDim.x, ...
+// and requests the rows of its next round before it works on the current one.
+template <int HV4, int WPT>
+__global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
+    constexpr int TPR = 16 / WPT;          // tokens per round
+    constexpr int RPG = AQ_ROWS / TPR;     // rounds per 8-token group
+    extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // AQ_ROWS x (Kp + 16) bytes, then the gain
+    __shared__ double red_ss[TPR][WPT];
+    __shared__ float red_max[TPR][WPT];
+    __shared__ int red_sum[TPR][WPT];
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rl = wave / WPT, part = wave % WPT;
+    const int K = a.K;
+    const int stride = a.Kp + 16;          // the 16-byte skew keeps the 8 rows on different LDS banks
+    const int ngroups = (a.M + AQ_ROWS - 1) / AQ_ROWS;
+
+    int grp = blockIdx.x, rnd = 0;
+    float4 v[HV4];
+    load_rows<HV4, WPT>(a, grp * AQ_ROWS + rl, lane, part, v);
+
+    // the norm gain is the same for every token: parked in LDS once (read after the first barrier below)
+    float* gain_lds = reinterpret_cast<float*>(rowbuf + (size_t)AQ_ROWS * stride);
     if (a.gain) {
-        double ss = 0.0;
+        for (int k = 4 * threadIdx.x; k < K; k += 4 * AQ_THREADS)
+            *reinterpret_cast<float4*>(gain_lds + k) = *reinterpret_cast<const float4*>(a.gain + k);
+    }
+
+    while (true) {
+        const int next_rnd = (rnd + 1) % RPG;
+        const int next_grp = next_rnd == 0 ? grp + (int)gridDim.x : grp;
+        const bool more = next_grp < ngroups;
+        float4 vn[HV4];
+        if (more) load_rows<HV4, WPT>(a, next_grp * AQ_ROWS + next_rnd * TPR + rl, lane, part, vn);
+
+        const int row0 = grp * AQ_ROWS;
+        const int row = row0 + rnd * TPR + rl;
+        const bool live = row < a.M;
+
+        if (a.gain) {
+            double ss = 0.0;
 #pragma unroll
-        for (int i = 0; i < HV4; ++i) {
-            ss += (double)v[i].x * (double)v[i].x;
-            ss += (double)v[i].y * (double)v[i].y;
-            ss += (double)v[i].z * (double)v[i].z;
-            ss += (double)v[i].w * (double)v[i].w;
-        }
+            for (int i = 0; i < HV4; ++i) {
+                ss += (double)v[i].x * (double)v[i].x;
+                ss += (double)v[i].y * (double)v[i].y;
+                ss += (double)v[i].z * (double)v[i].z;
+                ss += (double)v[i].w * (double)v[i].w;
+            }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
-        if (lane == 0) red_ss[rl][half] = ss;
-        __syncthreads();
-        const double ms = (red_ss[rl][0] + red_ss[rl][1]) / (double)K;
-        const float r = (float)(1.0 / sqrt(ms + (double)a.eps_norm));
+            for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+            if (lane == 0) red_ss[rl][part] = ss;
+            __syncthreads();
+            double tot = red_ss[rl][0];
 #pragma unroll
-        for (int i = 0; i < HV4; ++i) {
-            const int k = 4 * (lane + 64 * (2 * i + half));
-            if (k < K) {
-                const float4 g = *reinterpret_cast<const float4*>(a.gain + k);
-                v[i].x = (v[i].x * r) * g.x;
-                v[i].y = (v[i].y * r) * g.y;
-                v[i].z = (v[i].z * r) * g.z;
-                v[i].w = (v[i].w * r) * g.w;
+            for (int w = 1; w < WPT; ++w) tot += red_ss[rl][w];
+            const float r = (float)(1.0 / sqrt(tot / (double)K + (double)a.eps_norm));
+#pragma unroll
+            for (int i = 0; i < HV4; ++i) {
+                const int k = 4 * (lane + 64 * (WPT * i + part));
+                if (k < K) {
+                    const float4 g = *reinterpret_cast<const float4*>(gain_lds + k);
+                    v[i].x = (v[i].x * r) * g.x;
+                    v[i].y = (v[i].y * r) * g.y;
+                    v[i].z = (v[i].z * r) * g.z;
+                    v[i].w = (v[i].w * r) * g.w;
+                }
             }
         }
-    }
 
-    float amax = 0.f;
+        float amax = 0.f;
 #pragma unroll
-    for (int i = 0; i < HV4; ++i) {
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[i].x), fabsf(v[i].y)), fmaxf(fabsf(v[i].z), fabsf(v[i].w))));
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-    if (lane == 0) red_max[rl][half] = amax;
-    __syncthreads();
-    const float ac = fmaxf(fmaxf(red_max[rl][0], red_max[rl][1]), a.eps_act);
-    const float s = 127.0f / ac;
-
-    int sum = 0;
-    uint32_t* myrow = reinterpret_cast<uint32_t*>(rowbuf + (size_t)rl * stride);
-#pragma unroll
-    for (int i = 0; i < HV4; ++i) {
-        const int k = 4 * (lane + 64 * (2 * i + half));
-        if (k < a.Kp) {
-            int q0 = (int)fminf(fmaxf(rintf(v[i].x * s), -127.f), 127.f);
-            int q1 = (int)fminf(fmaxf(rintf(v[i].y * s), -127.f), 127.f);
-            int q2 = (int)fminf(fmaxf(rintf(v[i].z * s), -127.f), 127.f);
-            int q3 = (int)fminf(fmaxf(rintf(v[i].w * s), -127.f), 127.f);
-            sum += q0 + q1 + q2 + q3;
-            const uint32_t word = (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) | ((uint32_t)(q2 & 0xff) << 16) |
-                                  ((uint32_t)(q3 & 0xff) << 24);
-            myrow[k >> 2] = word;
-            if (a.xq_rowmajor && live && k < K) *reinterpret_cast<uint32_t*>(a.xq_rowmajor + (size_t)row * K + k) = word;
+        for (int i = 0; i < HV4; ++i) {
+            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[i].x), fabsf(v[i].y)), fmaxf(fabsf(v[i].z), fabsf(v[i].w))));
         }
-    }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
-    if (lane == 0) red_sum[rl][half] = sum;
-    __syncthreads();
-    if (lane == 0 && half == 0 && live) {
-        a.absmax[row] = ac;
-        a.dscale[row] = ac / 127.0f;
-        a.sumq[row] = red_sum[rl][0] + red_sum[rl][1];
-        if (a.absmax_tap) a.absmax_tap[row] = ac;
-    }
+        for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        if (lane == 0) red_max[rl][part] = amax;
+        __syncthreads();
+        float ac = a.eps_act;
+#pragma unroll
+        for (int w = 0; w < WPT; ++w) ac = fmaxf(ac, red_max[rl][w]);
+        const float s = 127.0f / ac;
 
-    // tiled write-out: thread (token t8, chunk kc) moves the 16 bytes of k = 16 kc .. 16 kc + 15;
-    // the 8 tokens of one chunk are 128 contiguous bytes of the tile
-    const int t8 = threadIdx.x & 7;
-    const int mb = row0 >> 5, r0 = row0 & 31;
-    const int nchunks = a.Kp >> 4;
-    for (int kc = threadIdx.x >> 3; kc < nchunks; kc += AQ_THREADS / 8) {
-        const uint4 val = *reinterpret_cast<const uint4*>(rowbuf + (size_t)t8 * stride + 16 * kc);
-        const int sb = kc >> 3, dd = (kc >> 1) & 3, hh = kc & 1;
-        const size_t off = ((((size_t)mb * a.nsb + sb) * 4 + dd) * 64 + (hh * 32 + r0 + t8)) * 16;
-        *reinterpret_cast<uint4*>(a.q_tiled + off) = val;
+        int sum = 0;
+        uint32_t* myrow = reinterpret_cast<uint32_t*>(rowbuf + (size_t)(rnd * TPR + rl) * stride);
+#pragma unroll
+        for (int i = 0; i < HV4; ++i) {
+            const int k = 4 * (lane + 64 * (WPT * i + part));
+            if (k < a.Kp) {
+                int q0 = (int)fminf(fmaxf(rintf(v[i].x * s), -127.f), 127.f);
+                int q1 = (int)fminf(fmaxf(rintf(v[i].y * s), -127.f), 127.f);
+                int q2 = (int)fminf(fmaxf(rintf(v[i].z * s), -127.f), 127.f);
+                int q3 = (int)fminf(fmaxf(rintf(v[i].w * s), -127.f), 127.f);
+                sum += q0 + q1 + q2 + q3;
+                const uint32_t word = (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) |
+                                      ((uint32_t)(q2 & 0xff) << 16) | ((uint32_t)(q3 & 0xff) << 24);
+                myrow[k >> 2] = word;
+                if (a.xq_rowmajor && live && k < K)
+                    *reinterpret_cast<uint32_t*>(a.xq_rowmajor + (size_t)row * K + k) = word;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if (lane == 0) red_sum[rl][part] = sum;
+        __syncthreads();
+        if (lane == 0 && part == 0 && live) {
+            int tot = red_sum[rl][0];
+#pragma unroll
+            for (int w = 1; w < WPT; ++w) tot += red_sum[rl][w];
+            a.absmax[row] = ac;
+            a.dscale[row] = ac / 127.0f;
+            a.sumq[row] = tot;
+            if (a.absmax_tap) a.absmax_tap[row] = ac;
+        }
+
+        if (rnd == RPG - 1) {
+            // tiled write-out: thread (token t8, chunk kc) moves the 16 bytes of k = 16 kc .. 16 kc + 15;
+            // the 8 tokens of one chunk are 128 contiguous bytes of the tile
+            const int t8 = threadIdx.x & 7;
+            const int mb = row0 >> 5, r0 = row0 & 31;
+            const int nchunks = a.Kp >> 4;
+            for (int kc = threadIdx.x >> 3; kc < nchunks; kc += AQ_THREADS / 8) {
+                const uint4 val = *reinterpret_cast<const uint4*>(rowbuf + (size_t)t8 * stride + 16 * kc);
+                const int sb = kc >> 3, dd = (kc >> 1) & 3, hh = kc & 1;
+                const size_t off = ((((size_t)mb * a.nsb + sb) * 4 + dd) * 64 + (hh * 32 + r0 + t8)) * 16;
+                *reinterpret_cast<uint4*>(a.q_tiled + off) = val;
+            }
+        }
+
+        if (!more) break;
+        // (the barriers of the next round order its LDS writes after the reads above)
+#pragma unroll
+        for (int i = 0; i < HV4; ++i) v[i] = vn[i];
+        grp = next_grp;
+        rnd = next_rnd;
     }
+}
+
+template <int HV4, int WPT>
+int launch_one(const QK& a, int ngroups, size_t lds, hipStream_t s) {
+    static int slots = 0;            // workgroups the device holds at once
+    static bool raised = false;      // more than the default 64 KB of dynamic LDS allowed
+    constexpr size_t max_lds = (size_t)AQ_ROWS * (HV4 * WPT * 256 + 16) + (size_t)HV4 * WPT * 256 * 4;
+    if (!raised && max_lds > 65536) {
+        BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<HV4, WPT>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds));
+        raised = true;
+    }
+    if (slots == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, act_quant_kernel<HV4, WPT>, AQ_THREADS, max_lds) !=
+                hipSuccess ||
+            cus <= 0 || per_cu <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+            per_cu = 1;
+        }
+        slots = cus * per_cu;
+    }
+    const int grid = ngroups < slots ? ngroups : slots;
+    hipLaunchKernelGGL((act_quant_kernel<HV4, WPT>), dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    return BRL_OK;
 }
 
 }  // namespace
@@ -165,28 +241,26 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     a.M = in.M; a.K = in.K; a.Kp = round_up(in.K, SBK); a.nsb = a.Kp / SBK;
     a.q_tiled = out.q; a.absmax = out.absmax; a.dscale = out.dscale; a.sumq = out.sumq;
     a.xq_rowmajor = in.xq_rowmajor; a.absmax_tap = in.absmax_tap;
-    const int grid = (in.M + AQ_ROWS - 1) / AQ_ROWS;
-    const size_t lds = (size_t)AQ_ROWS * (a.Kp + 16);
-    const int hv4 = (a.Kp + 511) / 512;      // float4 chunks per lane of each of the two wavefronts
+    const int ngroups = (in.M + AQ_ROWS - 1) / AQ_ROWS;
+    const size_t lds = (size_t)AQ_ROWS * (a.Kp + 16) + (in.gain ? (size_t)a.Kp * 4 : 0);
+    // registers hold the current and the next row share of a lane: at most 2 x 9 float4
     LaunchTimer tm(BRL_KC_ACT_QUANT, s);
-    if (hv4 <= 2) {
-        hipLaunchKernelGGL(act_quant_kernel<2>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
-    } else if (hv4 <= 6) {
-        hipLaunchKernelGGL(act_quant_kernel<6>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
-    } else if (hv4 <= 14) {
-        hipLaunchKernelGGL(act_quant_kernel<14>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
-    } else if (hv4 <= 18) {
-        static bool raised = false;     // this instantiation needs more than the default 64 KB of dynamic LDS
-        if (!raised) {
-            BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<18>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, AQ_ROWS * (MAX_K + 16)));
-            raised = true;
-        }
-        hipLaunchKernelGGL(act_quant_kernel<18>, dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    int rc;
+    if (a.Kp <= 1024) {
+        rc = launch_one<2, 2>(a, ngroups, lds, s);
+    } else if (a.Kp <= 3072) {
+        rc = launch_one<6, 2>(a, ngroups, lds, s);
+    } else if (a.Kp <= 4608) {
+        rc = launch_one<9, 2>(a, ngroups, lds, s);
+    } else if (a.Kp <= 7168) {
+        rc = launch_one<7, 4>(a, ngroups, lds, s);
+    } else if (a.Kp <= MAX_K) {
+        rc = launch_one<9, 4>(a, ngroups, lds, s);
     } else {
         set_error("act_quant: K = %d exceeds the supported %d", in.K, MAX_K);
         return BRL_EINVAL;
     }
+    if (rc != BRL_OK) return rc;
     BRL_LAUNCH_CHECK("act_quant_kernel");
     return BRL_OK;
 }

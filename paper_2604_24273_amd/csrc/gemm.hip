@@ -383,7 +383,7 @@ struct LdsTile {
 };
 
 template <int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64, WM * WN / 2) void gemm_lds_kernel(GemmArgs g) {
+__global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_kernel(GemmArgs g) {
     using Tile = LdsTile<TM, TN, WM, WN>;
     constexpr int NW = Tile::NW;
     __shared__ __attribute__((aligned(1024))) uint4 stage0[Tile::STAGE];
@@ -636,10 +636,23 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
         if (g.nmb <= 2) return launch_direct<2, 1, 1, 1, 4>(g, s);
         if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
     }
-    // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64) once they fill the chip twice over,
-    // else 128 x 128 tiles (4 wavefronts)
+    // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64, two workgroups per CU) or 128 x 128 tiles
+    // (4 wavefronts, four per CU).  The wide tile does about 5 % more work per unit time; the narrow
+    // one wins when it spreads the tiles more evenly over the compute units.
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+        }
+    }
     const long t_wide = (long)((g.nmb + 3) / 4) * ((g.nnb + 7) / 8);
-    if (t_wide >= 512) return launch_lds<2, 2, 2, 4>(g, s);
+    const long t_narrow = (long)((g.nmb + 3) / 4) * ((g.nnb + 3) / 4);
+    const double fill_wide = (double)t_wide / (double)(((t_wide + cus - 1) / cus) * cus);
+    const double fill_narrow = (double)t_narrow / (double)(((t_narrow + cus - 1) / cus) * cus);
+    if (t_wide >= 2 * cus && fill_wide >= 0.95 * fill_narrow) return launch_lds<2, 2, 2, 4>(g, s);
     return launch_lds<2, 2, 2, 2>(g, s);
 }
 
