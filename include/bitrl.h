@@ -116,6 +116,27 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K,
                       void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Many independent few-token BitLinear problems of one shape in one launch:
+ *   y[i] = BitLinear(x[i]; packed[i], beta[i]),  i = 0 .. count-1,
+ * each computed exactly as bitlinear_forward computes it (Section 3.1: the
+ * frozen encoder is evaluated once per environment step on a single short
+ * state, where the ternary matmul is bound by streaming the weights).  With
+ * one token a 2560 x 6912 matrix is 4.4 MB of weights and far below the cost
+ * of a kernel launch; this entry point lets a caller that has many such
+ * products queued (several encoders, adapters or layers whose inputs are
+ * already known) stream them at HBM rate.
+ *
+ * packed, beta, x, y: DEVICE arrays of count device pointers (packed[i] from
+ * bitlinear_quantize_weights for an [N, K] matrix; beta[i] [1]; x[i] [M, K]
+ * of x_dtype; y[i] [M, N] fp32).  1 <= M <= 4.  Entries may repeat in packed /
+ * beta / x; the y[i] must be distinct buffers.  No workspace, no taps.
+ * The pointer arrays are read on the device only: the host cannot check them.
+ * ------------------------------------------------------------------------ */
+int bitlinear_forward_batch(const void* const* packed, const float* const* beta, int N, int K,
+                            const void* const* x, int x_dtype, int M, float eps_act,
+                            float* const* y, int count, void* stream);
+
+/* ------------------------------------------------------------------------
  * One feed-forward block:
  *   n = RMSNorm_d(x; norm_g);  (G, U) = BitLinear_gate(n), BitLinear_up(n)
  *   (n is quantised once, each matrix keeps its own beta);

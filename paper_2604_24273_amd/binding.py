@@ -77,6 +77,8 @@ _SIGNATURES = {
     "brl_bitlinear_workspace_bytes": (c_size_t, [c_int, c_int, c_int]),
     "bitlinear_forward": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "bitlinear_forward_batch": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
+                                        c_void_p, c_int, c_void_p]),
     "brl_ffn_workspace_bytes": (c_size_t, [c_int, c_int, c_int]),
     "ffn_block_forward": (c_int, [C.POINTER(brl_ffn_weights), c_void_p, c_int, c_int, c_int, c_int, c_float, c_float,
                                   c_void_p, c_void_p, c_size_t, c_void_p]),
@@ -170,6 +172,13 @@ def bitlinear_forward(packed: torch.Tensor, beta: torch.Tensor, N: int, K: int, 
     _check(lib().bitlinear_forward(_ptr(packed), _ptr(beta), N, K, _ptr(x), _dtype_code(x), M, eps_act, _ptr(y),
                                    _ptr(residual), _ptr(xq_dbg), _ptr(absmax_dbg), _ptr(acc_dbg), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+def bitlinear_forward_batch(packed_ptrs: torch.Tensor, beta_ptrs: torch.Tensor, N: int, K: int, x_ptrs: torch.Tensor,
+                            x_dtype: int, M: int, eps_act: float, y_ptrs: torch.Tensor, count: int) -> None:
+    """The four *_ptrs are int64 device tensors holding device addresses (tensor.data_ptr() values)."""
+    _check(lib().bitlinear_forward_batch(_ptr(packed_ptrs), _ptr(beta_ptrs), N, K, _ptr(x_ptrs), x_dtype, M, eps_act,
+                                         _ptr(y_ptrs), count, _stream()))
 
 
 def brl_ffn_workspace_bytes(M: int, d: int, f: int) -> int:

@@ -406,6 +406,17 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K, const
     return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, 0, s);
 }
 
+int bitlinear_forward_batch(const void* const* packed, const float* const* beta, int N, int K, const void* const* x,
+                            int x_dtype, int M, float eps_act, float* const* y, int count, void* stream) {
+    BRL_REQUIRE(packed && beta && x && y, "bitlinear_forward_batch: null pointer array");
+    BRL_REQUIRE(M >= 1 && M <= 4, "bitlinear_forward_batch: M = %d out of range 1..4", M);
+    BRL_REQUIRE(count >= 0, "bitlinear_forward_batch: count = %d", count);
+    BRL_REQUIRE(x_dtype == BRL_F32 || x_dtype == BRL_BF16, "bitlinear_forward_batch: unknown x_dtype %d", x_dtype);
+    BRL_REQUIRE(eps_act > 0.f, "bitlinear_forward_batch: eps_act must be positive");
+    if (int rc = check_linear_shape(N, K, "bitlinear_forward_batch")) return rc;
+    return launch_gemv_batch(packed, beta, N, K, x, x_dtype, M, eps_act, y, count, static_cast<hipStream_t>(stream));
+}
+
 size_t brl_ffn_workspace_bytes(int M, int d, int f) {
     if (M < 1 || d < 1 || f < 1) return 0;
     return ffn_ws_layout(M, d, f).total;

@@ -114,6 +114,8 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K,
 int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t* packed, const float* beta,
                 float eps_act, float* y, const float* residual, int8_t* xq_dbg, float* absmax_dbg,
                 int32_t* acc_dbg, hipStream_t s);
+int launch_gemv_batch(const void* const* packed, const float* const* beta, int N, int K, const void* const* x,
+                      int x_dtype, int M, float eps_act, float* const* y, int count, hipStream_t s);
 
 // attention, embedding, pooling, heads
 int launch_rope_table(float* cos_t, float* sin_t, int S, int head_dim, float theta, hipStream_t s);

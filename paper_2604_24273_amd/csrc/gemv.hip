@@ -178,6 +178,192 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvArgs g) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Many independent problems of one shape in a single launch.  Work item i is row block
+// i % nwg of problem i / nwg; a persistent workgroup takes a contiguous run of items,
+// requests the weights of its next item before it contracts the current one, and
+// quantises the activations of a problem once for all of that problem's row blocks it owns.
+// ---------------------------------------------------------------------------
+struct GemvBatchArgs {
+    const uint4* const* packed;   // device arrays of device pointers, one entry per problem
+    const float* const* beta;
+    const void* const* x;
+    float* const* y;
+    int x_dtype;
+    int M, K, N, nsb, nwg, count;
+    float eps_act;
+};
+
+__device__ inline void gv_request(const uint4* packed, int nb, int nsb, int wave, int lane,
+                                  uint4 (&w)[GV_SB_PER_WAVE]) {
+#pragma unroll
+    for (int u = 0; u < GV_SB_PER_WAVE; ++u) {
+        const int sb = wave + GV_WAVES * u;
+        w[u] = make_uint4(0x55555555u, 0x55555555u, 0x55555555u, 0x55555555u);   // code 0 everywhere
+        if (sb < nsb) w[u] = packed[((size_t)nb * nsb + sb) * 64 + lane];
+    }
+}
+
+template <int MT>
+__global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g) {
+    __shared__ __attribute__((aligned(16))) int xq[MT][MAX_K / 4];
+    __shared__ float wmax[MT][GV_WAVES];
+    __shared__ int wsum[MT][GV_WAVES];
+    __shared__ int red[2][GV_WAVES][MT][32];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int K = g.K, Kp = g.nsb * SBK;
+    const long items = (long)g.count * g.nwg;
+    const long i0 = items * blockIdx.x / gridDim.x, i1 = items * (blockIdx.x + 1) / gridDim.x;
+    if (i0 >= i1) return;
+
+    uint4 wreg[GV_SB_PER_WAVE], wnext[GV_SB_PER_WAVE];
+    gv_request(g.packed[i0 / g.nwg], (int)(i0 % g.nwg), g.nsb, wave, lane, wreg);
+
+    int cur_p = -1, par = 0;
+    float dsc[MT];          // a / 127 per token of the current problem
+    int sq[MT];             // sum_k q per token
+    float beta = 0.f;
+    float* yp = nullptr;
+    const int hh = lane >> 5;
+
+    for (long it = i0; it < i1; ++it) {
+        const int p = (int)(it / g.nwg), nb = (int)(it % g.nwg);
+        if (it + 1 < i1)
+            gv_request(g.packed[(it + 1) / g.nwg], (int)((it + 1) % g.nwg), g.nsb, wave, lane, wnext);
+
+        if (p != cur_p) {
+            __syncthreads();               // every wavefront is done with the previous problem's xq
+            const void* x = g.x[p];
+            float4 xv[MT][GV_X4];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                float tm = 0.f;
+#pragma unroll
+                for (int u = 0; u < GV_X4; ++u) {
+                    const int k = 4 * ((int)threadIdx.x + GV_THREADS * u);
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (t < g.M && k < K) v = load_x4(x, g.x_dtype, (size_t)t * K + k);
+                    xv[t][u] = v;
+                    tm = fmaxf(tm, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+                }
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) tm = fmaxf(tm, __shfl_xor(tm, off, 64));
+                if (lane == 0) wmax[t][wave] = tm;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                float m = wmax[t][0];
+#pragma unroll
+                for (int w = 1; w < GV_WAVES; ++w) m = fmaxf(m, wmax[t][w]);
+                const float ac = fmaxf(m, g.eps_act);
+                dsc[t] = ac / 127.0f;
+                const float sc = 127.0f / ac;
+                int qsum = 0;
+#pragma unroll
+                for (int u = 0; u < GV_X4; ++u) {
+                    const int k = 4 * ((int)threadIdx.x + GV_THREADS * u);
+                    if (k < Kp) {
+                        const float4 v = xv[t][u];
+                        const int q0 = (int)fminf(fmaxf(rintf(v.x * sc), -127.f), 127.f);
+                        const int q1 = (int)fminf(fmaxf(rintf(v.y * sc), -127.f), 127.f);
+                        const int q2 = (int)fminf(fmaxf(rintf(v.z * sc), -127.f), 127.f);
+                        const int q3 = (int)fminf(fmaxf(rintf(v.w * sc), -127.f), 127.f);
+                        qsum += q0 + q1 + q2 + q3;
+                        xq[t][k >> 2] = (q0 & 0xff) | ((q1 & 0xff) << 8) | ((q2 & 0xff) << 16) | ((q3 & 0xff) << 24);
+                    }
+                }
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) qsum += __shfl_xor(qsum, off, 64);
+                if (lane == 0) wsum[t][wave] = qsum;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                int sum = 0;
+#pragma unroll
+                for (int w = 0; w < GV_WAVES; ++w) sum += wsum[t][w];
+                sq[t] = sum;
+            }
+            beta = *g.beta[p];
+            yp = g.y[p];
+            cur_p = p;
+        }
+
+        int acc[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[t] = 0;
+#pragma unroll
+        for (int u = 0; u < GV_SB_PER_WAVE; ++u) {
+            const int sb = wave + GV_WAVES * u;
+            if (sb >= g.nsb) continue;
+            const uint32_t wd[4] = {wreg[u].x, wreg[u].y, wreg[u].z, wreg[u].w};
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) {
+                const uint32_t pw = wd[dd];
+                const int c0 = (int)(pw & 0x03030303u), c1 = (int)((pw >> 2) & 0x03030303u);
+                const int c2 = (int)((pw >> 4) & 0x03030303u), c3 = (int)((pw >> 6) & 0x03030303u);
+                const int xoff = (sb * 128 + dd * 32 + hh * 16) / 4;
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    const int4 xw = *reinterpret_cast<const int4*>(&xq[t][xoff]);
+                    acc[t] = __builtin_amdgcn_sdot4(c0, xw.x, acc[t], false);
+                    acc[t] = __builtin_amdgcn_sdot4(c1, xw.y, acc[t], false);
+                    acc[t] = __builtin_amdgcn_sdot4(c2, xw.z, acc[t], false);
+                    acc[t] = __builtin_amdgcn_sdot4(c3, xw.w, acc[t], false);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            acc[t] += __shfl_xor(acc[t], 32, 64);
+            if (lane < 32) red[par][wave][t][lane] = acc[t];
+        }
+        __syncthreads();
+        // threads 0 .. 32 MT - 1 each own one (token, row); red[par] is next written two barriers from here
+        const int t_of = threadIdx.x >> 5, r_of = threadIdx.x & 31;
+        if (t_of < MT && t_of < g.M) {
+            int part = 0;
+#pragma unroll
+            for (int w = 0; w < GV_WAVES; ++w) part += red[par][w][t_of][r_of];
+            float d = dsc[0];
+            int s = sq[0];
+#pragma unroll
+            for (int t = 1; t < MT; ++t)
+                if (t_of == t) { d = dsc[t]; s = sq[t]; }
+            const int n = nb * 32 + r_of;
+            if (n < g.N) yp[(size_t)t_of * g.N + n] = ((float)(part - s) * d) * beta;
+        }
+        par ^= 1;
+        if (it + 1 < i1) {
+#pragma unroll
+            for (int u = 0; u < GV_SB_PER_WAVE; ++u) wreg[u] = wnext[u];
+        }
+    }
+}
+
+template <int MT>
+int launch_batch_one(const GemvBatchArgs& g, hipStream_t s) {
+    static int slots = 0;            // workgroups the device holds at once
+    if (slots == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_batch_kernel<MT>, GV_THREADS, 0) != hipSuccess ||
+            cus <= 0 || per_cu <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+            per_cu = 1;
+        }
+        slots = cus * per_cu;
+    }
+    const long items = (long)g.count * g.nwg;
+    const int grid = (int)(items < slots ? items : slots);
+    hipLaunchKernelGGL(gemv_batch_kernel<MT>, dim3(grid), dim3(GV_THREADS), 0, s, g);
+    return BRL_OK;
+}
+
 }  // namespace
 
 int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t* packed, const float* beta,
@@ -203,6 +389,33 @@ int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t*
         default: set_error("gemv: M = %d out of range 1..4", M); return BRL_EINVAL;
     }
     BRL_LAUNCH_CHECK("gemv_kernel");
+    return BRL_OK;
+}
+
+int launch_gemv_batch(const void* const* packed, const float* const* beta, int N, int K, const void* const* x,
+                      int x_dtype, int M, float eps_act, float* const* y, int count, hipStream_t s) {
+    GemvBatchArgs g;
+    g.packed = reinterpret_cast<const uint4* const*>(packed);
+    g.beta = beta; g.x = x; g.y = y; g.x_dtype = x_dtype;
+    g.M = M; g.K = K; g.N = N;
+    g.nsb = round_up(K, SBK) / SBK;
+    g.nwg = round_up(N, NB) / NB;
+    g.count = count;
+    g.eps_act = eps_act;
+    if (g.nsb > GV_MAX_SB) {
+        set_error("gemv batch: K = %d exceeds the supported %d", K, MAX_K);
+        return BRL_EINVAL;
+    }
+    if (count == 0) return BRL_OK;
+    LaunchTimer tm(BRL_KC_GEMV, s);
+    switch (M) {
+        case 1: launch_batch_one<1>(g, s); break;
+        case 2: launch_batch_one<2>(g, s); break;
+        case 3:
+        case 4: launch_batch_one<4>(g, s); break;
+        default: set_error("gemv batch: M = %d out of range 1..4", M); return BRL_EINVAL;
+    }
+    BRL_LAUNCH_CHECK("gemv_batch_kernel");
     return BRL_OK;
 }
 

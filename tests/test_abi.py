@@ -76,6 +76,13 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.bitlinear_forward(fake, fake, 32, 16384, fake, 0, 1, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
     assert lib.bitlinear_forward(fake, fake, 32, 128, fake, 0, 0, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
     assert lib.bitlinear_forward(fake, fake, 32, 128, fake, 7, 1, 1e-5, fake, None, None, None, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    # the batch entry point: few-token problems only, sane counts and shapes
+    assert lib.bitlinear_forward_batch(None, fake, 32, 128, fake, 0, 1, 1e-5, fake, 1, None) == B.BRL_EINVAL
+    assert lib.bitlinear_forward_batch(fake, fake, 32, 128, fake, 0, 5, 1e-5, fake, 1, None) == B.BRL_EINVAL
+    assert lib.bitlinear_forward_batch(fake, fake, 32, 128, fake, 0, 0, 1e-5, fake, 1, None) == B.BRL_EINVAL
+    assert lib.bitlinear_forward_batch(fake, fake, 32, 128, fake, 0, 1, 1e-5, fake, -1, None) == B.BRL_EINVAL
+    assert lib.bitlinear_forward_batch(fake, fake, 32, 100, fake, 0, 1, 1e-5, fake, 1, None) == B.BRL_EINVAL
+    assert lib.bitlinear_forward_batch(fake, fake, 32, 128, fake, 9, 1, 1e-5, fake, 1, None) == B.BRL_EINVAL
     # workspace too small
     assert lib.bitlinear_forward(fake, fake, 32, 128, fake, 0, 64, 1e-5, fake, None, None, None, None, fake, 16, None) == B.BRL_ENOSPC
     assert "workspace" in err()

@@ -162,6 +162,43 @@ def test_gemv_pair_decode_shape_repeated():
         assert np.array_equal(yy, y_ref)
 
 
+@pytest.mark.parametrize("m,n,k,count,bf16", [(1, 6912, 2560, 9, False), (1, 2560, 6912, 7, False), (3, 100, 200, 5, True),
+                                              (2, 264, 8200, 3, False), (4, 96, 128, 700, False)])
+def test_bitlinear_forward_batch(m, n, k, count, bf16):
+    """Many independent few-token problems in one launch: each equals the oracle and the one-problem entry point."""
+    B, R = _mods()
+    n_w = min(count, 4)                       # weights and inputs repeat across the batch, outputs do not
+    cases = [synth.bitlinear_case(100 + i, n, k, m) for i in range(n_w)]
+    pls = [R.quantize_linear(c["W"]) for c in cases]
+    xs_host = [synth.bf16_bits_to_f32(synth.to_bf16_bits(c["X"])) if bf16 else c["X"] for c in cases]
+    xs = [R.bf16_from_bits(synth.to_bf16_bits(c["X"])) if bf16 else R.dev(c["X"]) for c in cases]
+    ys = [torch.full((m, n), float("nan"), dtype=torch.float32, device="cuda") for _ in range(count)]
+    order = [(3 * i + 1) % n_w for i in range(count)]
+
+    def ptrs(ts):
+        return torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device="cuda")
+
+    B.bitlinear_forward_batch(ptrs([pls[j].packed for j in order]), ptrs([pls[j].beta for j in order]), n, k,
+                              ptrs([xs[j] for j in order]), B.BRL_BF16 if bf16 else B.BRL_F32, m, 1e-5, ptrs(ys), count)
+    torch.cuda.synchronize()
+    refs = []
+    for j in range(n_w):
+        codes, beta = O.ternary_quantize(cases[j]["W"])
+        refs.append(O.bitlinear_forward(xs_host[j], codes, beta))
+    ws = R.Workspace(B.brl_bitlinear_workspace_bytes(m, n, k))
+    single = []
+    for j in range(n_w):
+        y1 = torch.empty((m, n), dtype=torch.float32, device="cuda")
+        B.bitlinear_forward(pls[j].packed, pls[j].beta, n, k, xs[j], m, 1e-5, y1, None, None, None, None, ws.buf)
+        single.append(y1.cpu().numpy())
+    for i in range(count):
+        got = ys[i].cpu().numpy()
+        assert np.array_equal(got, single[order[i]]), i
+        assert_fp_close(got, refs[order[i]])
+    # an empty batch is a no-op
+    B.bitlinear_forward_batch(ptrs(ys[:1]), ptrs(ys[:1]), n, k, ptrs(ys[:1]), B.BRL_F32, m, 1e-5, ptrs(ys[:1]), 0)
+
+
 # ---------------------------------------------------------------------- FFN
 
 @pytest.mark.parametrize("m,d,f,bf16", [(256, 2560, 6912, True), (37, 256, 392, False), (3, 128, 264, True), (130, 3200, 8640, False)])
