@@ -180,9 +180,12 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvArgs g) {
 
 // ---------------------------------------------------------------------------
 // Many independent problems of one shape in a single launch.  Work item i is row block
-// i % nwg of problem i / nwg; a persistent workgroup takes a contiguous run of items,
-// requests the weights of its next item before it contracts the current one, and
-// quantises the activations of a problem once for all of that problem's row blocks it owns.
+// i % nwg of problem i / nwg.  A persistent workgroup takes a contiguous run of items and
+// quantises the activations of a problem once (into LDS) for all of that problem's row
+// blocks it owns.  Inside a problem every wavefront owns whole row blocks: it streams the
+// block's packed weights in chunks of GB_CH super-blocks, the next chunk (also across
+// row blocks) requested before the current one is contracted, and finishes the 32 rows by
+// itself - no partial sums cross wavefronts and no barrier is met until the problem changes.
 // ---------------------------------------------------------------------------
 struct GemvBatchArgs {
     const uint4* const* packed;   // device arrays of device pointers, one entry per problem
@@ -194,13 +197,40 @@ struct GemvBatchArgs {
     float eps_act;
 };
 
-__device__ inline void gv_request(const uint4* packed, int nb, int nsb, int wave, int lane,
-                                  uint4 (&w)[GV_SB_PER_WAVE]) {
+constexpr int GB_CH = 4;          // super-blocks (1 KB wavefront loads) per chunk
+
+__device__ inline void gb_request(const uint4* blk, int c, int nsb, int lane, uint4 (&w)[GB_CH]) {
 #pragma unroll
-    for (int u = 0; u < GV_SB_PER_WAVE; ++u) {
-        const int sb = wave + GV_WAVES * u;
-        w[u] = make_uint4(0x55555555u, 0x55555555u, 0x55555555u, 0x55555555u);   // code 0 everywhere
-        if (sb < nsb) w[u] = packed[((size_t)nb * nsb + sb) * 64 + lane];
+    for (int u = 0; u < GB_CH; ++u) {
+        const int sb = c * GB_CH + u;
+        if (sb < nsb) w[u] = blk[(size_t)sb * 64 + lane];
+    }
+}
+
+template <int MT>
+__device__ inline void gb_contract(const uint4 (&w)[GB_CH], int c, int nsb, int hh, const int (*xq)[MAX_K / 4],
+                                   int (&acc)[MT]) {
+#pragma unroll
+    for (int u = 0; u < GB_CH; ++u) {
+        const int sb = c * GB_CH + u;
+        if (sb < nsb) {
+            const uint32_t wd[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) {
+                const uint32_t pw = wd[dd];
+                const int c0 = (int)(pw & 0x03030303u), c1 = (int)((pw >> 2) & 0x03030303u);
+                const int c2 = (int)((pw >> 4) & 0x03030303u), c3 = (int)((pw >> 6) & 0x03030303u);
+                const int xoff = (sb * 128 + dd * 32 + hh * 16) / 4;
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    const int4 xw = *reinterpret_cast<const int4*>(&xq[t][xoff]);
+                    acc[t] = __builtin_amdgcn_sdot4(c0, xw.x, acc[t], false);
+                    acc[t] = __builtin_amdgcn_sdot4(c1, xw.y, acc[t], false);
+                    acc[t] = __builtin_amdgcn_sdot4(c2, xw.z, acc[t], false);
+                    acc[t] = __builtin_amdgcn_sdot4(c3, xw.w, acc[t], false);
+                }
+            }
+        }
     }
 }
 
@@ -209,31 +239,24 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
     __shared__ __attribute__((aligned(16))) int xq[MT][MAX_K / 4];
     __shared__ float wmax[MT][GV_WAVES];
     __shared__ int wsum[MT][GV_WAVES];
-    __shared__ int red[2][GV_WAVES][MT][32];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int K = g.K, Kp = g.nsb * SBK;
     const long items = (long)g.count * g.nwg;
     const long i0 = items * blockIdx.x / gridDim.x, i1 = items * (blockIdx.x + 1) / gridDim.x;
-    if (i0 >= i1) return;
-
-    uint4 wreg[GV_SB_PER_WAVE], wnext[GV_SB_PER_WAVE];
-    gv_request(g.packed[i0 / g.nwg], (int)(i0 % g.nwg), g.nsb, wave, lane, wreg);
-
-    int cur_p = -1, par = 0;
-    float dsc[MT];          // a / 127 per token of the current problem
-    int sq[MT];             // sum_k q per token
-    float beta = 0.f;
-    float* yp = nullptr;
     const int hh = lane >> 5;
+    const int nchunks = (g.nsb + GB_CH - 1) / GB_CH;
 
-    for (long it = i0; it < i1; ++it) {
-        const int p = (int)(it / g.nwg), nb = (int)(it % g.nwg);
-        if (it + 1 < i1)
-            gv_request(g.packed[(it + 1) / g.nwg], (int)((it + 1) % g.nwg), g.nsb, wave, lane, wnext);
+    long it = i0;
+    while (it < i1) {
+        const int p = (int)(it / g.nwg);
+        const long p_end = min(i1, (long)(p + 1) * g.nwg);     // this workgroup's items of problem p: [it, p_end)
 
-        if (p != cur_p) {
-            __syncthreads();               // every wavefront is done with the previous problem's xq
+        // ---- quantise the activations of problem p into LDS
+        __syncthreads();                   // every wavefront is done with the previous problem's xq
+        float dsc[MT];                     // a / 127 per token
+        int sq[MT];                        // sum_k q per token
+        {
             const void* x = g.x[p];
             float4 xv[MT][GV_X4];
 #pragma unroll
@@ -286,60 +309,46 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
                 for (int w = 0; w < GV_WAVES; ++w) sum += wsum[t][w];
                 sq[t] = sum;
             }
-            beta = *g.beta[p];
-            yp = g.y[p];
-            cur_p = p;
         }
+        const float beta = *g.beta[p];
+        float* yp = g.y[p];
+        const uint4* wp = g.packed[p];
 
+        // ---- this wavefront's row blocks: it + wave, + 16, ...; a flat walk over (row block, chunk)
+        const long first = it + wave;
+        const int mine = first < p_end ? (int)((p_end - first + GV_WAVES - 1) / GV_WAVES) : 0;
+        const int total = mine * nchunks;
+        const int nb_first = (int)(first % g.nwg);              // row blocks of one problem are consecutive
+        uint4 wa[GB_CH], wb[GB_CH];
         int acc[MT];
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[t] = 0;
+
+        auto block_of = [&](int q) { return wp + (size_t)(nb_first + (q / nchunks) * GV_WAVES) * g.nsb * 64; };
+        auto finish = [&](int q) {
+            // last chunk of a row block: fold the two k-halves, rescale, store 32 rows per token
+            const int nb = nb_first + (q / nchunks) * GV_WAVES;
+            const int n = nb * 32 + (lane & 31);
 #pragma unroll
-        for (int u = 0; u < GV_SB_PER_WAVE; ++u) {
-            const int sb = wave + GV_WAVES * u;
-            if (sb >= g.nsb) continue;
-            const uint32_t wd[4] = {wreg[u].x, wreg[u].y, wreg[u].z, wreg[u].w};
-#pragma unroll
-            for (int dd = 0; dd < 4; ++dd) {
-                const uint32_t pw = wd[dd];
-                const int c0 = (int)(pw & 0x03030303u), c1 = (int)((pw >> 2) & 0x03030303u);
-                const int c2 = (int)((pw >> 4) & 0x03030303u), c3 = (int)((pw >> 6) & 0x03030303u);
-                const int xoff = (sb * 128 + dd * 32 + hh * 16) / 4;
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    const int4 xw = *reinterpret_cast<const int4*>(&xq[t][xoff]);
-                    acc[t] = __builtin_amdgcn_sdot4(c0, xw.x, acc[t], false);
-                    acc[t] = __builtin_amdgcn_sdot4(c1, xw.y, acc[t], false);
-                    acc[t] = __builtin_amdgcn_sdot4(c2, xw.z, acc[t], false);
-                    acc[t] = __builtin_amdgcn_sdot4(c3, xw.w, acc[t], false);
-                }
+            for (int t = 0; t < MT; ++t) {
+                const int full = acc[t] + __shfl_xor(acc[t], 32, 64);
+                if (lane < 32 && t < g.M && n < g.N) yp[(size_t)t * g.N + n] = ((float)(full - sq[t]) * dsc[t]) * beta;
+                acc[t] = 0;
+            }
+        };
+
+        if (total > 0) gb_request(block_of(0), 0, g.nsb, lane, wa);
+        for (int q = 0; q < total; q += 2) {
+            if (q + 1 < total) gb_request(block_of(q + 1), (q + 1) % nchunks, g.nsb, lane, wb);
+            gb_contract<MT>(wa, q % nchunks, g.nsb, hh, xq, acc);
+            if (q % nchunks == nchunks - 1) finish(q);
+            if (q + 2 < total) gb_request(block_of(q + 2), (q + 2) % nchunks, g.nsb, lane, wa);
+            if (q + 1 < total) {
+                gb_contract<MT>(wb, (q + 1) % nchunks, g.nsb, hh, xq, acc);
+                if ((q + 1) % nchunks == nchunks - 1) finish(q + 1);
             }
         }
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            acc[t] += __shfl_xor(acc[t], 32, 64);
-            if (lane < 32) red[par][wave][t][lane] = acc[t];
-        }
-        __syncthreads();
-        // threads 0 .. 32 MT - 1 each own one (token, row); red[par] is next written two barriers from here
-        const int t_of = threadIdx.x >> 5, r_of = threadIdx.x & 31;
-        if (t_of < MT && t_of < g.M) {
-            int part = 0;
-#pragma unroll
-            for (int w = 0; w < GV_WAVES; ++w) part += red[par][w][t_of][r_of];
-            float d = dsc[0];
-            int s = sq[0];
-#pragma unroll
-            for (int t = 1; t < MT; ++t)
-                if (t_of == t) { d = dsc[t]; s = sq[t]; }
-            const int n = nb * 32 + r_of;
-            if (n < g.N) yp[(size_t)t_of * g.N + n] = ((float)(part - s) * d) * beta;
-        }
-        par ^= 1;
-        if (it + 1 < i1) {
-#pragma unroll
-            for (int u = 0; u < GV_SB_PER_WAVE; ++u) wreg[u] = wnext[u];
-        }
+        it = p_end;
     }
 }
 
