@@ -31,6 +31,11 @@ INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, TOP/s
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
 
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by what
+# the same counters read for a copy kernel of known size); null until measured for the kernel as it stands.
+ROOFLINE_TRAFFIC = {"encoder-2b": None, "prefill-3b": None}
+
+
 def linear_macs_per_token(shape) -> int:
     dq = shape.n_heads * shape.head_dim
     dkv = shape.n_kv_heads * shape.head_dim
@@ -128,20 +133,28 @@ def main() -> int:
     B.brl_timing_enable(False)
     classes = {}
     for kc, name in enumerate(B.KERNEL_CLASSES):
-        n, ms = B.brl_timing_read(kc)
-        classes[name] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps}
-    gemm = classes["gemm"]
+        n, ms, ops = B.brl_timing_read_ops(kc)
+        classes[name] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
+                         "int8_ops_per_step": ops / args.steps}
     macs_tok = linear_macs_per_token(shape) * n_layers // shape.n_layers
     ops_step = 2.0 * macs_tok * Bn * S
+    # dominant kernel: the 128 x 256-tile int8 MFMA GEMM; its algorithmic ops per launch are the
+    # 2 M N K of the products it ran (counted by the library per launch), over its own event time
+    gemm = classes["gemm"]
     gemm_launches = max(gemm["launches_per_step"], 1)
     gemm_avg_ms = gemm["ms_per_step"] / gemm_launches
-    ops_per_launch = ops_step / gemm_launches
+    ops_per_launch = gemm["int8_ops_per_step"] / gemm_launches
     achieved_tops = ops_per_launch / (gemm_avg_ms * 1e-3) / 1e12 if gemm_avg_ms > 0 else 0.0
-    roofline = {"bound": "mfma", "kernel": "gemm_lds_kernel<2,2,2,4> (int8 MFMA BitLinear)",
+    all_gemm_ms = gemm["ms_per_step"] + classes["gemm_narrow"]["ms_per_step"]
+    all_gemm_ops = gemm["int8_ops_per_step"] + classes["gemm_narrow"]["int8_ops_per_step"]
+    roofline = {"bound": "mfma", "kernel": "gemm_lds_kernel<2,2,2,4> (int8 MFMA BitLinear, 128x256 tile)",
                 "achieved": round(achieved_tops, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                "frac": round(achieved_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                "frac": round(achieved_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": ROOFLINE_TRAFFIC.get(args.workload),
                 "avg_launch_ms": round(gemm_avg_ms, 5), "launches_per_step": gemm_launches,
-                "ops_per_launch": ops_per_launch}
+                "ops_per_launch": ops_per_launch,
+                "all_bitlinear_gemms": {"ms_per_step": round(all_gemm_ms, 4),
+                                        "tops": round(all_gemm_ops / (all_gemm_ms * 1e-3) / 1e12, 2) if all_gemm_ms > 0 else 0.0,
+                                        "ops_counted_vs_analytic": round(all_gemm_ops / ops_step, 6)}}
 
     # ---- optional extra leg: the same batch as concurrent micro-batches on separate streams
     concurrent = None

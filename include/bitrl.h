@@ -233,14 +233,18 @@ int policy_value_head(const brl_head* head /* HOST */, const float* h, int B,
  * ------------------------------------------------------------------------ */
 #define BRL_KC_QUANTIZE_WEIGHTS 0
 #define BRL_KC_ACT_QUANT        1   /* activation quantisation incl. fused norm / GLU */
-#define BRL_KC_GEMM             2   /* int8 MFMA BitLinear */
+#define BRL_KC_GEMM             2   /* int8 MFMA BitLinear, 128 x 256 workgroup tile (the many-token kernel) */
 #define BRL_KC_GEMV             3   /* 1..4 token BitLinear */
 #define BRL_KC_ATTENTION        4
 #define BRL_KC_OTHER            5   /* embedding, pooling, heads, fills */
-#define BRL_KC_COUNT            6
+#define BRL_KC_GEMM_NARROW      6   /* int8 MFMA BitLinear, 128 x 128 tile and the few-token kernels */
+#define BRL_KC_COUNT            7
 
 int brl_timing_enable(int on);
 int brl_timing_read(int kernel_class, long long* launches, double* total_ms);
+/* Same, and also the int8 operations (2 per multiply-accumulate, padding excluded) of the
+ * launches read; 0 for classes that are not matrix products. */
+int brl_timing_read_ops(int kernel_class, long long* launches, double* total_ms, double* int8_ops);
 
 #ifdef __cplusplus
 }

@@ -90,6 +90,7 @@ _SIGNATURES = {
                                   c_void_p, c_size_t, c_void_p]),
     "brl_timing_enable": (c_int, [c_int]),
     "brl_timing_read": (c_int, [c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
+    "brl_timing_read_ops": (c_int, [c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
 }
 
 EXPORTS = tuple(_SIGNATURES)
@@ -211,8 +212,9 @@ def policy_value_head(head: brl_head, h: torch.Tensor, B: int, logits: torch.Ten
                                    workspace.numel() * workspace.element_size(), _stream()))
 
 
-BRL_KC_QUANTIZE_WEIGHTS, BRL_KC_ACT_QUANT, BRL_KC_GEMM, BRL_KC_GEMV, BRL_KC_ATTENTION, BRL_KC_OTHER = range(6)
-KERNEL_CLASSES = ("quantize_weights", "act_quant", "gemm", "gemv", "attention", "other")
+BRL_KC_QUANTIZE_WEIGHTS, BRL_KC_ACT_QUANT, BRL_KC_GEMM, BRL_KC_GEMV, BRL_KC_ATTENTION, BRL_KC_OTHER, \
+    BRL_KC_GEMM_NARROW = range(7)
+KERNEL_CLASSES = ("quantize_weights", "act_quant", "gemm", "gemv", "attention", "other", "gemm_narrow")
 
 
 def brl_timing_enable(on: bool) -> None:
@@ -223,6 +225,12 @@ def brl_timing_read(kernel_class: int):
     n, ms = C.c_longlong(0), C.c_double(0.0)
     _check(lib().brl_timing_read(kernel_class, C.byref(n), C.byref(ms)))
     return n.value, ms.value
+
+
+def brl_timing_read_ops(kernel_class: int):
+    n, ms, ops = C.c_longlong(0), C.c_double(0.0), C.c_double(0.0)
+    _check(lib().brl_timing_read_ops(kernel_class, C.byref(n), C.byref(ms), C.byref(ops)))
+    return n.value, ms.value, ops.value
 
 
 # ------------------------------------------------ struct builders (marshalling)

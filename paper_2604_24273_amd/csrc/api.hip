@@ -31,6 +31,7 @@ std::mutex g_tm_mu;
 bool g_tm_on = false;
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_tm_events[BRL_KC_COUNT];
 std::vector<hipEvent_t> g_tm_free;
+double g_tm_ops[BRL_KC_COUNT];
 
 hipEvent_t tm_get_event() {
     if (!g_tm_free.empty()) {
@@ -44,13 +45,14 @@ hipEvent_t tm_get_event() {
 }
 }  // namespace
 
-LaunchTimer::LaunchTimer(int kernel_class, hipStream_t s) : stop_(nullptr), s_(s), on_(false) {
+LaunchTimer::LaunchTimer(int kernel_class, hipStream_t s, double int8_ops) : stop_(nullptr), s_(s), on_(false) {
     std::lock_guard<std::mutex> lk(g_tm_mu);
     if (!g_tm_on) return;
     hipEvent_t a = tm_get_event(), b = tm_get_event();
     if (!a || !b) return;
     (void)hipEventRecord(a, s);
     g_tm_events[kernel_class].push_back(std::make_pair(a, b));
+    g_tm_ops[kernel_class] += int8_ops;
     stop_ = b;
     on_ = true;
 }
@@ -299,12 +301,19 @@ int brl_timing_enable(int on) {
 }
 
 int brl_timing_read(int kernel_class, long long* launches, double* total_ms) {
+    double ops = 0.0;
+    return brl_timing_read_ops(kernel_class, launches, total_ms, &ops);
+}
+
+int brl_timing_read_ops(int kernel_class, long long* launches, double* total_ms, double* int8_ops) {
     BRL_REQUIRE(kernel_class >= 0 && kernel_class < BRL_KC_COUNT, "timing_read: unknown class %d", kernel_class);
-    BRL_REQUIRE(launches && total_ms, "timing_read: null pointer");
+    BRL_REQUIRE(launches && total_ms && int8_ops, "timing_read: null pointer");
     std::vector<std::pair<hipEvent_t, hipEvent_t>> evs;
     {
         std::lock_guard<std::mutex> lk(g_tm_mu);
         evs.swap(g_tm_events[kernel_class]);
+        *int8_ops = g_tm_ops[kernel_class];
+        g_tm_ops[kernel_class] = 0.0;
     }
     double sum = 0.0;
     int rc = BRL_OK;

@@ -32,7 +32,7 @@ int hip_fail(hipError_t e, const char* what);
 
 // ---- optional per-launch timing (host): brackets a launch with two events ----
 struct LaunchTimer {
-    LaunchTimer(int kernel_class, hipStream_t s);
+    LaunchTimer(int kernel_class, hipStream_t s, double int8_ops = 0.0);
     ~LaunchTimer();
     LaunchTimer(const LaunchTimer&) = delete;
     LaunchTimer& operator=(const LaunchTimer&) = delete;

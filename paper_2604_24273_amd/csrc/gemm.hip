@@ -45,6 +45,7 @@ struct GemmArgs {
     const float* residual;
     int32_t* acc_dbg;
     int fast_epilogue;       // every segment a multiple of 32 rows, ldy % 4 == 0, no debug tap
+    double ops;              // int8 operations of the product (for the timing hooks)
     int glu;                 // 1: segments are (gate, up) of equal size, interleaved block by block;
                              //    the epilogue emits h = (max(G,0) * max(G,0)) * U, one column per pair
 };
@@ -572,7 +573,7 @@ int launch_direct(GemmArgs& g, hipStream_t s) {
     g.group_m = 4;
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 7) / 8) * 8;
-    LaunchTimer tm(BRL_KC_GEMM, s);
+    LaunchTimer tm(BRL_KC_GEMM_NARROW, s, g.ops);
     hipLaunchKernelGGL((gemm_direct_kernel<TM, TN, WM, WN, WK>), dim3(grid), dim3(256), 0, s, g);
     BRL_LAUNCH_CHECK("gemm_direct_kernel");
     return BRL_OK;
@@ -585,7 +586,7 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
     g.group_m = 4;
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 7) / 8) * 8;
-    LaunchTimer tm(BRL_KC_GEMM, s);
+    LaunchTimer tm(WN == 4 ? BRL_KC_GEMM : BRL_KC_GEMM_NARROW, s, g.ops);
     hipLaunchKernelGGL((gemm_lds_kernel<TM, TN, WM, WN>), dim3(grid), dim3(WM * WN * 64), 0, s, g);
     BRL_LAUNCH_CHECK("gemm_lds_kernel");
     return BRL_OK;
@@ -618,6 +619,7 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
         g.nnb = 2 * w.nb_end[0];
     }
     g.nsb = round_up(K, SBK) / SBK;
+    g.ops = 2.0 * (double)M * (double)w.n_end[w.count - 1] * (double)K;
     g.y = y;
     g.ldy = ldy;
     g.residual = residual;
