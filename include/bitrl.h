@@ -200,6 +200,26 @@ int encoder_forward(const brl_encoder* enc /* HOST */, const int32_t* ids, int B
                     void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The same encoder on states of different lengths stored back to back, with
+ * no padding (Sec. 5.2: a serialised state is 15 to 40 tokens): state b owns
+ * the token rows cu_seqlens[b] .. cu_seqlens[b+1]-1, positions count from 0
+ * inside each state, attention never crosses a state boundary, and
+ * h[b] = mean over the state's own positions.  Each state's result equals
+ * what encoder_forward gives for that state alone.
+ *
+ * ids [T] int32 (device), T = cu_seqlens[B]; cu_seqlens [B+1] int32, given
+ * twice: a DEVICE copy read by the kernels and a HOST copy used to check the
+ * lengths (cu[0] = 0, 1 <= length <= max_len, else BRL_EINVAL) and to cut the
+ * batch into micro-batches of whole states; max_len bounds every length and
+ * sizes the rotary table.  h [B, d] fp32.
+ * ------------------------------------------------------------------------ */
+size_t brl_encoder_packed_workspace_bytes(const brl_encoder* enc /* HOST */, int B, int T, int max_len);
+int encoder_forward_packed(const brl_encoder* enc /* HOST */, const int32_t* ids,
+                           const int32_t* cu_seqlens /* DEVICE */, const int32_t* cu_seqlens_host /* HOST */,
+                           int B, int max_len, float* h,
+                           void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Policy and value heads (Sec. 3.1, Eq. 3; fp32 parameters, Appendix table):
  * each is an MLP, out = W_L act(... act(W_1 h + b_1) ...) + b_L, accumulated
  * in fp64 and rounded to fp32 once at the output.  The softmax over the

@@ -85,6 +85,9 @@ _SIGNATURES = {
     "brl_encoder_workspace_bytes": (c_size_t, [C.POINTER(brl_encoder), c_int, c_int]),
     "encoder_forward": (c_int, [C.POINTER(brl_encoder), c_void_p, c_int, c_int, c_void_p, c_void_p,
                                 c_void_p, c_size_t, c_void_p]),
+    "brl_encoder_packed_workspace_bytes": (c_size_t, [C.POINTER(brl_encoder), c_int, c_int, c_int]),
+    "encoder_forward_packed": (c_int, [C.POINTER(brl_encoder), c_void_p, c_void_p, c_void_p, c_int, c_int, c_void_p,
+                                       c_void_p, c_size_t, c_void_p]),
     "brl_head_workspace_bytes": (c_size_t, [C.POINTER(brl_head), c_int]),
     "policy_value_head": (c_int, [C.POINTER(brl_head), c_void_p, c_int, c_void_p, c_void_p,
                                   c_void_p, c_size_t, c_void_p]),
@@ -200,6 +203,18 @@ def encoder_forward(enc: brl_encoder, ids: torch.Tensor, B: int, S: int, lengths
                     h: torch.Tensor, workspace: torch.Tensor) -> None:
     _check(lib().encoder_forward(C.byref(enc), _ptr(ids), B, S, _ptr(lengths), _ptr(h), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_encoder_packed_workspace_bytes(enc: brl_encoder, B: int, T: int, max_len: int) -> int:
+    return lib().brl_encoder_packed_workspace_bytes(C.byref(enc), B, T, max_len)
+
+
+def encoder_forward_packed(enc: brl_encoder, ids: torch.Tensor, cu_seqlens: torch.Tensor, cu_seqlens_host,
+                           B: int, max_len: int, h: torch.Tensor, workspace: torch.Tensor) -> None:
+    """cu_seqlens: int32 device tensor [B+1]; cu_seqlens_host: contiguous int32 numpy array with the same values."""
+    _check(lib().encoder_forward_packed(C.byref(enc), _ptr(ids), _ptr(cu_seqlens), cu_seqlens_host.ctypes.data, B, max_len,
+                                        _ptr(h), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream()))
 
 
 def brl_head_workspace_bytes(head: brl_head, B: int) -> int:

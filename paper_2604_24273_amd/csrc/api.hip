@@ -466,6 +466,62 @@ size_t brl_encoder_workspace_bytes(const brl_encoder* enc, int B, int S) {
     return encoder_ws_layout(enc, B, S).total;
 }
 
+namespace {
+
+// One micro-batch through embedding, all layers, final norm and pooling.  nb states, Mt token rows
+// (nb * S in the uniform layout), S = rows per state or the bound on the state lengths.
+int run_encoder_microbatch(const brl_encoder* enc, const EncWs& L, char* base, const int32_t* ids, int nb, int Mt, int S,
+                           int rows_cap, const SeqMap& sm, const int32_t* lengths, float* h_out, hipStream_t s) {
+    const int d = enc->d, f = enc->f, dh = enc->head_dim;
+    const int dq = enc->n_heads * dh, dkv = enc->n_kv_heads * dh;
+    float* x = reinterpret_cast<float*>(base + L.x_off);
+    float* big = reinterpret_cast<float*>(base + L.big_off);
+    float* cos_t = reinterpret_cast<float*>(base + L.cos_off);
+    float* sin_t = reinterpret_cast<float*>(base + L.sin_off);
+    float* rinv = reinterpret_cast<float*>(base + L.rinv_off);
+    Carver c(base + L.act_off);
+    int kmax = d > dq ? d : dq;
+    if (f > kmax) kmax = f;
+    const ActBuf act = take_actbuf(c, rows_cap, kmax);
+    float* qkv = big;
+    float* att = big + (size_t)Mt * L.big_ld_qkv;
+    if (int rc = launch_embed(enc->embedding, ids, Mt, d, enc->vocab, x, s)) return rc;
+    for (int l = 0; l < enc->n_layers; ++l) {
+        const brl_layer_weights& w = enc->layers[l];
+        QuantArgs qa;
+        memset(&qa, 0, sizeof(qa));
+        qa.x = x; qa.x_dtype = BRL_F32; qa.gain = w.attn_norm_g; qa.eps_norm = enc->eps_norm; qa.eps_act = enc->eps_act;
+        qa.M = Mt; qa.K = d;
+        if (int rc = launch_act_quant(qa, act, s)) return rc;
+        WeightSegs wqkv;
+        memset(&wqkv, 0, sizeof(wqkv));
+        add_seg(wqkv, w.wq_packed, w.wq_beta, dq);
+        add_seg(wqkv, w.wk_packed, w.wk_beta, dkv);
+        add_seg(wqkv, w.wv_packed, w.wv_beta, dkv);
+        if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, 0, s)) return rc;
+        if (enc->attn_precision == BRL_ATTN_MFMA) {
+            if (int rc = launch_attention_mfma(qkv, L.big_ld_qkv, nb, S, sm, enc->n_heads, enc->n_kv_heads, dh, cos_t,
+                                               sin_t, base + L.frag_off, att, s))
+                return rc;
+        } else {
+            if (int rc = launch_attention_f32(qkv, L.big_ld_qkv, nb, S, sm, enc->n_heads, enc->n_kv_heads, dh, cos_t,
+                                              sin_t, att, s))
+                return rc;
+        }
+        QuantArgs qo;
+        memset(&qo, 0, sizeof(qo));
+        qo.x = att; qo.x_dtype = BRL_F32; qo.gain = w.attn_subln_g; qo.eps_norm = enc->eps_norm; qo.eps_act = enc->eps_act;
+        qo.M = Mt; qo.K = dq;
+        if (int rc = launch_act_quant(qo, act, s)) return rc;
+        const WeightSegs wo = one_seg(w.wo_packed, w.wo_beta, d);
+        if (int rc = launch_gemm(act, wo, Mt, d, dq, x, d, x, nullptr, 0, s)) return rc;
+        if (int rc = run_ffn(&w.ffn, x, x, BRL_F32, Mt, d, f, enc->eps_norm, enc->eps_act, x, act, big, act, s)) return rc;
+    }
+    return launch_final_pool(x, enc->final_norm_g, nb, S, Mt, d, lengths, sm, enc->eps_norm, rinv, h_out, s);
+}
+
+}  // namespace
+
 int encoder_forward(const brl_encoder* enc, const int32_t* ids, int B, int S, const int32_t* lengths, float* h,
                     void* workspace, size_t ws_bytes, void* stream) {
     if (int rc = check_encoder(enc)) return rc;
@@ -480,60 +536,100 @@ int encoder_forward(const brl_encoder* enc, const int32_t* ids, int B, int S, co
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* base = static_cast<char*>(workspace);
-    const int d = enc->d, f = enc->f, dh = enc->head_dim;
-    const int dq = enc->n_heads * dh, dkv = enc->n_kv_heads * dh;
-    float* x = reinterpret_cast<float*>(base + L.x_off);
-    float* big = reinterpret_cast<float*>(base + L.big_off);
-    float* cos_t = reinterpret_cast<float*>(base + L.cos_off);
-    float* sin_t = reinterpret_cast<float*>(base + L.sin_off);
-    float* rinv = reinterpret_cast<float*>(base + L.rinv_off);
-    if (int rc = launch_rope_table(cos_t, sin_t, S, dh, enc->rope_theta, s)) return rc;
-
+    if (int rc = launch_rope_table(reinterpret_cast<float*>(base + L.cos_off), reinterpret_cast<float*>(base + L.sin_off), S,
+                                   enc->head_dim, enc->rope_theta, s))
+        return rc;
+    SeqMap uniform;
+    uniform.cu = nullptr;
+    uniform.b0 = 0;
     for (int b0 = 0; b0 < B; b0 += L.states_mb) {
         const int nb = (B - b0 < L.states_mb) ? B - b0 : L.states_mb;
-        const int Mt = nb * S;
-        Carver c(base + L.act_off);
-        int kmax = d > dq ? d : dq;
-        if (f > kmax) kmax = f;
-        const ActBuf act = take_actbuf(c, L.states_mb * S, kmax);
-        float* qkv = big;
-        float* att = big + (size_t)Mt * L.big_ld_qkv;
-        if (int rc = launch_embed(enc->embedding, ids + (size_t)b0 * S, Mt, d, enc->vocab, x, s)) return rc;
-        for (int l = 0; l < enc->n_layers; ++l) {
-            const brl_layer_weights& w = enc->layers[l];
-            QuantArgs qa;
-            memset(&qa, 0, sizeof(qa));
-            qa.x = x; qa.x_dtype = BRL_F32; qa.gain = w.attn_norm_g; qa.eps_norm = enc->eps_norm; qa.eps_act = enc->eps_act;
-            qa.M = Mt; qa.K = d;
-            if (int rc = launch_act_quant(qa, act, s)) return rc;
-            WeightSegs wqkv;
-            memset(&wqkv, 0, sizeof(wqkv));
-            add_seg(wqkv, w.wq_packed, w.wq_beta, dq);
-            add_seg(wqkv, w.wk_packed, w.wk_beta, dkv);
-            add_seg(wqkv, w.wv_packed, w.wv_beta, dkv);
-            if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, 0, s)) return rc;
-            if (enc->attn_precision == BRL_ATTN_MFMA) {
-                if (int rc = launch_attention_mfma(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t,
-                                                   sin_t, base + L.frag_off, att, s))
-                    return rc;
-            } else {
-                if (int rc = launch_attention_f32(qkv, L.big_ld_qkv, nb, S, enc->n_heads, enc->n_kv_heads, dh, cos_t,
-                                                  sin_t, att, s))
-                    return rc;
-            }
-            QuantArgs qo;
-            memset(&qo, 0, sizeof(qo));
-            qo.x = att; qo.x_dtype = BRL_F32; qo.gain = w.attn_subln_g; qo.eps_norm = enc->eps_norm; qo.eps_act = enc->eps_act;
-            qo.M = Mt; qo.K = dq;
-            if (int rc = launch_act_quant(qo, act, s)) return rc;
-            const WeightSegs wo = one_seg(w.wo_packed, w.wo_beta, d);
-            if (int rc = launch_gemm(act, wo, Mt, d, dq, x, d, x, nullptr, 0, s)) return rc;
-            if (int rc = run_ffn(&w.ffn, x, x, BRL_F32, Mt, d, f, enc->eps_norm, enc->eps_act, x, act, big, act, s))
-                return rc;
-        }
-        if (int rc = launch_final_pool(x, enc->final_norm_g, nb, S, d, lengths ? lengths + b0 : nullptr, enc->eps_norm,
-                                       rinv, h + (size_t)b0 * d, s))
+        if (int rc = run_encoder_microbatch(enc, L, base, ids + (size_t)b0 * S, nb, nb * S, S, L.states_mb * S, uniform,
+                                            lengths ? lengths + b0 : nullptr, h + (size_t)b0 * enc->d, s))
             return rc;
+    }
+    return BRL_OK;
+}
+
+namespace {
+
+constexpr int PACK_MB_STATES = 2048;      // states per micro-batch of the packed layout
+
+// Packed layout: micro-batches hold at most ENC_MB_TOKENS token rows (at least one whole state) and
+// at most PACK_MB_STATES states.
+EncWs encoder_packed_ws_layout(const brl_encoder* e, int B, int T, int max_len) {
+    EncWs L;
+    memset(&L, 0, sizeof(L));
+    L.states_mb = B < PACK_MB_STATES ? B : PACK_MB_STATES;
+    size_t Mt = (size_t)(T < ENC_MB_TOKENS ? T : ENC_MB_TOKENS);
+    if (Mt < (size_t)max_len) Mt = (size_t)max_len;
+    const int dq = e->n_heads * e->head_dim, dkv = e->n_kv_heads * e->head_dim;
+    int kmax = e->d;
+    if (dq > kmax) kmax = dq;
+    if (e->f > kmax) kmax = e->f;
+    L.x_off = 0;
+    L.act_off = round_up_sz(Mt * e->d * 4, ALIGN);
+    L.big_off = L.act_off + actbuf_bytes((int)Mt, kmax);
+    const size_t attn_cols = (size_t)dq + 2 * dkv + dq;
+    const size_t big_cols = attn_cols > (size_t)e->f ? attn_cols : (size_t)e->f;
+    L.cos_off = L.big_off + round_up_sz(Mt * big_cols * 4, ALIGN);
+    const size_t tbl = round_up_sz((size_t)max_len * (e->head_dim / 2) * 4, ALIGN);
+    L.sin_off = L.cos_off + tbl;
+    L.rinv_off = L.sin_off + tbl;
+    L.frag_off = L.rinv_off + round_up_sz(Mt * 4, ALIGN);
+    L.total = L.frag_off +
+              round_up_sz(attention_mfma_ws_bytes(L.states_mb, max_len, e->n_heads, e->n_kv_heads, e->head_dim), ALIGN);
+    L.big_ld_qkv = dq + 2 * dkv;
+    return L;
+}
+
+}  // namespace
+
+size_t brl_encoder_packed_workspace_bytes(const brl_encoder* enc, int B, int T, int max_len) {
+    if (!enc || B < 1 || T < B || max_len < 1 || enc->d < 1 || enc->f < 1 || enc->head_dim < 2) return 0;
+    return encoder_packed_ws_layout(enc, B, T, max_len).total;
+}
+
+int encoder_forward_packed(const brl_encoder* enc, const int32_t* ids, const int32_t* cu_seqlens,
+                           const int32_t* cu_seqlens_host, int B, int max_len, float* h, void* workspace,
+                           size_t ws_bytes, void* stream) {
+    if (int rc = check_encoder(enc)) return rc;
+    BRL_REQUIRE(ids && cu_seqlens && cu_seqlens_host && h && workspace && aligned16(h) && aligned16(workspace),
+                "encoder_forward_packed: null or misaligned pointer");
+    BRL_REQUIRE(B >= 1 && max_len >= 1 && max_len <= ENC_MB_TOKENS, "encoder_forward_packed: B = %d, max_len = %d", B,
+                max_len);
+    BRL_REQUIRE(enc->eps_act > 0.f && enc->eps_norm >= 0.f && enc->rope_theta > 0.f,
+                "encoder_forward_packed: bad eps / theta");
+    BRL_REQUIRE(cu_seqlens_host[0] == 0, "encoder_forward_packed: cu_seqlens[0] must be 0");
+    for (int b = 0; b < B; ++b) {
+        const long long n = (long long)cu_seqlens_host[b + 1] - cu_seqlens_host[b];
+        BRL_REQUIRE(n >= 1 && n <= max_len, "encoder_forward_packed: state %d has %lld tokens (1..%d allowed)", b, n,
+                    max_len);
+    }
+    const int T = cu_seqlens_host[B];
+    const EncWs L = encoder_packed_ws_layout(enc, B, T, max_len);
+    if (ws_bytes < L.total) {
+        set_error("encoder_forward_packed: workspace %zu < %zu", ws_bytes, L.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    if (int rc = launch_rope_table(reinterpret_cast<float*>(base + L.cos_off), reinterpret_cast<float*>(base + L.sin_off),
+                                   max_len, enc->head_dim, enc->rope_theta, s))
+        return rc;
+    const int rows_cap = (T < ENC_MB_TOKENS ? T : ENC_MB_TOKENS) < max_len ? max_len : (T < ENC_MB_TOKENS ? T : ENC_MB_TOKENS);
+    int b0 = 0;
+    while (b0 < B) {
+        int b1 = b0 + 1;                   // a micro-batch takes whole states while they fit
+        while (b1 < B && b1 - b0 < L.states_mb && cu_seqlens_host[b1 + 1] - cu_seqlens_host[b0] <= ENC_MB_TOKENS) ++b1;
+        SeqMap sm;
+        sm.cu = cu_seqlens;
+        sm.b0 = b0;
+        const int Mt = cu_seqlens_host[b1] - cu_seqlens_host[b0];
+        if (int rc = run_encoder_microbatch(enc, L, base, ids + cu_seqlens_host[b0], b1 - b0, Mt, max_len, rows_cap, sm,
+                                            nullptr, h + (size_t)b0 * enc->d, s))
+            return rc;
+        b0 = b1;
     }
     return BRL_OK;
 }

@@ -18,7 +18,8 @@ constexpr int AT_KB = 32;
 struct AttnArgs {
     const float* qkv;     // [B*S, ld]: q heads | k heads | v heads
     int ld;
-    int B, S, Hq, Hkv;
+    int B, S, Hq, Hkv;    // S: rows per state, or the bound on the state lengths with a SeqMap
+    SeqMap sm;
     const float* cos_t;   // [S, dh/2]
     const float* sin_t;
     float* out;           // [B*S, Hq*dh]
@@ -49,17 +50,19 @@ __global__ __launch_bounds__(AT_THREADS) void attention_f32_kernel(AttnArgs a) {
     const int b = blockIdx.x / (chunks * a.Hkv);
     const int rho0 = c * AT_THREADS;
     const int rho1 = min(R, rho0 + AT_THREADS) - 1;
-    const int p_hi = (rho0 / a.S != rho1 / a.S) ? a.S - 1 : rho1 % a.S;
+    const int len = seq_len(a.sm, b, a.S);
+    const size_t row0 = (size_t)seq_row0(a.sm, b, a.S);
+    const int p_hi = min((rho0 / a.S != rho1 / a.S) ? a.S - 1 : rho1 % a.S, len - 1);
 
     const int rho = rho0 + threadIdx.x;
-    const bool live = rho < R;
+    const bool live = rho < R && rho % a.S < len;
     const int h = j * group + (live ? rho / a.S : 0);
     const int p = live ? rho % a.S : 0;
     const int dq = a.Hq * DH, dkv = a.Hkv * DH;
 
     float q[DH], o[DH];
     {
-        const float* qp = a.qkv + ((size_t)b * a.S + p) * a.ld + (size_t)h * DH;
+        const float* qp = a.qkv + (row0 + p) * a.ld + (size_t)h * DH;
         const float* cp = a.cos_t + (size_t)p * HALF;
         const float* sp = a.sin_t + (size_t)p * HALF;
 #pragma unroll
@@ -74,7 +77,7 @@ __global__ __launch_bounds__(AT_THREADS) void attention_f32_kernel(AttnArgs a) {
     }
     float m_run = -INFINITY, l_run = 0.f;
 
-    const int n_blocks = p_hi / AT_KB + 1;
+    const int n_blocks = p_hi < 0 ? 0 : p_hi / AT_KB + 1;
     for (int kb = 0; kb < n_blocks; ++kb) {
         __syncthreads();
         // stage K (rotated) and V of keys kb*32 .. kb*32+31
@@ -82,8 +85,8 @@ __global__ __launch_bounds__(AT_THREADS) void attention_f32_kernel(AttnArgs a) {
             const int jj = e / HALF, i = e % HALF;
             const int kp = kb * AT_KB + jj;
             float k1 = 0.f, k2 = 0.f, v1 = 0.f, v2 = 0.f, cs = 1.f, sn = 0.f;
-            if (kp < a.S) {
-                const float* row = a.qkv + ((size_t)b * a.S + kp) * a.ld;
+            if (kp < len) {
+                const float* row = a.qkv + (row0 + kp) * a.ld;
                 k1 = row[dq + j * DH + i];
                 k2 = row[dq + j * DH + i + HALF];
                 v1 = row[dq + dkv + j * DH + i];
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(AT_THREADS) void attention_f32_kernel(AttnArgs a) {
     }
     if (live) {
         const float inv = 1.0f / l_run;
-        float* op = a.out + ((size_t)b * a.S + p) * dq + (size_t)h * DH;
+        float* op = a.out + (row0 + p) * dq + (size_t)h * DH;
 #pragma unroll
         for (int d = 0; d < DH; ++d) op[d] = o[d] * inv;
     }
@@ -160,10 +163,10 @@ int launch_rope_table(float* cos_t, float* sin_t, int S, int head_dim, float the
     return BRL_OK;
 }
 
-int launch_attention_f32(const float* qkv, int ld, int B, int S, int n_heads, int n_kv_heads, int head_dim,
-                         const float* cos_t, const float* sin_t, float* out, hipStream_t s) {
+int launch_attention_f32(const float* qkv, int ld, int B, int S, const SeqMap& sm, int n_heads, int n_kv_heads,
+                         int head_dim, const float* cos_t, const float* sin_t, float* out, hipStream_t s) {
     AttnArgs a;
-    a.qkv = qkv; a.ld = ld; a.B = B; a.S = S; a.Hq = n_heads; a.Hkv = n_kv_heads;
+    a.qkv = qkv; a.ld = ld; a.B = B; a.S = S; a.sm = sm; a.Hq = n_heads; a.Hkv = n_kv_heads;
     a.cos_t = cos_t; a.sin_t = sin_t; a.out = out;
     a.scale = (float)(1.0 / sqrt((double)head_dim));
     const int group = n_heads / n_kv_heads;

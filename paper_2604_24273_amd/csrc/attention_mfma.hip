@@ -36,7 +36,8 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct PackArgs {
     const float* qkv;     // [B*S, ld]: q heads | k heads | v heads
-    int ld, B, S, NRB, Hq, Hkv, dh;
+    int ld, B, S, NRB, Hq, Hkv, dh;   // S: rows per state, or the bound on the state lengths with a SeqMap
+    SeqMap sm;
     const float* cos_t;   // [S, dh/2]
     const float* sin_t;
     uint4* KVF;           // [B][Hkv][NRB][ K: [KS][hi,lo] | V: [DB][2][hi,lo] ][64 lanes]
@@ -134,8 +135,9 @@ __global__ __launch_bounds__(256) void attn_pack_kernel(PackArgs a) {
     const int b = blockIdx.x / (a.Hkv * a.NRB);
     const int half = a.dh / 2;
     const int dq = a.Hq * a.dh, dkv = a.Hkv * a.dh;
-    const int n_valid = min(32, a.S - rb * 32);
-    const float* rows = a.qkv + ((size_t)b * a.S + rb * 32) * a.ld;
+    const int n_valid = min(32, seq_len(a.sm, b, a.S) - rb * 32);
+    if (n_valid <= 0) return;             // this state has no such key block (never read either)
+    const float* rows = a.qkv + ((size_t)seq_row0(a.sm, b, a.S) + rb * 32) * a.ld;
     uint4* dst = a.KVF + ((size_t)(b * a.Hkv + hd) * a.NRB + rb) * KVFR * 64;
 
     // k head: each wavefront stages a quarter of the rows, then writes a quarter of the fragments
@@ -174,6 +176,7 @@ struct FragArgs {
     float qscale;         // softmax scale in log2 units, folded into q
     const uint4* KVF;
     int B, S, NRB, Hq, Hkv, dh;
+    SeqMap sm;
     int n_work;           // B * Hkv * chunks
     float* out;           // [B*S, Hq*dh]
 };
@@ -264,10 +267,14 @@ __global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
     const int c = chunks - 1 - w % chunks;
     const int j = (w / chunks) % a.Hkv;
     const int b = w / (chunks * a.Hkv);
+    const int len = seq_len(a.sm, b, a.S);
+    const int nrb = (len + 31) >> 5;                  // query / key blocks this state really has
+    const size_t row0 = (size_t)seq_row0(a.sm, b, a.S);
     const int u0 = 4 * c, u1 = min(U, u0 + 4) - 1;
-    const int kb_max = (u0 / a.NRB != u1 / a.NRB) ? a.NRB - 1 : u1 % a.NRB;
+    const int kb_max = min((u0 / a.NRB != u1 / a.NRB) ? a.NRB - 1 : u1 % a.NRB, nrb - 1);
+    if (kb_max < 0 || (u0 / a.NRB == u1 / a.NRB && u0 % a.NRB >= nrb)) return;   // none of the four units exists
     const int u = u0 + wave;
-    const bool live = u < U;
+    const bool live = u < U && u % a.NRB < nrb;
     const int head = j * group + (live ? u / a.NRB : 0);
     const int qb = live ? u % a.NRB : -1;
 
@@ -278,8 +285,8 @@ __global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
         char* region = reinterpret_cast<char*>(wave < 2 ? stage0 : stage1) + (wave & 1) * (128 * DHP);
         if (live) {
             const int half = a.dh / 2;
-            stage_rope_rows<DHP, VW>(a.qkv + ((size_t)b * a.S + qb * 32) * a.ld + head * a.dh, a.ld,
-                                     min(32, a.S - qb * 32), a.cos_t + (size_t)qb * 32 * half,
+            stage_rope_rows<DHP, VW>(a.qkv + (row0 + qb * 32) * a.ld + head * a.dh, a.ld,
+                                     min(32, len - qb * 32), a.cos_t + (size_t)qb * 32 * half,
                                      a.sin_t + (size_t)qb * 32 * half, a.dh, a.qscale, region, lane);
         }
         __syncthreads();
@@ -318,10 +325,10 @@ __global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const int pos = qpos;
-    if (live && pos < a.S) {
+    if (live && pos < len) {
         const float inv = 1.0f / l_tot;
         const int h = lane >> 5;
-        float* op = a.out + ((size_t)b * a.S + pos) * ((size_t)a.Hq * a.dh) + (size_t)head * a.dh;
+        float* op = a.out + (row0 + pos) * ((size_t)a.Hq * a.dh) + (size_t)head * a.dh;
 #pragma unroll
         for (int r = 0; r < DB; ++r)
 #pragma unroll
@@ -358,8 +365,8 @@ void launch_pair(const PackArgs& p, const FragArgs& f, dim3 pgrid, dim3 agrid, h
 
 }  // namespace
 
-int launch_attention_mfma(const float* qkv, int ld, int B, int S, int n_heads, int n_kv_heads, int head_dim,
-                          const float* cos_t, const float* sin_t, void* frag_ws, float* out, hipStream_t s) {
+int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& sm, int n_heads, int n_kv_heads,
+                          int head_dim, const float* cos_t, const float* sin_t, void* frag_ws, float* out, hipStream_t s) {
     if (head_dim % 4 != 0 || head_dim > 128 || ld % 4 != 0) {
         set_error("attention: head_dim %d must be a multiple of 4, at most 128 (row stride %d a multiple of 4)",
                   head_dim, ld);
@@ -371,12 +378,14 @@ int launch_attention_mfma(const float* qkv, int ld, int B, int S, int n_heads, i
     const int chunks = (group * nrb + 3) / 4;
     PackArgs p;
     p.qkv = qkv; p.ld = ld; p.B = B; p.S = S; p.NRB = nrb; p.Hq = n_heads; p.Hkv = n_kv_heads; p.dh = head_dim;
+    p.sm = sm;
     p.cos_t = cos_t; p.sin_t = sin_t;
     p.KVF = static_cast<uint4*>(frag_ws);
     FragArgs f;
     f.qkv = qkv; f.ld = ld; f.cos_t = cos_t; f.sin_t = sin_t;
     f.qscale = (float)(1.0 / sqrt((double)head_dim)) * 1.4426950408889634f;
     f.KVF = p.KVF; f.B = B; f.S = S; f.NRB = nrb; f.Hq = n_heads; f.Hkv = n_kv_heads; f.dh = head_dim;
+    f.sm = sm;
     f.n_work = B * n_kv_heads * chunks;
     f.out = out;
     const dim3 pgrid((unsigned)((size_t)B * nrb * n_kv_heads));

@@ -118,15 +118,30 @@ int launch_gemv_batch(const void* const* packed, const float* const* beta, int N
                       int x_dtype, int M, float eps_act, float* const* y, int count, hipStream_t s);
 
 // attention, embedding, pooling, heads
+// Where the rows of state b of a micro-batch live.  cu == nullptr: every state has S rows, state b
+// starts at row b * S.  Otherwise cu holds cumulative state lengths of the whole call; the micro-batch
+// starts at state b0 and its rows are counted from cu[b0]; S then only bounds the lengths.
+struct SeqMap {
+    const int32_t* cu;
+    int b0;
+};
+__device__ inline int seq_row0(const SeqMap& m, int b, int S) { return m.cu ? m.cu[m.b0 + b] - m.cu[m.b0] : b * S; }
+__device__ inline int seq_len(const SeqMap& m, int b, int S) {
+    if (!m.cu) return S;
+    const int n = m.cu[m.b0 + b + 1] - m.cu[m.b0 + b];
+    return n < 0 ? 0 : (n > S ? S : n);
+}
+
 int launch_rope_table(float* cos_t, float* sin_t, int S, int head_dim, float theta, hipStream_t s);
-int launch_attention_f32(const float* qkv, int ld, int B, int S, int n_heads, int n_kv_heads, int head_dim,
-                         const float* cos_t, const float* sin_t, float* out, hipStream_t s);
+int launch_attention_f32(const float* qkv, int ld, int B, int S, const SeqMap& sm, int n_heads, int n_kv_heads,
+                         int head_dim, const float* cos_t, const float* sin_t, float* out, hipStream_t s);
 size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim);
-int launch_attention_mfma(const float* qkv, int ld, int B, int S, int n_heads, int n_kv_heads, int head_dim,
-                          const float* cos_t, const float* sin_t, void* frag_ws, float* out, hipStream_t s);
+int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& sm, int n_heads, int n_kv_heads,
+                          int head_dim, const float* cos_t, const float* sin_t, void* frag_ws, float* out, hipStream_t s);
 int launch_embed(const uint16_t* table, const int32_t* ids, int M, int d, int vocab, float* x, hipStream_t s);
-int launch_final_pool(const float* x, const float* gain, int B, int S, int d, const int32_t* lengths,
-                      float eps_norm, float* rinv, float* h, hipStream_t s);
+// M rows in all; lengths (or nullptr) applies to the uniform layout only
+int launch_final_pool(const float* x, const float* gain, int B, int S, int M, int d, const int32_t* lengths,
+                      const SeqMap& sm, float eps_norm, float* rinv, float* h, hipStream_t s);
 int launch_mlp_layer(const double* in64, const float* in32, const float* W, const float* b, int B, int in_dim,
                      int out_dim, int act, double* out64, float* out32, hipStream_t s);
 int launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -69,16 +69,17 @@ __global__ __launch_bounds__(256) void row_rinv_kernel(const float* __restrict__
 
 // h[b, c] = fp32( sum_{s < len_b} fp64((x[b,s,c] * rinv[b,s]) * g[c]) / len_b ), positions in order
 __global__ void pool_kernel(const float* __restrict__ x, const float* __restrict__ rinv, const float* __restrict__ gain,
-                            int B, int S, int d, const int32_t* __restrict__ lengths, float* __restrict__ h) {
+                            int B, int S, int d, const int32_t* __restrict__ lengths, SeqMap sm, float* __restrict__ h) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)B * d) return;
     const int b = (int)(idx / d), c = (int)(idx % d);
-    int len = lengths ? lengths[b] : S;
+    int len = sm.cu ? seq_len(sm, b, S) : (lengths ? lengths[b] : S);
     len = len < 1 ? 1 : (len > S ? S : len);
+    const size_t m0 = (size_t)seq_row0(sm, b, S);
     const float g = gain[c];
     double acc = 0.0;
     for (int s = 0; s < len; ++s) {
-        const size_t m = (size_t)b * S + s;
+        const size_t m = m0 + s;
         const float v = (x[m * d + c] * rinv[m]) * g;
         acc += (double)v;
     }
@@ -141,14 +142,13 @@ int launch_embed(const uint16_t* table, const int32_t* ids, int M, int d, int vo
     return BRL_OK;
 }
 
-int launch_final_pool(const float* x, const float* gain, int B, int S, int d, const int32_t* lengths, float eps_norm,
-                      float* rinv, float* h, hipStream_t s) {
-    const int M = B * S;
+int launch_final_pool(const float* x, const float* gain, int B, int S, int M, int d, const int32_t* lengths,
+                      const SeqMap& sm, float eps_norm, float* rinv, float* h, hipStream_t s) {
     LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(row_rinv_kernel, dim3((M + 3) / 4), dim3(256), 0, s, x, M, d, eps_norm, rinv);
     BRL_LAUNCH_CHECK("row_rinv_kernel");
     const size_t n = (size_t)B * d;
-    hipLaunchKernelGGL(pool_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, rinv, gain, B, S, d, lengths, h);
+    hipLaunchKernelGGL(pool_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, rinv, gain, B, S, d, lengths, sm, h);
     BRL_LAUNCH_CHECK("pool_kernel");
     return BRL_OK;
 }

@@ -134,6 +134,20 @@ class EncoderHandle:
         return h
 
 
+    def forward_packed(self, ids_flat: torch.Tensor, cu_seqlens_host: np.ndarray, max_len: Optional[int] = None) -> torch.Tensor:
+        """States of different lengths stored back to back: ids_flat [T] int32 on the GPU, cu_seqlens_host [B+1]."""
+        cu = np.ascontiguousarray(cu_seqlens_host, dtype=np.int32)
+        b = cu.shape[0] - 1
+        if max_len is None:
+            max_len = int(np.max(np.diff(cu)))
+        need = B.brl_encoder_packed_workspace_bytes(self.struct, b, int(cu[-1]), max_len)
+        self.ws = Workspace(need) if self.ws is None else self.ws.ensure(need)
+        h = torch.empty((b, self.shape.d), dtype=torch.float32, device=DEV)
+        cu_dev = torch.from_numpy(cu).to(DEV)
+        B.encoder_forward_packed(self.struct, ids_flat, cu_dev, cu, b, max_len, h, self.ws.buf)
+        return h
+
+
 class HeadHandle:
     def __init__(self, shape: synth.EncoderShape, seed: int = 0, act: int = B.BRL_ACT_TANH):
         pw, pb = synth.head_params(seed, shape, "policy")

@@ -99,6 +99,18 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     enc = B.brl_encoder(0, 256, 4, 2, 48, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
     assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
     assert "head_dim" in err()
+    # packed layout: the host copy of the cumulative lengths is checked before anything is launched
+    enc = B.brl_encoder(0, 256, 4, 2, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
+    import numpy as np
+    for cu, max_len in (([1, 5], 8), ([0, 5, 5], 8), ([0, 9], 8), ([0, 3, 2], 8)):
+        cu_h = np.asarray(cu, dtype=np.int32)
+        rc = lib.encoder_forward_packed(C.byref(enc), fake, fake, cu_h.ctypes.data, len(cu) - 1, max_len, fake, fake,
+                                        1 << 30, None)
+        assert rc == B.BRL_EINVAL, cu
+    cu_h = np.asarray([0, 3, 8], dtype=np.int32)
+    assert lib.encoder_forward_packed(C.byref(enc), fake, fake, cu_h.ctypes.data, 2, 8, fake, fake, 16, None) == B.BRL_ENOSPC
+    assert lib.brl_encoder_packed_workspace_bytes(C.byref(enc), 2, 8, 8) > 0
+    assert lib.brl_encoder_packed_workspace_bytes(C.byref(enc), 2, 1, 8) == 0
     head = B.brl_head()
     assert lib.policy_value_head(C.byref(head), fake, 1, fake, fake, fake, 1 << 20, None) == B.BRL_EINVAL
 

@@ -271,6 +271,41 @@ def test_encoder_small_shapes(kw, b, s, attn):
         assert torch.equal(h_all[1:2], h_one)
 
 
+@pytest.mark.parametrize("kw,lens", [
+    (dict(n_layers=2, d=256, n_heads=4, n_kv_heads=2, head_dim=64, f=384, vocab=512), [15, 40, 1, 32, 33, 27, 64, 31]),
+    (dict(n_layers=2, d=200, n_heads=2, n_kv_heads=2, head_dim=100, f=392, vocab=64), [7, 70, 36]),
+    (dict(n_layers=1, d=256, n_heads=8, n_kv_heads=2, head_dim=32, f=512, vocab=1000), [5]),
+    (dict(n_layers=1, d=128, n_heads=2, n_kv_heads=1, head_dim=128, f=264, vocab=300), [129, 2, 96, 18, 40]),
+])
+@pytest.mark.parametrize("attn", ["mfma", "f32"])
+def test_encoder_packed_variable_length(kw, lens, attn):
+    """States of different lengths stored back to back: every state equals the oracle run on that state
+    alone, and (bit for bit) the padded entry point with `lengths`."""
+    B, R = _mods()
+    print("encoder_forward_packed", kw, lens, attn, flush=True)
+    shape = synth.tiny_shape(**kw)
+    host = []
+    enc = R.EncoderHandle(shape, seed=2, layer_sink=lambda l, w: host.append(w),
+                          attn_precision=B.BRL_ATTN_MFMA if attn == "mfma" else B.BRL_ATTN_F32)
+    cfg, layers = _oracle_encoder(shape, 2, host)
+    emb = synth.embedding_bf16(2, shape)
+    gfin = synth.final_norm_gain(2, shape)
+    nb, smax = len(lens), max(lens)
+    padded = synth.token_ids(2, 500, (nb, smax), shape.vocab)
+    flat = np.concatenate([padded[i, :n] for i, n in enumerate(lens)]).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    h = enc.forward_packed(R.dev(flat), cu)
+    # a larger bound on the lengths changes nothing
+    assert torch.equal(h, enc.forward_packed(R.dev(flat), cu, max_len=smax + 29))
+    h_pad = enc.forward(R.dev(padded), R.dev(np.asarray(lens, dtype=np.int32)))
+    assert torch.equal(h, h_pad)
+    hn = h.cpu().numpy()
+    for i, n in enumerate(lens):
+        h_ref = O.encoder_forward(padded[i:i + 1, :n], emb, layers, gfin, cfg)[0]
+        assert cosine(hn[i], h_ref) >= 0.999, (i, n, cosine(hn[i], h_ref))
+        assert np.abs(hn[i] - h_ref).max() / np.abs(h_ref).max() < 2e-3
+
+
 def test_head_parity_and_variants():
     B, R = _mods()
     for hidden, act in (((256,), B.BRL_ACT_TANH), ((256, 128), B.BRL_ACT_TANH), ((64,), B.BRL_ACT_RELU), ((), B.BRL_ACT_TANH)):
