@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by what
 # the same counters read for a copy kernel of known size); null until measured for the kernel as it stands.
-ROOFLINE_TRAFFIC = {"encoder-2b": None, "prefill-3b": None}
+ROOFLINE_TRAFFIC = {"encoder-2b": None, "prefill-3b": None, "rl-states-2b": None}
 
 
 def linear_macs_per_token(shape) -> int:
@@ -48,9 +48,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", choices=["encoder-2b", "prefill-3b"], default="encoder-2b",
+    ap.add_argument("--workload", choices=["encoder-2b", "prefill-3b", "rl-states-2b"], default="encoder-2b",
                     help="encoder-2b: 64 states x 128 tokens at the 2B shape (the headline); "
-                         "prefill-3b: 1024 states x 512 tokens at the 3B shape (large-batch regime)")
+                         "prefill-3b: 1024 states x 512 tokens at the 3B shape (large-batch regime); "
+                         "rl-states-2b: 1024 states of 15-40 tokens each at the 2B shape, stored back to back")
     ap.add_argument("--states", type=int, default=None)
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="debug only: fewer layers (invalidates the metric)")
@@ -80,10 +81,11 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
 
-    shape = synth.SHAPE_2B if args.workload == "encoder-2b" else synth.SHAPE_3B
+    packed = args.workload == "rl-states-2b"
+    shape = synth.SHAPE_3B if args.workload == "prefill-3b" else synth.SHAPE_2B
     n_layers = shape.n_layers if args.layers is None else args.layers
     Bn = args.states if args.states is not None else (64 if args.workload == "encoder-2b" else 1024)
-    S = args.tokens if args.tokens is not None else (128 if args.workload == "encoder-2b" else 512)
+    S = args.tokens if args.tokens is not None else {"encoder-2b": 128, "prefill-3b": 512, "rl-states-2b": 40}[args.workload]
     want_cpu = not args.no_cpu_baseline
 
     # ---- weights: seeded host draws -> packed on the GPU; the oracle's copy is quantised on the side
@@ -106,13 +108,31 @@ def main() -> int:
     enc = R.EncoderHandle(shape, seed=0, layer_sink=sink, n_layers=n_layers)
     head = R.HeadHandle(shape, seed=0)
     ids_host = synth.token_ids(0, 500, (Bn, S), shape.vocab)
-    ids = R.dev(ids_host)
+    if packed:
+        # states of 15 .. S tokens (the paper's serialised states are 15-40 tokens), stored back to back
+        lens = synth.state_lengths(0, 501, Bn, min(15, S), S)
+        cu_host = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        ids = R.dev(np.concatenate([ids_host[i, :n] for i, n in enumerate(lens)]).astype(np.int32))
+        cu_dev = R.dev(cu_host)
+        tokens_step = int(cu_host[-1])
+        enc.ws = R.Workspace(B.brl_encoder_packed_workspace_bytes(enc.struct, Bn, tokens_step, S))
+        h_buf = torch.empty((Bn, shape.d), dtype=torch.float32, device="cuda")
+
+        def encode():
+            B.encoder_forward_packed(enc.struct, ids, cu_dev, cu_host, Bn, S, h_buf, enc.ws.buf)
+            return h_buf
+    else:
+        lens = np.full((Bn,), S, dtype=np.int32)
+        ids = R.dev(ids_host)
+        tokens_step = Bn * S
+
+        def encode():
+            return enc.forward(ids)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
     def step():
-        h = enc.forward(ids)
-        return head.forward(h)
+        return head.forward(encode())
 
     for _ in range(args.warmup):
         step()
@@ -137,7 +157,7 @@ def main() -> int:
         classes[name] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
                          "int8_ops_per_step": ops / args.steps}
     macs_tok = linear_macs_per_token(shape) * n_layers // shape.n_layers
-    ops_step = 2.0 * macs_tok * Bn * S
+    ops_step = 2.0 * macs_tok * tokens_step
     # dominant kernel: the 128 x 256-tile int8 MFMA GEMM; its algorithmic ops per launch are the
     # 2 M N K of the products it ran (counted by the library per launch), over its own event time
     gemm = classes["gemm"]
@@ -158,7 +178,7 @@ def main() -> int:
 
     # ---- optional extra leg: the same batch as concurrent micro-batches on separate streams
     concurrent = None
-    if args.streams > 1:
+    if args.streams > 1 and not packed:
         parts = [p.contiguous() for p in torch.chunk(ids, args.streams, dim=0)]
         wss = [R.Workspace(B.brl_encoder_workspace_bytes(enc.struct, p.shape[0], S)) for p in parts]
         h_all = torch.empty((Bn, shape.d), dtype=torch.float32, device="cuda")
@@ -192,6 +212,11 @@ def main() -> int:
     if not args.no_gemv:
         gemv = bench_gemv(torch, B, R, synth, args.gemv_calls)
 
+    # ---- one short state per call (the paper's deployment shape: a 15-40 token state per environment step)
+    single = None
+    if not args.no_gemv and shape is synth.SHAPE_2B:
+        single = bench_single_state(torch, B, R, synth, np, enc, head, shape)
+
     # ---- CPU oracle on a bounded sample of the same workload
     cpu = None
     if want_cpu:
@@ -206,10 +231,13 @@ def main() -> int:
         val = O.MLP(*head.host["value"], "tanh")
         ns = max(1, min(args.cpu_sample_states, Bn))
         t0 = time.perf_counter()
-        h_ref = O.encoder_forward(ids_host[:ns], emb, layers, gfin, cfg)
+        if packed:
+            h_ref = np.concatenate([O.encoder_forward(ids_host[i:i + 1, :lens[i]], emb, layers, gfin, cfg) for i in range(ns)])
+        else:
+            h_ref = O.encoder_forward(ids_host[:ns], emb, layers, gfin, cfg)
         l_ref, v_ref = O.policy_value_head(h_ref, pol, val)
         cpu_s = time.perf_counter() - t0
-        h_gpu = enc.forward(ids)[:ns].cpu().numpy().astype(np.float64)
+        h_gpu = encode()[:ns].cpu().numpy().astype(np.float64)
         cosines = [float(h_gpu[i] @ h_ref[i] / np.linalg.norm(h_gpu[i]) / np.linalg.norm(h_ref[i])) for i in range(ns)]
         try:
             from threadpoolctl import threadpool_info
@@ -217,27 +245,29 @@ def main() -> int:
         except Exception:
             cores = os.cpu_count() or 1
         cpu = {"value": round(ns / cpu_s, 4), "unit": "states/s", "cores": int(cores), "kind": "oracle",
-               "sample": "%d of the %d states (%d tokens each, all %d layers + heads), NumPy oracle, fp64 BLAS integer matmul"
-                         % (ns, Bn, S, n_layers),
+               "sample": "%d of the %d states (%s tokens each, all %d layers + heads), NumPy oracle, fp64 BLAS integer matmul"
+                         % (ns, Bn, "/".join(str(int(n)) for n in lens[:ns]) if packed else str(S), n_layers),
                "seconds": round(cpu_s, 2), "min_cosine_gpu_vs_oracle": round(min(cosines), 6)}
 
     out = {
         "metric": "encoded RL states/sec at %s shape (BitLinear int8 TOPS as %% of roofline alongside)"
-                  % ("2B" if args.workload == "encoder-2b" else "3B"),
+                  % ("3B" if args.workload == "prefill-3b" else "2B"),
         "value": round(states_per_s, 2), "unit": "states/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (ternary x int8 -> int32, fp32 rescale)", "data": "synthetic",
         "config": {"workload": "frozen %s-shape ternary encoder + fp32 heads: %d layers, hidden %d, %d/%d heads, FFN %d, "
-                               "vocab %d; batch %d states x %d tokens, seed 0"
-                               % ("2B" if args.workload == "encoder-2b" else "3B", n_layers, shape.d, shape.n_heads,
-                                  shape.n_kv_heads, shape.f, shape.vocab, Bn, S),
-                   "states": Bn, "tokens_per_state": S, "int8_ops_per_step": ops_step},
+                               "vocab %d; batch %d states x %s tokens, seed 0"
+                               % ("3B" if args.workload == "prefill-3b" else "2B", n_layers, shape.d, shape.n_heads,
+                                  shape.n_kv_heads, shape.f, shape.vocab, Bn,
+                                  ("15-%d (uniform, %d in all, no padding)" % (S, tokens_step)) if packed else str(S)),
+                   "states": Bn, "tokens_per_state": (tokens_step / Bn) if packed else S, "int8_ops_per_step": ops_step},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernel_classes_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in classes.items()},
         "linear_tops_wall": round(ops_step / (ms_per_step * 1e-3) / 1e12, 2),
         "int8_ceiling_states_per_s": round(Bn / (ops_step / (INT8_MFMA_PEAK_TOPS * 1e12)), 1),
         "gemv_pair": gemv,
+        "single_state_latency": single,
         "concurrent_microbatches": concurrent,
         "paper_context": {"hardware": "Raspberry Pi 4 (Cortex-A72 @ 1.5 GHz), bitnet.cpp", "steps_per_s": 40.3,
                           "median_latency_ms": 24.8, "note": "one 15-40 token state per step; context only"},
@@ -245,6 +275,65 @@ def main() -> int:
     }
     print(json.dumps(out))
     return 0
+
+
+def bench_single_state(torch, B, R, synth, np, enc, head, shape, n_tokens: int = 27, calls: int = 50):
+    """encoder_forward_packed + heads on ONE state of n_tokens tokens per call: launch-per-kernel from the host,
+    and the same call sequence captured once into a HIP graph and replayed (the entry points allocate nothing and
+    never synchronise, so they can be captured as they are)."""
+    ids = R.dev(synth.token_ids(0, 510, (n_tokens,), shape.vocab))
+    cu_host = np.asarray([0, n_tokens], dtype=np.int32)
+    cu_dev = R.dev(cu_host)
+    ws = R.Workspace(B.brl_encoder_packed_workspace_bytes(enc.struct, 1, n_tokens, n_tokens))
+    hws = R.Workspace(B.brl_head_workspace_bytes(head.struct, 1))
+    h = torch.empty((1, shape.d), dtype=torch.float32, device="cuda")
+    logits = torch.empty((1, head.n_actions), dtype=torch.float32, device="cuda")
+    value = torch.empty((1,), dtype=torch.float32, device="cuda")
+
+    def call():
+        B.encoder_forward_packed(enc.struct, ids, cu_dev, cu_host, 1, n_tokens, h, ws.buf)
+        B.policy_value_head(head.struct, h, 1, logits, value, hws.buf)
+
+    for _ in range(5):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(calls):
+        call()
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) / calls * 1e3
+    ref = (h.clone(), logits.clone(), value.clone())
+
+    graph_ms, same = None, None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            call()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            call()
+        same = True
+        for _ in range(3):                     # replays interleaved with eager work, each checked
+            h.zero_(); logits.zero_(); value.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            same = same and bool(torch.equal(h, ref[0]) and torch.equal(logits, ref[1]) and torch.equal(value, ref[2]))
+            call()
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(calls):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / calls * 1e3
+    except Exception as e:                      # capture is an extra; the eager figure stands on its own
+        graph_ms, same = None, "capture failed: %s" % (str(e)[:120],)
+    return {"tokens": n_tokens, "calls": calls, "launch_per_kernel_ms_per_state": round(eager_ms, 4),
+            "hip_graph_replay_ms_per_state": None if graph_ms is None else round(graph_ms, 4),
+            "graph_replays_match_eager": same,
+            "states_per_s_one_at_a_time": round(1e3 / (graph_ms if graph_ms else eager_ms), 1)}
 
 
 def bench_gemv(torch, B, R, synth, calls: int):
