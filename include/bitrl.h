@@ -244,6 +244,64 @@ int policy_value_head(const brl_head* head /* HOST */, const float* h, int B,
                       void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Training of the two heads on a cached rollout (Sec. 3.1 Eq. 1; Sec. 3.2;
+ * Appendix hyper-parameter table).  The backbone is frozen, so the encoder
+ * output h_t of every rollout step is stored once and an update touches only
+ * the heads.
+ *
+ * ppo_gae: generalised advantage estimate of n_envs independent rollouts of T
+ * steps (arrays [n_envs, T], env-major; last_value [n_envs] bootstraps V after
+ * the last step; dones[e, t] = 1 when the episode ended with step t):
+ *   delta_t = r_t + gamma V_{t+1} (1 - done_t) - V_t,
+ *   A_t = delta_t + gamma lambda (1 - done_t) A_{t+1},   returns = A + V,
+ * accumulated backwards in fp64, stored as fp32.
+ *
+ * ppo_head_update: for epoch e = 0 .. epochs-1 the rollout indices perm[e, :]
+ * (DEVICE [epochs, T] int32, the shuffles are the caller's random draws) are
+ * cut into T / batch mini-batches (a remainder is dropped); each mini-batch is
+ * one optimiser step on both heads:
+ *   advantages normalised over the mini-batch, (A - mean) / (std_{n-1} + adv_eps),
+ *     if normalize_adv;
+ *   L_pi = -mean min(r A, clip(r, 1 - clip_eps, 1 + clip_eps) A) - ent_coef mean H,
+ *     r = exp(log pi(a_t | h_t) - logp_old_t), H the entropy of pi(. | h_t);
+ *   L_V = 0.5 mean (V(h_t) - returns_t)^2;
+ *   all gradients scaled by min(1, max_grad_norm / (||g||_2 + 1e-6)), one norm
+ *     over both heads;
+ *   Adam with bias correction, rate lr_policy on the policy head's tensors and
+ *     lr_value on the value head's.
+ * Parameters live in ONE flat fp32 DEVICE buffer (policy W_1, b_1, ..., W_L,
+ * b_L, then the value head likewise; brl_ppo_param_offsets gives each tensor's
+ * offset so a brl_head for policy_value_head can point into it), adam_m and
+ * adam_v likewise (zero them before the first update).  *adam_step (HOST)
+ * counts optimiser steps across calls.  h [T, dims[0]] fp32, actions [T]
+ * int32, logp_old / adv / returns [T] fp32.  stats (DEVICE, or NULL):
+ * [epochs * (T / batch), 5] = policy loss, value loss, mean entropy, fraction
+ * of clipped samples, gradient norm before clipping.  Sums run in fp64 in a
+ * fixed order: the result does not depend on scheduling.
+ * ------------------------------------------------------------------------ */
+typedef struct brl_ppo_config {
+    int policy_layers;            /* 1..8 weight matrices */
+    const int* policy_dims;       /* HOST [policy_layers + 1]: in, hidden..., actions */
+    int value_layers;
+    const int* value_dims;        /* HOST [value_layers + 1]: in, hidden..., 1 */
+    int act;                      /* BRL_ACT_* between layers */
+    float clip_eps, ent_coef, max_grad_norm, lr_policy, lr_value;
+    float adam_b1, adam_b2, adam_eps, adv_eps;
+    int normalize_adv;
+} brl_ppo_config;
+
+size_t brl_ppo_param_count(const brl_ppo_config* cfg /* HOST */);
+int brl_ppo_param_offsets(const brl_ppo_config* cfg, size_t* w_offsets, size_t* b_offsets /* HOST [policy_layers + value_layers] each */);
+size_t brl_ppo_workspace_bytes(const brl_ppo_config* cfg, int batch);
+int ppo_gae(const float* rewards, const float* values, const float* dones, const float* last_value,
+            int n_envs, int T, float gamma, float lam, float* adv, float* returns, void* stream);
+int ppo_head_update(const brl_ppo_config* cfg /* HOST */, float* params, float* adam_m, float* adam_v,
+                    long long* adam_step /* HOST */,
+                    const float* h, const int32_t* actions, const float* logp_old, const float* adv,
+                    const float* returns, int T, const int32_t* perm, int epochs, int batch,
+                    float* stats, void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Per-kernel timing with HIP events, for measurement harnesses (off by
  * default; not a paper operation).  While enabled, every kernel launch of the
  * library is bracketed by two events recorded on the launch stream.

@@ -66,6 +66,16 @@ class BitrlError(RuntimeError):
 
 _lib = None
 
+class brl_ppo_config(C.Structure):
+    _fields_ = [("policy_layers", c_int), ("policy_dims", C.POINTER(c_int)),
+                ("value_layers", c_int), ("value_dims", C.POINTER(c_int)),
+                ("act", c_int),
+                ("clip_eps", c_float), ("ent_coef", c_float), ("max_grad_norm", c_float),
+                ("lr_policy", c_float), ("lr_value", c_float),
+                ("adam_b1", c_float), ("adam_b2", c_float), ("adam_eps", c_float), ("adv_eps", c_float),
+                ("normalize_adv", c_int)]
+
+
 _SIGNATURES = {
     "brl_last_error": (C.c_char_p, []),
     "brl_abi_version": (c_int, []),
@@ -91,6 +101,14 @@ _SIGNATURES = {
     "brl_head_workspace_bytes": (c_size_t, [C.POINTER(brl_head), c_int]),
     "policy_value_head": (c_int, [C.POINTER(brl_head), c_void_p, c_int, c_void_p, c_void_p,
                                   c_void_p, c_size_t, c_void_p]),
+    "brl_ppo_param_count": (c_size_t, [C.POINTER(brl_ppo_config)]),
+    "brl_ppo_param_offsets": (c_int, [C.POINTER(brl_ppo_config), C.POINTER(c_size_t), C.POINTER(c_size_t)]),
+    "brl_ppo_workspace_bytes": (c_size_t, [C.POINTER(brl_ppo_config), c_int]),
+    "ppo_gae": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_float, c_float, c_void_p, c_void_p,
+                        c_void_p]),
+    "ppo_head_update": (c_int, [C.POINTER(brl_ppo_config), c_void_p, c_void_p, c_void_p, C.POINTER(C.c_longlong),
+                                c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int,
+                                c_void_p, c_void_p, c_size_t, c_void_p]),
     "brl_timing_enable": (c_int, [c_int]),
     "brl_timing_read": (c_int, [c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "brl_timing_read_ops": (c_int, [c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
@@ -225,6 +243,51 @@ def policy_value_head(head: brl_head, h: torch.Tensor, B: int, logits: torch.Ten
                       workspace: torch.Tensor) -> None:
     _check(lib().policy_value_head(C.byref(head), _ptr(h), B, _ptr(logits), _ptr(value), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+def make_ppo_config(policy_dims: Sequence[int], value_dims: Sequence[int], act: int, clip_eps: float = 0.1,
+                    ent_coef: float = 0.05, max_grad_norm: float = 0.5, lr_policy: float = 3e-4, lr_value: float = 1e-3,
+                    adam_b1: float = 0.9, adam_b2: float = 0.999, adam_eps: float = 1e-8, adv_eps: float = 1e-8,
+                    normalize_adv: bool = True):
+    """Returns (brl_ppo_config, keepalive); defaults are the paper's hyper-parameter table."""
+    pd = (c_int * len(policy_dims))(*policy_dims)
+    vd = (c_int * len(value_dims))(*value_dims)
+    cfg = brl_ppo_config(len(policy_dims) - 1, pd, len(value_dims) - 1, vd, act, clip_eps, ent_coef, max_grad_norm,
+                         lr_policy, lr_value, adam_b1, adam_b2, adam_eps, adv_eps, 1 if normalize_adv else 0)
+    return cfg, (pd, vd)
+
+
+def brl_ppo_param_count(cfg: brl_ppo_config) -> int:
+    return lib().brl_ppo_param_count(C.byref(cfg))
+
+
+def brl_ppo_param_offsets(cfg: brl_ppo_config):
+    n = cfg.policy_layers + cfg.value_layers
+    w, b = (c_size_t * n)(), (c_size_t * n)()
+    _check(lib().brl_ppo_param_offsets(C.byref(cfg), w, b))
+    return list(w), list(b)
+
+
+def brl_ppo_workspace_bytes(cfg: brl_ppo_config, batch: int) -> int:
+    return lib().brl_ppo_workspace_bytes(C.byref(cfg), batch)
+
+
+def ppo_gae(rewards: torch.Tensor, values: torch.Tensor, dones: torch.Tensor, last_value: torch.Tensor, n_envs: int,
+            T: int, gamma: float, lam: float, adv: torch.Tensor, returns: torch.Tensor) -> None:
+    _check(lib().ppo_gae(_ptr(rewards), _ptr(values), _ptr(dones), _ptr(last_value), n_envs, T, gamma, lam, _ptr(adv),
+                         _ptr(returns), _stream()))
+
+
+def ppo_head_update(cfg: brl_ppo_config, params: torch.Tensor, adam_m: torch.Tensor, adam_v: torch.Tensor, adam_step: int,
+                    h: torch.Tensor, actions: torch.Tensor, logp_old: torch.Tensor, adv: torch.Tensor,
+                    returns: torch.Tensor, T: int, perm: torch.Tensor, epochs: int, batch: int,
+                    stats: Optional[torch.Tensor], workspace: torch.Tensor) -> int:
+    """Returns the optimiser step count after the update."""
+    step = C.c_longlong(adam_step)
+    _check(lib().ppo_head_update(C.byref(cfg), _ptr(params), _ptr(adam_m), _ptr(adam_v), C.byref(step), _ptr(h),
+                                 _ptr(actions), _ptr(logp_old), _ptr(adv), _ptr(returns), T, _ptr(perm), epochs, batch,
+                                 _ptr(stats), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+    return step.value
 
 
 BRL_KC_QUANTIZE_WEIGHTS, BRL_KC_ACT_QUANT, BRL_KC_GEMM, BRL_KC_GEMV, BRL_KC_ATTENTION, BRL_KC_OTHER, \

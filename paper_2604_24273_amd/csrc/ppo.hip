@@ -1,0 +1,461 @@
+// PPO update of the trainable policy / value heads on cached encoder outputs (Sec. 3.1 Eq. 1,
+// Sec. 3.2, Appendix hyper-parameter table), and the generalised advantage estimate.
+//
+// The backbone is frozen, so a rollout stores h_t once and the update touches only the two small
+// MLPs: every mini-batch is a forward pass of both heads, the clipped-surrogate / entropy / value
+// gradients at their outputs, back-propagation, one global gradient-norm clip and an Adam step.
+// The products are tiny (64 x 2560 x 256), so the work is laid out as a few wide kernels per
+// step, each with fp64 accumulation in a fixed order: results do not depend on scheduling.
+// Parameters and optimiser state are fp32 in one flat buffer each (policy W_1, b_1, ..., W_L, b_L,
+// then the value head likewise); activations, deltas and gradients of a step live in fp64 scratch.
+#include "common.hpp"
+
+#include <cmath>
+#include <cstring>
+
+namespace brl {
+
+namespace {
+
+constexpr int PPO_MAX_LAYERS = 8;
+
+struct HeadShape {
+    int n;                           // layers
+    int dims[PPO_MAX_LAYERS + 1];
+    size_t w_off[PPO_MAX_LAYERS];    // offsets into the flat parameter buffer
+    size_t b_off[PPO_MAX_LAYERS];
+};
+
+struct Layout {
+    HeadShape head[2];               // 0 policy, 1 value
+    size_t n_params, n_policy;
+    int max_dim;                     // widest layer output
+};
+
+int make_layout(const brl_ppo_config* c, Layout& L) {
+    BRL_REQUIRE(c != nullptr, "ppo: null config");
+    BRL_REQUIRE(c->policy_dims && c->value_dims, "ppo: null layer sizes");
+    BRL_REQUIRE(c->policy_layers >= 1 && c->policy_layers <= PPO_MAX_LAYERS && c->value_layers >= 1 &&
+                    c->value_layers <= PPO_MAX_LAYERS,
+                "ppo: 1..%d layers per head", PPO_MAX_LAYERS);
+    BRL_REQUIRE(c->act == BRL_ACT_TANH || c->act == BRL_ACT_RELU, "ppo: unknown activation %d", c->act);
+    size_t off = 0;
+    L.max_dim = 1;
+    for (int hd = 0; hd < 2; ++hd) {
+        HeadShape& H = L.head[hd];
+        H.n = hd == 0 ? c->policy_layers : c->value_layers;
+        const int* dims = hd == 0 ? c->policy_dims : c->value_dims;
+        for (int i = 0; i <= H.n; ++i) {
+            BRL_REQUIRE(dims[i] >= 1 && dims[i] <= (1 << 20), "ppo: layer size %d", dims[i]);
+            H.dims[i] = dims[i];
+            if (i > 0 && dims[i] > L.max_dim) L.max_dim = dims[i];
+        }
+        for (int l = 0; l < H.n; ++l) {
+            H.w_off[l] = off;
+            off += (size_t)H.dims[l + 1] * H.dims[l];
+            H.b_off[l] = off;
+            off += (size_t)H.dims[l + 1];
+        }
+        if (hd == 0) L.n_policy = off;
+    }
+    L.n_params = off;
+    BRL_REQUIRE(L.head[0].dims[0] == L.head[1].dims[0], "ppo: the heads disagree on the input width");
+    BRL_REQUIRE(L.head[1].dims[L.head[1].n] == 1, "ppo: the value head must end in one output");
+    BRL_REQUIRE(L.head[0].dims[L.head[0].n] <= 1024, "ppo: at most 1024 actions");
+    return BRL_OK;
+}
+
+// ---- kernels ---------------------------------------------------------------------------------
+
+// adv[e, t], ret[e, t] for E independent rollouts of T steps, one thread per rollout, backwards in fp64:
+// delta = r + gamma V' (1 - done) - V;  A = delta + gamma lambda (1 - done) A'
+__global__ void gae_kernel(const float* __restrict__ rewards, const float* __restrict__ values,
+                           const float* __restrict__ dones, const float* __restrict__ last_value, int E, int T,
+                           double gamma, double lam, float* __restrict__ adv, float* __restrict__ ret) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= E) return;
+    double nxt_adv = 0.0, nxt_val = (double)last_value[e];
+    for (int t = T - 1; t >= 0; --t) {
+        const size_t i = (size_t)e * T + t;
+        const double live = 1.0 - (double)dones[i];
+        const double v = (double)values[i];
+        const double delta = (double)rewards[i] + gamma * nxt_val * live - v;
+        nxt_adv = delta + gamma * lam * live * nxt_adv;
+        adv[i] = (float)nxt_adv;
+        ret[i] = (float)(nxt_adv + v);
+        nxt_val = v;
+    }
+}
+
+// out[b, o] = act(sum_i W[o, i] in(b, i) + bias[o]); one wavefront per output, fp64 accumulation in lane order.
+// in(b, i) = in64[b, i], or for the first layer the cached encoder output h[rows[b], i].
+__global__ __launch_bounds__(256) void ppo_forward_kernel(const double* __restrict__ in64, const float* __restrict__ h,
+                                                           const int32_t* __restrict__ rows, const float* __restrict__ W,
+                                                           const float* __restrict__ bias, int B, int in_dim, int out_dim,
+                                                           int act, int last, double* __restrict__ out) {
+    const size_t wid = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (wid >= (size_t)B * out_dim) return;
+    const int b = (int)(wid / out_dim), o = (int)(wid % out_dim);
+    const float* w = W + (size_t)o * in_dim;
+    const float* hrow = in64 ? nullptr : h + (size_t)rows[b] * in_dim;
+    double acc = 0.0;
+    for (int i = lane; i < in_dim; i += 64) {
+        const double v = in64 ? in64[(size_t)b * in_dim + i] : (double)hrow[i];
+        acc += (double)w[i] * v;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) {
+        double z = acc + (double)bias[o];
+        if (!last) z = (act == BRL_ACT_RELU) ? fmax(z, 0.0) : tanh(z);
+        out[(size_t)b * out_dim + o] = z;
+    }
+}
+
+struct LossArgs {
+    const double* logits;     // [B, A]
+    const double* v;          // [B]
+    const int32_t* rows;      // [B] indices into the rollout
+    const int32_t* actions;
+    const float* logp_old;
+    const float* adv;
+    const float* returns;
+    int B, A;
+    double clip_eps, ent_coef, adv_eps;
+    int normalize_adv;
+    double* dlogits;          // [B, A]
+    double* dv;               // [B]
+    float* stats;             // [5]: policy loss, value loss, entropy, clip fraction, (gradient norm: written later) or null
+    double* row_terms;        // [4, B] scratch
+};
+
+// One workgroup: advantage normalisation over the mini-batch, then one thread per sample for the
+// clipped surrogate (Eq. 1), the entropy bonus and the value error, and their gradients at the heads' outputs.
+__global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
+    __shared__ double s_mean, s_inv;
+    if (threadIdx.x == 0) {
+        double mean = 0.0, inv = 1.0;
+        if (a.normalize_adv) {
+            for (int b = 0; b < a.B; ++b) mean += (double)a.adv[a.rows[b]];
+            mean /= (double)a.B;
+            double ss = 0.0;
+            for (int b = 0; b < a.B; ++b) {
+                const double d = (double)a.adv[a.rows[b]] - mean;
+                ss += d * d;
+            }
+            const double sd = a.B > 1 ? sqrt(ss / (double)(a.B - 1)) : 0.0;
+            inv = 1.0 / (sd + a.adv_eps);
+        }
+        s_mean = mean;
+        s_inv = inv;
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < a.B; b += blockDim.x) {
+        const int r = a.rows[b];
+        const double A = ((double)a.adv[r] - s_mean) * s_inv;
+        const double* z = a.logits + (size_t)b * a.A;
+        double m = z[0];
+        for (int k = 1; k < a.A; ++k) m = fmax(m, z[k]);
+        double se = 0.0;
+        for (int k = 0; k < a.A; ++k) se += exp(z[k] - m);
+        const double lse = m + log(se);
+        const int act = a.actions[r];
+        const double logp = z[act] - lse;
+        const double ratio = exp(logp - (double)a.logp_old[r]);
+        const double surr1 = ratio * A;
+        const double clipped = fmin(fmax(ratio, 1.0 - a.clip_eps), 1.0 + a.clip_eps);
+        const double surr2 = clipped * A;
+        const double active = surr1 <= surr2 ? 1.0 : 0.0;
+        double ent = 0.0;
+        for (int k = 0; k < a.A; ++k) {
+            const double lp = z[k] - lse;
+            ent -= exp(lp) * lp;
+        }
+        const double coef = -(active * A * ratio);
+        for (int k = 0; k < a.A; ++k) {
+            const double lp = z[k] - lse, p = exp(lp);
+            a.dlogits[(size_t)b * a.A + k] = (coef * ((k == act ? 1.0 : 0.0) - p) + a.ent_coef * p * (lp + ent)) / (double)a.B;
+        }
+        const double diff = a.v[b] - (double)a.returns[r];
+        a.dv[b] = diff / (double)a.B;
+        a.row_terms[0 * a.B + b] = fmin(surr1, surr2);
+        a.row_terms[1 * a.B + b] = ent;
+        a.row_terms[2 * a.B + b] = diff * diff;
+        a.row_terms[3 * a.B + b] = 1.0 - active;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && a.stats) {
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        for (int b = 0; b < a.B; ++b) {
+            s0 += a.row_terms[0 * a.B + b];
+            s1 += a.row_terms[1 * a.B + b];
+            s2 += a.row_terms[2 * a.B + b];
+            s3 += a.row_terms[3 * a.B + b];
+        }
+        const double n = (double)a.B;
+        a.stats[0] = (float)(-s0 / n - a.ent_coef * s1 / n);
+        a.stats[1] = (float)(0.5 * s2 / n);
+        a.stats[2] = (float)(s1 / n);
+        a.stats[3] = (float)(s3 / n);
+    }
+}
+
+// dW[o, i] = sum_b delta[b, o] in(b, i) (samples in order), db[o] = sum_b delta[b, o]; one thread per (o, i),
+// i fastest; the squares of a workgroup's gradients are summed to partial[blockIdx.x] for the global norm.
+__global__ __launch_bounds__(256) void ppo_weight_grad_kernel(const double* __restrict__ delta, const double* __restrict__ in64,
+                                                               const float* __restrict__ h, const int32_t* __restrict__ rows,
+                                                               int B, int in_dim, int out_dim, double* __restrict__ gW,
+                                                               double* __restrict__ gb, double* __restrict__ partial) {
+    __shared__ double red[256];
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    double sq = 0.0;
+    if (idx < (size_t)out_dim * in_dim) {
+        const int o = (int)(idx / in_dim), i = (int)(idx % in_dim);
+        double acc = 0.0, accb = 0.0;
+        for (int b = 0; b < B; ++b) {
+            const double d = delta[(size_t)b * out_dim + o];
+            const double x = in64 ? in64[(size_t)b * in_dim + i] : (double)h[(size_t)rows[b] * in_dim + i];
+            acc += d * x;
+            accb += d;
+        }
+        gW[idx] = acc;
+        sq = acc * acc;
+        if (i == 0) {
+            gb[o] = accb;
+            sq += accb * accb;
+        }
+    }
+    red[threadIdx.x] = sq;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+// delta_prev[b, i] = (sum_o delta[b, o] W[o, i]) * act'(a[b, i]), a = the activated output of the layer below
+__global__ __launch_bounds__(256) void ppo_delta_kernel(const double* __restrict__ delta, const float* __restrict__ W,
+                                                         const double* __restrict__ a_prev, int B, int in_dim, int out_dim,
+                                                         int act, double* __restrict__ delta_prev) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)B * in_dim) return;
+    const int b = (int)(idx / in_dim), i = (int)(idx % in_dim);
+    double acc = 0.0;
+    for (int o = 0; o < out_dim; ++o) acc += delta[(size_t)b * out_dim + o] * (double)W[(size_t)o * in_dim + i];
+    const double a = a_prev[idx];
+    delta_prev[idx] = acc * (act == BRL_ACT_RELU ? (a > 0.0 ? 1.0 : 0.0) : 1.0 - a * a);
+}
+
+// scal[0] = global L2 norm of the gradients (partials summed in index order), scal[1] = min(1, max_norm / (norm + 1e-6))
+__global__ void ppo_norm_kernel(const double* __restrict__ partial, int n, double max_norm, double* __restrict__ scal,
+                                float* __restrict__ stats) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += partial[i];
+    const double norm = sqrt(s);
+    scal[0] = norm;
+    scal[1] = fmin(1.0, max_norm / (norm + 1e-6));
+    if (stats) stats[4] = (float)norm;
+}
+
+// Adam with bias correction on the clipped gradient: p -= lr (m / c1) / (sqrt(v / c2) + eps)
+__global__ __launch_bounds__(256) void ppo_adam_kernel(float* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
+                                                        const double* __restrict__ g, const double* __restrict__ scal,
+                                                        size_t n, size_t n_policy, double lr_policy, double lr_value,
+                                                        double b1, double b2, double c1, double c2, double eps) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const double gi = g[i] * scal[1];
+    const double mi = b1 * (double)m[i] + (1.0 - b1) * gi;
+    const double vi = b2 * (double)v[i] + (1.0 - b2) * gi * gi;
+    m[i] = (float)mi;
+    v[i] = (float)vi;
+    const double lr = i < n_policy ? lr_policy : lr_value;
+    p[i] = (float)((double)p[i] - lr * (mi / c1) / (sqrt(vi / c2) + eps));
+}
+
+// ---- workspace ---------------------------------------------------------------------------------
+
+struct PpoWs {
+    size_t act_off[2][PPO_MAX_LAYERS];   // layer outputs [batch, dims[l+1]] fp64
+    size_t delta_off[2];                 // ping-pong deltas [batch, max_dim] fp64
+    size_t dv_off, grad_off, partial_off, scal_off, rows_off, total;
+    int n_partials;
+    int partial_first[2][PPO_MAX_LAYERS];
+};
+
+constexpr size_t PPO_ALIGN = 256;
+
+PpoWs ppo_ws_layout(const Layout& L, int batch) {
+    PpoWs W;
+    memset(&W, 0, sizeof(W));
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += round_up_sz(bytes, PPO_ALIGN);
+        return at;
+    };
+    for (int hd = 0; hd < 2; ++hd)
+        for (int l = 0; l < L.head[hd].n; ++l) W.act_off[hd][l] = take((size_t)batch * L.head[hd].dims[l + 1] * 8);
+    W.delta_off[0] = take((size_t)batch * L.max_dim * 8);
+    W.delta_off[1] = take((size_t)batch * L.max_dim * 8);
+    W.dv_off = take((size_t)batch * 8);
+    W.grad_off = take(L.n_params * 8);
+    int np = 0;
+    for (int hd = 0; hd < 2; ++hd)
+        for (int l = 0; l < L.head[hd].n; ++l) {
+            W.partial_first[hd][l] = np;
+            np += (int)(((size_t)L.head[hd].dims[l + 1] * L.head[hd].dims[l] + 255) / 256);
+        }
+    W.n_partials = np;
+    W.partial_off = take((size_t)np * 8);
+    W.scal_off = take(2 * 8);
+    W.rows_off = take((size_t)4 * batch * 8);
+    W.total = off;
+    return W;
+}
+
+}  // namespace
+
+}  // namespace brl
+
+using namespace brl;
+
+extern "C" {
+
+size_t brl_ppo_param_count(const brl_ppo_config* cfg) {
+    Layout L;
+    if (make_layout(cfg, L) != BRL_OK) return 0;
+    return L.n_params;
+}
+
+int brl_ppo_param_offsets(const brl_ppo_config* cfg, size_t* w_offsets, size_t* b_offsets) {
+    Layout L;
+    if (int rc = make_layout(cfg, L)) return rc;
+    BRL_REQUIRE(w_offsets && b_offsets, "ppo_param_offsets: null pointer");
+    int k = 0;
+    for (int hd = 0; hd < 2; ++hd)
+        for (int l = 0; l < L.head[hd].n; ++l, ++k) {
+            w_offsets[k] = L.head[hd].w_off[l];
+            b_offsets[k] = L.head[hd].b_off[l];
+        }
+    return BRL_OK;
+}
+
+size_t brl_ppo_workspace_bytes(const brl_ppo_config* cfg, int batch) {
+    Layout L;
+    if (batch < 1 || make_layout(cfg, L) != BRL_OK) return 0;
+    return ppo_ws_layout(L, batch).total;
+}
+
+int ppo_gae(const float* rewards, const float* values, const float* dones, const float* last_value, int n_envs, int T,
+            float gamma, float lam, float* adv, float* returns, void* stream) {
+    BRL_REQUIRE(rewards && values && dones && last_value && adv && returns, "ppo_gae: null pointer");
+    BRL_REQUIRE(n_envs >= 1 && T >= 1, "ppo_gae: n_envs = %d, T = %d", n_envs, T);
+    BRL_REQUIRE(gamma >= 0.f && gamma <= 1.f && lam >= 0.f && lam <= 1.f, "ppo_gae: gamma and lambda must lie in [0, 1]");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LaunchTimer tm(BRL_KC_OTHER, s);
+    hipLaunchKernelGGL(gae_kernel, dim3((n_envs + 63) / 64), dim3(64), 0, s, rewards, values, dones, last_value, n_envs, T,
+                       (double)gamma, (double)lam, adv, returns);
+    BRL_LAUNCH_CHECK("gae_kernel");
+    return BRL_OK;
+}
+
+int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, float* adam_v, long long* adam_step,
+                    const float* h, const int32_t* actions, const float* logp_old, const float* adv, const float* returns,
+                    int T, const int32_t* perm, int epochs, int batch, float* stats, void* workspace, size_t ws_bytes,
+                    void* stream) {
+    Layout L;
+    if (int rc = make_layout(cfg, L)) return rc;
+    BRL_REQUIRE(params && adam_m && adam_v && adam_step && h && actions && logp_old && adv && returns && perm && workspace,
+                "ppo_head_update: null pointer");
+    BRL_REQUIRE(T >= 1 && epochs >= 0 && batch >= 1 && batch <= T, "ppo_head_update: T = %d, epochs = %d, batch = %d", T,
+                epochs, batch);
+    BRL_REQUIRE(*adam_step >= 0, "ppo_head_update: negative step count");
+    BRL_REQUIRE(!cfg->normalize_adv || batch >= 2, "ppo_head_update: advantage normalisation needs batch >= 2");
+    BRL_REQUIRE(cfg->clip_eps >= 0.f && cfg->max_grad_norm > 0.f && cfg->adam_eps > 0.f && cfg->adam_b1 >= 0.f &&
+                    cfg->adam_b1 < 1.f && cfg->adam_b2 >= 0.f && cfg->adam_b2 < 1.f && cfg->adv_eps >= 0.f,
+                "ppo_head_update: bad hyper-parameter");
+    const PpoWs W = ppo_ws_layout(L, batch);
+    if (ws_bytes < W.total) {
+        set_error("ppo_head_update: workspace %zu < %zu", ws_bytes, W.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    double* grads = reinterpret_cast<double*>(base + W.grad_off);
+    double* partial = reinterpret_cast<double*>(base + W.partial_off);
+    double* scal = reinterpret_cast<double*>(base + W.scal_off);
+    double* dv = reinterpret_cast<double*>(base + W.dv_off);
+    double* delta[2] = {reinterpret_cast<double*>(base + W.delta_off[0]), reinterpret_cast<double*>(base + W.delta_off[1])};
+    const int A = L.head[0].dims[L.head[0].n];
+    const int steps_per_epoch = T / batch;
+    LaunchTimer tm(BRL_KC_OTHER, s);
+    long long step = *adam_step;
+    for (int e = 0; e < epochs; ++e) {
+        for (int mb = 0; mb < steps_per_epoch; ++mb) {
+            const int32_t* rows = perm + (size_t)e * T + (size_t)mb * batch;
+            float* st = stats ? stats + ((size_t)e * steps_per_epoch + mb) * 5 : nullptr;
+            // forward, both heads
+            for (int hd = 0; hd < 2; ++hd) {
+                const HeadShape& H = L.head[hd];
+                for (int l = 0; l < H.n; ++l) {
+                    const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
+                    double* out = reinterpret_cast<double*>(base + W.act_off[hd][l]);
+                    const size_t waves = (size_t)batch * H.dims[l + 1];
+                    hipLaunchKernelGGL(ppo_forward_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, in64, h, rows,
+                                       params + H.w_off[l], params + H.b_off[l], batch, H.dims[l], H.dims[l + 1], cfg->act,
+                                       l == H.n - 1 ? 1 : 0, out);
+                }
+            }
+            // gradients at the outputs
+            LossArgs la;
+            la.logits = reinterpret_cast<const double*>(base + W.act_off[0][L.head[0].n - 1]);
+            la.v = reinterpret_cast<const double*>(base + W.act_off[1][L.head[1].n - 1]);
+            la.rows = rows; la.actions = actions; la.logp_old = logp_old; la.adv = adv; la.returns = returns;
+            la.B = batch; la.A = A;
+            la.clip_eps = (double)cfg->clip_eps; la.ent_coef = (double)cfg->ent_coef; la.adv_eps = (double)cfg->adv_eps;
+            la.normalize_adv = cfg->normalize_adv;
+            la.dlogits = delta[0];
+            la.dv = dv;
+            la.stats = st;
+            la.row_terms = reinterpret_cast<double*>(base + W.rows_off);
+            hipLaunchKernelGGL(ppo_loss_kernel, dim3(1), dim3(256), 0, s, la);
+            // backward, both heads
+            for (int hd = 0; hd < 2; ++hd) {
+                const HeadShape& H = L.head[hd];
+                const double* dcur = hd == 0 ? delta[0] : dv;
+                int pp = 1;                 // next ping-pong buffer (delta[0] holds dlogits until the policy head is done)
+                for (int l = H.n - 1; l >= 0; --l) {
+                    const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
+                    const size_t n = (size_t)H.dims[l + 1] * H.dims[l];
+                    hipLaunchKernelGGL(ppo_weight_grad_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dcur, in64, h,
+                                       rows, batch, H.dims[l], H.dims[l + 1], grads + H.w_off[l], grads + H.b_off[l],
+                                       partial + W.partial_first[hd][l]);
+                    if (l > 0) {
+                        double* dprev = delta[pp];
+                        const size_t m = (size_t)batch * H.dims[l];
+                        hipLaunchKernelGGL(ppo_delta_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, dcur,
+                                           params + H.w_off[l], in64, batch, H.dims[l], H.dims[l + 1], cfg->act, dprev);
+                        dcur = dprev;
+                        pp ^= 1;
+                    }
+                }
+            }
+            hipLaunchKernelGGL(ppo_norm_kernel, dim3(1), dim3(64), 0, s, partial, W.n_partials, (double)cfg->max_grad_norm, scal, st);
+            ++step;
+            const double c1 = 1.0 - pow((double)cfg->adam_b1, (double)step);
+            const double c2 = 1.0 - pow((double)cfg->adam_b2, (double)step);
+            hipLaunchKernelGGL(ppo_adam_kernel, dim3((unsigned)((L.n_params + 255) / 256)), dim3(256), 0, s, params, adam_m, adam_v,
+                               grads, scal, L.n_params, L.n_policy, (double)cfg->lr_policy, (double)cfg->lr_value,
+                               (double)cfg->adam_b1, (double)cfg->adam_b2, c1, c2, (double)cfg->adam_eps);
+        }
+    }
+    BRL_LAUNCH_CHECK("ppo_head_update");
+    *adam_step = step;
+    return BRL_OK;
+}
+
+}  // extern "C"

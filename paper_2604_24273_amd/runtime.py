@@ -167,3 +167,59 @@ class HeadHandle:
         value = torch.empty((b,), dtype=torch.float32, device=DEV)
         B.policy_value_head(self.struct, h, b, logits, value, self.ws.buf)
         return logits, value
+
+
+class PPOTrainer:
+    """The two trainable heads in one flat parameter buffer, their Adam state, and the update entry points."""
+
+    def __init__(self, policy_wb, value_wb, act: int = B.BRL_ACT_TANH, **hyper):
+        pw, pb = policy_wb
+        vw, vb = value_wb
+        pdims = [pw[0].shape[1]] + [w.shape[0] for w in pw]
+        vdims = [vw[0].shape[1]] + [w.shape[0] for w in vw]
+        self.cfg, self._keep = B.make_ppo_config(pdims, vdims, act, **hyper)
+        n = B.brl_ppo_param_count(self.cfg)
+        w_off, b_off = B.brl_ppo_param_offsets(self.cfg)
+        flat = np.zeros(n, dtype=np.float32)
+        self.slices = []
+        for k, (w, b) in enumerate(list(zip(pw, pb)) + list(zip(vw, vb))):
+            flat[w_off[k]:w_off[k] + w.size] = np.asarray(w, dtype=np.float32).reshape(-1)
+            flat[b_off[k]:b_off[k] + b.size] = np.asarray(b, dtype=np.float32).reshape(-1)
+            self.slices.append((w_off[k], w.shape, b_off[k], b.shape))
+        self.params = dev(flat)
+        self.adam_m = torch.zeros_like(self.params)
+        self.adam_v = torch.zeros_like(self.params)
+        self.step = 0
+        self.n_policy_layers = len(pw)
+        # a forward head whose tensors are views into the flat buffer
+        views = [(self.params[wo:wo + int(np.prod(ws))].view(*ws), self.params[bo:bo + int(np.prod(bs))].view(*bs))
+                 for wo, ws, bo, bs in self.slices]
+        pol, self._k1 = B.make_mlp([v[0] for v in views[:len(pw)]], [v[1] for v in views[:len(pw)]], act)
+        val, self._k2 = B.make_mlp([v[0] for v in views[len(pw):]], [v[1] for v in views[len(pw):]], act)
+        self.head = B.brl_head(pol, val)
+        self.ws: Optional[Workspace] = None
+
+    def tensors(self):
+        """Host copies of the parameters: (policy weights, policy biases, value weights, value biases)."""
+        flat = self.params.cpu().numpy()
+        out = [(flat[wo:wo + int(np.prod(ws))].reshape(ws).copy(), flat[bo:bo + int(np.prod(bs))].reshape(bs).copy())
+               for wo, ws, bo, bs in self.slices]
+        n = self.n_policy_layers
+        return [o[0] for o in out[:n]], [o[1] for o in out[:n]], [o[0] for o in out[n:]], [o[1] for o in out[n:]]
+
+    def update(self, h, actions, logp_old, adv, returns, perm, batch: int, want_stats: bool = True):
+        epochs, T = perm.shape
+        need = B.brl_ppo_workspace_bytes(self.cfg, batch)
+        self.ws = Workspace(need) if self.ws is None else self.ws.ensure(need)
+        stats = torch.zeros((epochs * (T // batch), 5), dtype=torch.float32, device=DEV) if want_stats else None
+        self.step = B.ppo_head_update(self.cfg, self.params, self.adam_m, self.adam_v, self.step, h, actions, logp_old, adv,
+                                      returns, T, perm, epochs, batch, stats, self.ws.buf)
+        return stats
+
+
+def gae(rewards: torch.Tensor, values: torch.Tensor, dones: torch.Tensor, last_value: torch.Tensor, gamma: float, lam: float):
+    n_envs, T = rewards.shape
+    adv = torch.empty_like(rewards)
+    ret = torch.empty_like(rewards)
+    B.ppo_gae(rewards, values, dones, last_value, n_envs, T, gamma, lam, adv, ret)
+    return adv, ret

@@ -159,3 +159,27 @@ def head_params(seed: int, shape: EncoderShape, which: str) -> Tuple[list, list]
         ws.append(normal(seed, base + 2 * i, (dims[i + 1], dims[i]), 1.0 / np.sqrt(dims[i])))
         bs.append(normal(seed, base + 2 * i + 1, (dims[i + 1],), 0.1))
     return ws, bs
+
+
+def ppo_rollout_case(seed: int, T: int, d: int, n_actions: int, epochs: int, n_envs: int = 1) -> Dict[str, np.ndarray]:
+    """A cached rollout for the head update: encoder outputs, actions, behaviour log-probabilities, rewards,
+    value predictions, episode ends, bootstrap values and the mini-batch shuffles (one permutation per epoch)."""
+    g = _rng(seed, 40)
+    n = T * n_envs
+    return {"h": normal(seed, 41, (n, d), 0.5),
+            "actions": g.integers(0, n_actions, size=n, dtype=np.int32),
+            "logp_old": (np.log(1.0 / n_actions) + 0.15 * normal(seed, 42, (n,))).astype(np.float32),
+            "rewards": normal(seed, 43, (n_envs, T)),
+            "values": normal(seed, 44, (n_envs, T), 0.7),
+            "dones": (g.random(size=(n_envs, T)) < 0.03).astype(np.float32),
+            "last_value": normal(seed, 45, (n_envs,), 0.7),
+            "perm": np.stack([g.permutation(n) for _ in range(max(epochs, 1))]).astype(np.int32)[:epochs].reshape(epochs, n)}
+
+
+def mlp_params(seed: int, stream: int, dims) -> Tuple[list, list]:
+    """fp32 weights N(0, 1/fan_in) and biases 0.1 N(0, 1) for a layer list."""
+    ws, bs = [], []
+    for i in range(len(dims) - 1):
+        ws.append(normal(seed, stream + 2 * i, (dims[i + 1], dims[i]), 1.0 / np.sqrt(dims[i])))
+        bs.append(normal(seed, stream + 2 * i + 1, (dims[i + 1],), 0.1))
+    return ws, bs

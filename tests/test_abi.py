@@ -99,6 +99,24 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     enc = B.brl_encoder(0, 256, 4, 2, 48, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
     assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
     assert "head_dim" in err()
+    # PPO head update: shapes and hyper-parameters are checked on the host
+    cfg, keep = B.make_ppo_config([16, 8, 4], [16, 8, 1], B.BRL_ACT_TANH)
+    assert lib.brl_ppo_param_count(C.byref(cfg)) == 16 * 8 + 8 + 8 * 4 + 4 + 16 * 8 + 8 + 8 + 1
+    w_off, b_off = B.brl_ppo_param_offsets(cfg)
+    assert w_off == [0, 136, 172, 308] and b_off == [128, 168, 300, 316]
+    assert lib.brl_ppo_workspace_bytes(C.byref(cfg), 64) > 0
+    step = C.c_longlong(0)
+    args = (fake,) * 3 + (C.byref(step),) + (fake,) * 5
+    assert lib.ppo_head_update(C.byref(cfg), *args, 128, fake, 1, 64, None, fake, 16, None) == B.BRL_ENOSPC
+    assert lib.ppo_head_update(C.byref(cfg), *args, 128, fake, 1, 256, None, fake, 1 << 30, None) == B.BRL_EINVAL   # batch > T
+    assert lib.ppo_head_update(C.byref(cfg), *args, 128, fake, 1, 1, None, fake, 1 << 30, None) == B.BRL_EINVAL     # normalisation of one sample
+    assert lib.ppo_head_update(C.byref(cfg), *args, 128, None, 1, 64, None, fake, 1 << 30, None) == B.BRL_EINVAL
+    bad, keep2 = B.make_ppo_config([16, 8, 4], [12, 8, 1], B.BRL_ACT_TANH)
+    assert lib.brl_ppo_param_count(C.byref(bad)) == 0 and "input width" in err()
+    bad, keep3 = B.make_ppo_config([16, 8, 4], [16, 8, 2], B.BRL_ACT_TANH)
+    assert lib.brl_ppo_param_count(C.byref(bad)) == 0 and "one output" in err()
+    assert lib.ppo_gae(fake, fake, fake, fake, 1, 0, 0.99, 0.95, fake, fake, None) == B.BRL_EINVAL
+    assert lib.ppo_gae(fake, fake, fake, fake, 1, 8, 1.5, 0.95, fake, fake, None) == B.BRL_EINVAL
     # packed layout: the host copy of the cumulative lengths is checked before anything is launched
     enc = B.brl_encoder(0, 256, 4, 2, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
     import numpy as np
