@@ -57,6 +57,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=None, help="debug only: fewer layers (invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemv", action="store_true")
+    ap.add_argument("--no-ppo", action="store_true")
     ap.add_argument("--cpu-sample-states", type=int, default=2)
     ap.add_argument("--gemv-calls", type=int, default=1000)
     ap.add_argument("--streams", type=int, default=1,
@@ -217,6 +218,11 @@ def main() -> int:
     if not args.no_gemv and shape is synth.SHAPE_2B:
         single = bench_single_state(torch, B, R, synth, np, enc, head, shape)
 
+    # ---- PPO update of the heads on a cached rollout (the step after the path)
+    ppo = None
+    if not args.no_ppo and shape is synth.SHAPE_2B:
+        ppo = bench_ppo(torch, B, R, synth, np, shape, want_cpu)
+
     # ---- CPU oracle on a bounded sample of the same workload
     cpu = None
     if want_cpu:
@@ -268,6 +274,7 @@ def main() -> int:
         "int8_ceiling_states_per_s": round(Bn / (ops_step / (INT8_MFMA_PEAK_TOPS * 1e12)), 1),
         "gemv_pair": gemv,
         "single_state_latency": single,
+        "ppo_head_update": ppo,
         "concurrent_microbatches": concurrent,
         "paper_context": {"hardware": "Raspberry Pi 4 (Cortex-A72 @ 1.5 GHz), bitnet.cpp", "steps_per_s": 40.3,
                           "median_latency_ms": 24.8, "note": "one 15-40 token state per step; context only"},
@@ -334,6 +341,52 @@ def bench_single_state(torch, B, R, synth, np, enc, head, shape, n_tokens: int =
             "hip_graph_replay_ms_per_state": None if graph_ms is None else round(graph_ms, 4),
             "graph_replays_match_eager": same,
             "states_per_s_one_at_a_time": round(1e3 / (graph_ms if graph_ms else eager_ms), 1)}
+
+
+def bench_ppo(torch, B, R, synth, np, shape, want_cpu: bool, T: int = 2048, batch: int = 64, epochs: int = 4):
+    """One PPO update of the 2560->256->{18,1} heads on a cached 2048-step rollout (mini-batches of 64, 4 epochs:
+    128 optimiser steps), hyper-parameters of the paper's table; the oracle's fp64 update timed beside it."""
+    dims_p, dims_v = [shape.d, 256, shape.n_actions], [shape.d, 256, 1]
+    c = synth.ppo_rollout_case(0, T, shape.d, shape.n_actions, epochs)
+    pw, pb = synth.mlp_params(0, 60, dims_p)
+    vw, vb = synth.mlp_params(0, 80, dims_v)
+    rew, val, don, last = R.dev(c["rewards"]), R.dev(c["values"]), R.dev(c["dones"]), R.dev(c["last_value"])
+    h, actions, logp_old, perm = R.dev(c["h"]), R.dev(c["actions"]), R.dev(c["logp_old"]), R.dev(c["perm"])
+
+    def run():
+        tr = R.PPOTrainer((pw, pb), (vw, vb))
+        adv, ret = R.gae(rew, val, don, last, 0.99, 0.95)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tr.update(h, actions, logp_old, adv.reshape(-1), ret.reshape(-1), perm, batch, want_stats=False)
+        torch.cuda.synchronize()
+        return tr, (time.perf_counter() - t0) * 1e3
+
+    run()
+    times = []
+    for _ in range(3):
+        tr, ms = run()
+        times.append(ms)
+    ms = min(times)
+    steps = epochs * (T // batch)
+    out = {"rollout_steps": T, "batch": batch, "epochs": epochs, "optimiser_steps": steps, "ms_per_update": round(ms, 3),
+           "us_per_optimiser_step": round(ms / steps * 1e3, 2), "trainable_params": int(tr.params.numel()),
+           "kernel_launches_per_update": steps * 13, "cpu_oracle": None}
+    if want_cpu:
+        from oracle import ppo_oracle as P
+        adv_ref, ret_ref = P.gae(c["rewards"][0], c["values"][0], c["dones"][0], c["last_value"][0], 0.99, 0.95)
+        pol = P.MLPParams([w.astype(np.float64) for w in pw], [b.astype(np.float64) for b in pb])
+        vl = P.MLPParams([w.astype(np.float64) for w in vw], [b.astype(np.float64) for b in vb])
+        t0 = time.perf_counter()
+        P.ppo_update(c["h"].astype(np.float64), c["actions"], c["logp_old"].astype(np.float64),
+                     adv_ref.astype(np.float32).astype(np.float64), ret_ref.astype(np.float32).astype(np.float64),
+                     pol, vl, c["perm"], batch, P.PPOHyper())
+        cpu_ms = (time.perf_counter() - t0) * 1e3
+        got = tr.tensors()
+        dev_max = max(float(np.abs(g.astype(np.float64) - w).max()) for g, w in zip(got[0] + got[2], pol.weights + vl.weights))
+        out["cpu_oracle"] = {"ms_per_update": round(cpu_ms, 1), "kind": "oracle (NumPy fp64)",
+                             "max_abs_weight_difference_gpu_vs_oracle": dev_max}
+    return out
 
 
 def bench_gemv(torch, B, R, synth, calls: int):

@@ -87,29 +87,52 @@ __global__ void gae_kernel(const float* __restrict__ rewards, const float* __res
     }
 }
 
-// out[b, o] = act(sum_i W[o, i] in(b, i) + bias[o]); one wavefront per output, fp64 accumulation in lane order.
+// out[b, o] = act(sum_i W[o, i] in(b, i) + bias[o]); a wavefront takes one output unit o for FB consecutive samples
+// (the weight row is read once for all of them); each output is summed in fp64 in lane order, then folded.
 // in(b, i) = in64[b, i], or for the first layer the cached encoder output h[rows[b], i].
+constexpr int FB = 4;
 __global__ __launch_bounds__(256) void ppo_forward_kernel(const double* __restrict__ in64, const float* __restrict__ h,
                                                            const int32_t* __restrict__ rows, const float* __restrict__ W,
                                                            const float* __restrict__ bias, int B, int in_dim, int out_dim,
                                                            int act, int last, double* __restrict__ out) {
     const size_t wid = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    if (wid >= (size_t)B * out_dim) return;
-    const int b = (int)(wid / out_dim), o = (int)(wid % out_dim);
+    const int bgroups = (B + FB - 1) / FB;
+    if (wid >= (size_t)bgroups * out_dim) return;
+    const int bg = (int)(wid / out_dim), o = (int)(wid % out_dim);
     const float* w = W + (size_t)o * in_dim;
-    const float* hrow = in64 ? nullptr : h + (size_t)rows[b] * in_dim;
-    double acc = 0.0;
+    const float* hrow[FB];
+    const double* drow[FB];
+#pragma unroll
+    for (int q = 0; q < FB; ++q) {
+        const int b = min(bg * FB + q, B - 1);          // a clamped duplicate is computed and not stored
+        hrow[q] = in64 ? nullptr : h + (size_t)rows[b] * in_dim;
+        drow[q] = in64 ? in64 + (size_t)b * in_dim : nullptr;
+    }
+    double acc[FB];
+#pragma unroll
+    for (int q = 0; q < FB; ++q) acc[q] = 0.0;
+#pragma unroll 4
     for (int i = lane; i < in_dim; i += 64) {
-        const double v = in64 ? in64[(size_t)b * in_dim + i] : (double)hrow[i];
-        acc += (double)w[i] * v;
+        const double wi = (double)w[i];
+#pragma unroll
+        for (int q = 0; q < FB; ++q) acc[q] += wi * (in64 ? drow[q][i] : (double)hrow[q][i]);
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    for (int q = 0; q < FB; ++q) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) acc[q] += __shfl_xor(acc[q], off, 64);
+    }
     if (lane == 0) {
-        double z = acc + (double)bias[o];
-        if (!last) z = (act == BRL_ACT_RELU) ? fmax(z, 0.0) : tanh(z);
-        out[(size_t)b * out_dim + o] = z;
+#pragma unroll
+        for (int q = 0; q < FB; ++q) {
+            const int b = bg * FB + q;
+            if (b < B) {
+                double z = acc[q] + (double)bias[o];
+                if (!last) z = (act == BRL_ACT_RELU) ? fmax(z, 0.0) : tanh(z);
+                out[(size_t)b * out_dim + o] = z;
+            }
+        }
     }
 }
 
@@ -134,21 +157,38 @@ struct LossArgs {
 // clipped surrogate (Eq. 1), the entropy bonus and the value error, and their gradients at the heads' outputs.
 __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
     __shared__ double s_mean, s_inv;
-    if (threadIdx.x == 0) {
-        double mean = 0.0, inv = 1.0;
-        if (a.normalize_adv) {
-            for (int b = 0; b < a.B; ++b) mean += (double)a.adv[a.rows[b]];
-            mean /= (double)a.B;
-            double ss = 0.0;
-            for (int b = 0; b < a.B; ++b) {
-                const double d = (double)a.adv[a.rows[b]] - mean;
-                ss += d * d;
-            }
-            const double sd = a.B > 1 ? sqrt(ss / (double)(a.B - 1)) : 0.0;
-            inv = 1.0 / (sd + a.adv_eps);
+    __shared__ double red[256];
+    if (a.normalize_adv) {
+        // mean and (n - 1) standard deviation over the mini-batch: strided partial sums, then a fixed tree
+        double part = 0.0;
+        for (int b = threadIdx.x; b < a.B; b += 256) part += (double)a.adv[a.rows[b]];
+        red[threadIdx.x] = part;
+        __syncthreads();
+        for (int st = 128; st >= 1; st >>= 1) {
+            if ((int)threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+            __syncthreads();
         }
-        s_mean = mean;
-        s_inv = inv;
+        const double mean = red[0] / (double)a.B;
+        __syncthreads();
+        part = 0.0;
+        for (int b = threadIdx.x; b < a.B; b += 256) {
+            const double d = (double)a.adv[a.rows[b]] - mean;
+            part += d * d;
+        }
+        red[threadIdx.x] = part;
+        __syncthreads();
+        for (int st = 128; st >= 1; st >>= 1) {
+            if ((int)threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            const double sd = a.B > 1 ? sqrt(red[0] / (double)(a.B - 1)) : 0.0;
+            s_mean = mean;
+            s_inv = 1.0 / (sd + a.adv_eps);
+        }
+    } else if (threadIdx.x == 0) {
+        s_mean = 0.0;
+        s_inv = 1.0;
     }
     __syncthreads();
     for (int b = threadIdx.x; b < a.B; b += blockDim.x) {
@@ -201,29 +241,44 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
     }
 }
 
-// dW[o, i] = sum_b delta[b, o] in(b, i) (samples in order), db[o] = sum_b delta[b, o]; one thread per (o, i),
-// i fastest; the squares of a workgroup's gradients are summed to partial[blockIdx.x] for the global norm.
+// dW[o, i] = sum_b delta[b, o] in(b, i) (samples in order), db[o] = sum_b delta[b, o]; one thread per (group of GO
+// output units, i), i fastest, so an input value is read once for GO gradients; the squares of a workgroup's
+// gradients are summed (fixed tree) to partial[blockIdx.x] for the global norm.
+constexpr int GO = 4;
 __global__ __launch_bounds__(256) void ppo_weight_grad_kernel(const double* __restrict__ delta, const double* __restrict__ in64,
                                                                const float* __restrict__ h, const int32_t* __restrict__ rows,
                                                                int B, int in_dim, int out_dim, double* __restrict__ gW,
                                                                double* __restrict__ gb, double* __restrict__ partial) {
     __shared__ double red[256];
+    const int ogroups = (out_dim + GO - 1) / GO;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     double sq = 0.0;
-    if (idx < (size_t)out_dim * in_dim) {
-        const int o = (int)(idx / in_dim), i = (int)(idx % in_dim);
-        double acc = 0.0, accb = 0.0;
+    if (idx < (size_t)ogroups * in_dim) {
+        const int og = (int)(idx / in_dim), i = (int)(idx % in_dim);
+        const int o0 = og * GO;
+        double acc[GO], accb[GO];
+#pragma unroll
+        for (int q = 0; q < GO; ++q) { acc[q] = 0.0; accb[q] = 0.0; }
+#pragma unroll 8
         for (int b = 0; b < B; ++b) {
-            const double d = delta[(size_t)b * out_dim + o];
             const double x = in64 ? in64[(size_t)b * in_dim + i] : (double)h[(size_t)rows[b] * in_dim + i];
-            acc += d * x;
-            accb += d;
+#pragma unroll
+            for (int q = 0; q < GO; ++q) {
+                const double d = delta[(size_t)b * out_dim + min(o0 + q, out_dim - 1)];
+                acc[q] += d * x;
+                accb[q] += d;
+            }
         }
-        gW[idx] = acc;
-        sq = acc * acc;
-        if (i == 0) {
-            gb[o] = accb;
-            sq += accb * accb;
+#pragma unroll
+        for (int q = 0; q < GO; ++q) {
+            if (o0 + q < out_dim) {
+                gW[(size_t)(o0 + q) * in_dim + i] = acc[q];
+                sq += acc[q] * acc[q];
+                if (i == 0) {
+                    gb[o0 + q] = accb[q];
+                    sq += accb[q] * accb[q];
+                }
+            }
         }
     }
     red[threadIdx.x] = sq;
@@ -248,16 +303,25 @@ __global__ __launch_bounds__(256) void ppo_delta_kernel(const double* __restrict
     delta_prev[idx] = acc * (act == BRL_ACT_RELU ? (a > 0.0 ? 1.0 : 0.0) : 1.0 - a * a);
 }
 
-// scal[0] = global L2 norm of the gradients (partials summed in index order), scal[1] = min(1, max_norm / (norm + 1e-6))
-__global__ void ppo_norm_kernel(const double* __restrict__ partial, int n, double max_norm, double* __restrict__ scal,
-                                float* __restrict__ stats) {
-    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+// scal[0] = global L2 norm of the gradients, scal[1] = min(1, max_norm / (norm + 1e-6)); the partial sums are
+// added in a fixed order (thread t takes partials t, t + 256, ..., then a fixed tree): same result every run.
+__global__ __launch_bounds__(256) void ppo_norm_kernel(const double* __restrict__ partial, int n, double max_norm,
+                                                        double* __restrict__ scal, float* __restrict__ stats) {
+    __shared__ double red[256];
     double s = 0.0;
-    for (int i = 0; i < n; ++i) s += partial[i];
-    const double norm = sqrt(s);
-    scal[0] = norm;
-    scal[1] = fmin(1.0, max_norm / (norm + 1e-6));
-    if (stats) stats[4] = (float)norm;
+    for (int i = threadIdx.x; i < n; i += 256) s += partial[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int st = 128; st >= 1; st >>= 1) {
+        if ((int)threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double norm = sqrt(red[0]);
+        scal[0] = norm;
+        scal[1] = fmin(1.0, max_norm / (norm + 1e-6));
+        if (stats) stats[4] = (float)norm;
+    }
 }
 
 // Adam with bias correction on the clipped gradient: p -= lr (m / c1) / (sqrt(v / c2) + eps)
@@ -307,7 +371,7 @@ PpoWs ppo_ws_layout(const Layout& L, int batch) {
     for (int hd = 0; hd < 2; ++hd)
         for (int l = 0; l < L.head[hd].n; ++l) {
             W.partial_first[hd][l] = np;
-            np += (int)(((size_t)L.head[hd].dims[l + 1] * L.head[hd].dims[l] + 255) / 256);
+            np += (int)(((size_t)((L.head[hd].dims[l + 1] + GO - 1) / GO) * L.head[hd].dims[l] + 255) / 256);
         }
     W.n_partials = np;
     W.partial_off = take((size_t)np * 8);
@@ -404,7 +468,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                 for (int l = 0; l < H.n; ++l) {
                     const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
                     double* out = reinterpret_cast<double*>(base + W.act_off[hd][l]);
-                    const size_t waves = (size_t)batch * H.dims[l + 1];
+                    const size_t waves = (size_t)((batch + FB - 1) / FB) * H.dims[l + 1];
                     hipLaunchKernelGGL(ppo_forward_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, in64, h, rows,
                                        params + H.w_off[l], params + H.b_off[l], batch, H.dims[l], H.dims[l + 1], cfg->act,
                                        l == H.n - 1 ? 1 : 0, out);
@@ -430,7 +494,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                 int pp = 1;                 // next ping-pong buffer (delta[0] holds dlogits until the policy head is done)
                 for (int l = H.n - 1; l >= 0; --l) {
                     const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
-                    const size_t n = (size_t)H.dims[l + 1] * H.dims[l];
+                    const size_t n = (size_t)((H.dims[l + 1] + GO - 1) / GO) * H.dims[l];
                     hipLaunchKernelGGL(ppo_weight_grad_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dcur, in64, h,
                                        rows, batch, H.dims[l], H.dims[l + 1], grads + H.w_off[l], grads + H.b_off[l],
                                        partial + W.partial_first[hd][l]);
@@ -444,7 +508,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                     }
                 }
             }
-            hipLaunchKernelGGL(ppo_norm_kernel, dim3(1), dim3(64), 0, s, partial, W.n_partials, (double)cfg->max_grad_norm, scal, st);
+            hipLaunchKernelGGL(ppo_norm_kernel, dim3(1), dim3(256), 0, s, partial, W.n_partials, (double)cfg->max_grad_norm, scal, st);
             ++step;
             const double c1 = 1.0 - pow((double)cfg->adam_b1, (double)step);
             const double c2 = 1.0 - pow((double)cfg->adam_b2, (double)step);
