@@ -133,8 +133,9 @@ struct BCols {
 // consecutive columns of one row per lane and the result leaves as 16-byte
 // stores (512-byte runs per row for TN = 4):
 //     y = (float(acc - sum_q[m]) * dscale[m]) * beta[n] (+ residual)
-// Interior tiles take the unguarded 16-byte path; tiles on the M / N edge (or with
-// debug taps, or unaligned rows) take a compact per-element loop.
+// Tiles whose column blocks are all full take the 16-byte path (token rows past M are
+// masked); tiles on the N edge (or with debug taps, or unaligned rows) take a compact
+// per-element loop.
 template <int TM, int TN>
 struct Epi {
     static constexpr int W = TN * 32, LD = W + 4;
@@ -208,8 +209,9 @@ __device__ inline void epilogue_glu(const GemmArgs& g, v16i (&acc)[TM][TN], int 
                 const float pz = fmaxf(G, 0.f);
                 hv[q] = (pz * pz) * U;
             }
-            *reinterpret_cast<float4*>(g.y + (size_t)(mbase + row[p]) * g.ldy + col) =
-                make_float4(hv[0], hv[1], hv[2], hv[3]);
+            if (mbase + row[p] < g.M)
+                *reinterpret_cast<float4*>(g.y + (size_t)(mbase + row[p]) * g.ldy + col) =
+                    make_float4(hv[0], hv[1], hv[2], hv[3]);
         }
         __builtin_amdgcn_sched_barrier(0);       // keeps the requests of later half blocks from piling up here
     }
@@ -240,10 +242,10 @@ __device__ inline void epilogue_plain(const GemmArgs& g, v16i (&acc)[TM][TN], in
         // the residual is requested before the LDS turn of this half block and used after it
         constexpr int NPRE = RES ? NP : 1;
         float4 res[NPRE];
-        const float* rbase = g.residual + (size_t)mbase * g.ldy + col;
-        if constexpr (RES) {
+        if constexpr (RES) {     // rows past M are clamped for the load and never stored
 #pragma unroll
-            for (int p = 0; p < NPRE; ++p) res[p] = *reinterpret_cast<const float4*>(rbase + (size_t)row[p] * g.ldy);
+            for (int p = 0; p < NPRE; ++p)
+                res[p] = *reinterpret_cast<const float4*>(g.residual + (size_t)min(mbase + row[p], g.M - 1) * g.ldy + col);
         }
         scatter_half<TM, TN>(acc, idx >> 1, idx & 1, lane, scr);
 #pragma unroll
@@ -258,10 +260,10 @@ __device__ inline void epilogue_plain(const GemmArgs& g, v16i (&acc)[TM][TN], in
             val.z = ((float)(a.z - sq) * d) * my_beta;
             val.w = ((float)(a.w - sq) * d) * my_beta;
             if constexpr (RES) {
-                const float4 r = p < NPRE ? res[p] : *reinterpret_cast<const float4*>(rbase + (size_t)row[p] * g.ldy);
+                const float4 r = res[p];
                 val.x = val.x + r.x; val.y = val.y + r.y; val.z = val.z + r.z; val.w = val.w + r.w;
             }
-            *reinterpret_cast<float4*>(g.y + (size_t)(mbase + row[p]) * g.ldy + col) = val;
+            if (mbase + row[p] < g.M) *reinterpret_cast<float4*>(g.y + (size_t)(mbase + row[p]) * g.ldy + col) = val;
         }
         __builtin_amdgcn_sched_barrier(0);       // keeps the requests of later half blocks from piling up here
     }
@@ -271,7 +273,8 @@ template <int TM, int TN>
 __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, const float (&beta)[TN],
                                 int lane, int* scr) {
     constexpr int W = Epi<TM, TN>::W, LD = Epi<TM, TN>::LD;
-    const bool interior = g.fast_epilogue && (mb0 + TM) * 32 <= g.M && nb0 + TN <= g.nnb;
+    // full column blocks take the 16-byte paths (token rows past M are masked there)
+    const bool interior = g.fast_epilogue && mb0 * 32 < g.M && nb0 + TN <= g.nnb;
     if (interior) {
         if (g.glu) {
             if constexpr (TN % 2 == 0) epilogue_glu<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
@@ -465,8 +468,8 @@ __global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_kernel(GemmArgs g) {
 // Few-token kernel: operands straight from L2 to registers; WK wavefronts split k.
 // ---------------------------------------------------------------------------
 template <int TM, int TN, int WM, int WN, int WK>
-__global__ __launch_bounds__(256) void gemm_direct_kernel(GemmArgs g) {
-    static_assert(WM * WN * WK == 4, "four wavefronts per workgroup");
+__global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs g) {
+    static_assert(WM * WN * WK == 4 || WM * WN * WK == 8 || WM * WN * WK == 16, "4, 8 or 16 wavefronts per workgroup");
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wk = wave % WK;
@@ -574,7 +577,7 @@ int launch_direct(GemmArgs& g, hipStream_t s) {
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 7) / 8) * 8;
     LaunchTimer tm(BRL_KC_GEMM_NARROW, s, g.ops);
-    hipLaunchKernelGGL((gemm_direct_kernel<TM, TN, WM, WN, WK>), dim3(grid), dim3(256), 0, s, g);
+    hipLaunchKernelGGL((gemm_direct_kernel<TM, TN, WM, WN, WK>), dim3(grid), dim3(WM * WN * WK * 64), 0, s, g);
     BRL_LAUNCH_CHECK("gemm_direct_kernel");
     return BRL_OK;
 }
@@ -630,12 +633,14 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     (void)N;
     // Tile choice: k-split wavefronts for skinny (few-token) problems, where weight
     // streaming bounds the time; LDS-staged big tiles once the grid fills the chip.
+    // (up to 16 wavefronts split k for one or two token blocks: the chain of dependent loads per
+    // wavefront is what a short state waits for)
     if (glu) {   // a wavefront needs the gate and the up block of a column pair: even TN only
-        if (g.nmb <= 1) return launch_direct<1, 2, 1, 1, 4>(g, s);
+        if (g.nmb <= 1) return launch_direct<1, 2, 1, 1, 8>(g, s);
         if (g.nmb <= 2) return launch_direct<2, 2, 1, 1, 4>(g, s);
     } else {
-        if (g.nmb <= 1) return launch_direct<1, 1, 1, 1, 4>(g, s);
-        if (g.nmb <= 2) return launch_direct<2, 1, 1, 1, 4>(g, s);
+        if (g.nmb <= 1) return launch_direct<1, 1, 1, 1, 16>(g, s);
+        if (g.nmb <= 2) return launch_direct<2, 1, 1, 1, 8>(g, s);
         if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
     }
     // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64, two workgroups per CU) or 128 x 128 tiles
