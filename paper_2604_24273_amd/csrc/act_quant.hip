@@ -68,10 +68,12 @@ __device__ inline void load_rows(const QK& a, int row, int lane, int part, float
 // The 16 wavefronts of a workgroup take 16 / WPT tokens per round; WPT / 2 rounds fill the 8-token
 // group that is written out together.  A workgroup walks the groups g = blockIdx.x, + gridDim.x, ...
 // and requests the rows of its next round before it works on the current one.
-template <int HV4, int WPT>
+template <int HV4, int WPT, int GR>
 __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
     constexpr int TPR = 16 / WPT;          // tokens per round
-    constexpr int RPG = AQ_ROWS / TPR;     // rounds per 8-token group
+    constexpr int RPG = GR / TPR;          // rounds per group of GR tokens that is written out together
+    static_assert(GR == 8 || GR == 4, "groups of 8 tokens (128-byte runs) or 4 (64-byte runs, few tokens)");
+    static_assert(GR % TPR == 0, "a group is a whole number of rounds");
     extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // AQ_ROWS x (Kp + 16) bytes, then the gain
     __shared__ double red_ss[TPR][WPT];
     __shared__ float red_max[TPR][WPT];
@@ -81,14 +83,14 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
     const int rl = wave / WPT, part = wave % WPT;
     const int K = a.K;
     const int stride = a.Kp + 16;          // the 16-byte skew keeps the 8 rows on different LDS banks
-    const int ngroups = (a.M + AQ_ROWS - 1) / AQ_ROWS;
+    const int ngroups = (a.M + GR - 1) / GR;
 
     int grp = blockIdx.x, rnd = 0;
     float4 v[HV4];
-    load_rows<HV4, WPT>(a, grp * AQ_ROWS + rl, lane, part, v);
+    load_rows<HV4, WPT>(a, grp * GR + rl, lane, part, v);
 
     // the norm gain is the same for every token: parked in LDS once (read after the first barrier below)
-    float* gain_lds = reinterpret_cast<float*>(rowbuf + (size_t)AQ_ROWS * stride);
+    float* gain_lds = reinterpret_cast<float*>(rowbuf + (size_t)GR * stride);
     if (a.gain) {
         for (int k = 4 * threadIdx.x; k < K; k += 4 * AQ_THREADS)
             *reinterpret_cast<float4*>(gain_lds + k) = *reinterpret_cast<const float4*>(a.gain + k);
@@ -99,9 +101,9 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
         const int next_grp = next_rnd == 0 ? grp + (int)gridDim.x : grp;
         const bool more = next_grp < ngroups;
         float4 vn[HV4];
-        if (more) load_rows<HV4, WPT>(a, next_grp * AQ_ROWS + next_rnd * TPR + rl, lane, part, vn);
+        if (more) load_rows<HV4, WPT>(a, next_grp * GR + next_rnd * TPR + rl, lane, part, vn);
 
-        const int row0 = grp * AQ_ROWS;
+        const int row0 = grp * GR;
         const int row = row0 + rnd * TPR + rl;
         const bool live = row < a.M;
 
@@ -182,15 +184,15 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
         }
 
         if (rnd == RPG - 1) {
-            // tiled write-out: thread (token t8, chunk kc) moves the 16 bytes of k = 16 kc .. 16 kc + 15;
-            // the 8 tokens of one chunk are 128 contiguous bytes of the tile
-            const int t8 = threadIdx.x & 7;
+            // tiled write-out: thread (token t, chunk kc) moves the 16 bytes of k = 16 kc .. 16 kc + 15;
+            // the GR tokens of one chunk are GR * 16 contiguous bytes of the tile
+            const int t = threadIdx.x % GR;
             const int mb = row0 >> 5, r0 = row0 & 31;
             const int nchunks = a.Kp >> 4;
-            for (int kc = threadIdx.x >> 3; kc < nchunks; kc += AQ_THREADS / 8) {
-                const uint4 val = *reinterpret_cast<const uint4*>(rowbuf + (size_t)t8 * stride + 16 * kc);
+            for (int kc = threadIdx.x / GR; kc < nchunks; kc += AQ_THREADS / GR) {
+                const uint4 val = *reinterpret_cast<const uint4*>(rowbuf + (size_t)t * stride + 16 * kc);
                 const int sb = kc >> 3, dd = (kc >> 1) & 3, hh = kc & 1;
-                const size_t off = ((((size_t)mb * a.nsb + sb) * 4 + dd) * 64 + (hh * 32 + r0 + t8)) * 16;
+                const size_t off = ((((size_t)mb * a.nsb + sb) * 4 + dd) * 64 + (hh * 32 + r0 + t)) * 16;
                 *reinterpret_cast<uint4*>(a.q_tiled + off) = val;
             }
         }
@@ -204,13 +206,15 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
     }
 }
 
-template <int HV4, int WPT>
-int launch_one(const QK& a, int ngroups, size_t lds, hipStream_t s) {
+template <int HV4, int WPT, int GR>
+int launch_one(const QK& a, hipStream_t s) {
+    const int ngroups = (a.M + GR - 1) / GR;
+    const size_t lds = (size_t)GR * (a.Kp + 16) + (a.gain ? (size_t)a.Kp * 4 : 0);
     static int slots = 0;            // workgroups the device holds at once
     static bool raised = false;      // more than the default 64 KB of dynamic LDS allowed
-    constexpr size_t max_lds = (size_t)AQ_ROWS * (HV4 * WPT * 256 + 16) + (size_t)HV4 * WPT * 256 * 4;
+    constexpr size_t max_lds = (size_t)GR * (HV4 * WPT * 256 + 16) + (size_t)HV4 * WPT * 256 * 4;
     if (!raised && max_lds > 65536) {
-        BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<HV4, WPT>),
+        BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<HV4, WPT, GR>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds));
         raised = true;
     }
@@ -218,7 +222,7 @@ int launch_one(const QK& a, int ngroups, size_t lds, hipStream_t s) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, act_quant_kernel<HV4, WPT>, AQ_THREADS, max_lds) !=
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, act_quant_kernel<HV4, WPT, GR>, AQ_THREADS, max_lds) !=
                 hipSuccess ||
             cus <= 0 || per_cu <= 0) {
             (void)hipGetLastError();
@@ -228,7 +232,7 @@ int launch_one(const QK& a, int ngroups, size_t lds, hipStream_t s) {
         slots = cus * per_cu;
     }
     const int grid = ngroups < slots ? ngroups : slots;
-    hipLaunchKernelGGL((act_quant_kernel<HV4, WPT>), dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    hipLaunchKernelGGL((act_quant_kernel<HV4, WPT, GR>), dim3(grid), dim3(AQ_THREADS), lds, s, a);
     return BRL_OK;
 }
 
@@ -241,21 +245,21 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     a.M = in.M; a.K = in.K; a.Kp = round_up(in.K, SBK); a.nsb = a.Kp / SBK;
     a.q_tiled = out.q; a.absmax = out.absmax; a.dscale = out.dscale; a.sumq = out.sumq;
     a.xq_rowmajor = in.xq_rowmajor; a.absmax_tap = in.absmax_tap;
-    const int ngroups = (in.M + AQ_ROWS - 1) / AQ_ROWS;
-    const size_t lds = (size_t)AQ_ROWS * (a.Kp + 16) + (in.gain ? (size_t)a.Kp * 4 : 0);
-    // registers hold the current and the next row share of a lane: at most 2 x 9 float4
+    // registers hold the current and the next row share of a lane: at most 2 x 9 float4.  With few tokens
+    // the wide rows are taken 4 tokens per workgroup in one round (more, shorter workgroups).
     LaunchTimer tm(BRL_KC_ACT_QUANT, s);
+    const bool few = in.M <= 256;
     int rc;
     if (a.Kp <= 1024) {
-        rc = launch_one<2, 2>(a, ngroups, lds, s);
+        rc = launch_one<2, 2, 8>(a, s);
     } else if (a.Kp <= 3072) {
-        rc = launch_one<6, 2>(a, ngroups, lds, s);
+        rc = launch_one<6, 2, 8>(a, s);
     } else if (a.Kp <= 4608) {
-        rc = launch_one<9, 2>(a, ngroups, lds, s);
+        rc = launch_one<9, 2, 8>(a, s);
     } else if (a.Kp <= 7168) {
-        rc = launch_one<7, 4>(a, ngroups, lds, s);
+        rc = few ? launch_one<7, 4, 4>(a, s) : launch_one<7, 4, 8>(a, s);
     } else if (a.Kp <= MAX_K) {
-        rc = launch_one<9, 4>(a, ngroups, lds, s);
+        rc = few ? launch_one<9, 4, 4>(a, s) : launch_one<9, 4, 8>(a, s);
     } else {
         set_error("act_quant: K = %d exceeds the supported %d", in.K, MAX_K);
         return BRL_EINVAL;
