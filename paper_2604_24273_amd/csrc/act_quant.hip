@@ -251,11 +251,11 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     const bool few = in.M <= 256;
     int rc;
     if (a.Kp <= 1024) {
-        rc = launch_one<2, 2, 8>(a, s);
+        rc = few ? launch_one<1, 4, 4>(a, s) : launch_one<2, 2, 8>(a, s);
     } else if (a.Kp <= 3072) {
-        rc = launch_one<6, 2, 8>(a, s);
+        rc = few ? launch_one<3, 4, 4>(a, s) : launch_one<6, 2, 8>(a, s);
     } else if (a.Kp <= 4608) {
-        rc = launch_one<9, 2, 8>(a, s);
+        rc = few ? launch_one<5, 4, 4>(a, s) : launch_one<9, 2, 8>(a, s);
     } else if (a.Kp <= 7168) {
         rc = few ? launch_one<7, 4, 4>(a, s) : launch_one<7, 4, 8>(a, s);
     } else if (a.Kp <= MAX_K) {
