@@ -77,6 +77,19 @@ def test_encoder_2b_shape_full_batch_sampled_states():
     h20 = O.encoder_forward(ids[37:38, :20], emb, layers, gfin, cfg)
     assert _cos(hl[37], h20[0]) >= 0.999
     assert np.array_equal(hl[0], hg[0])
+    # the packed entry point in the configuration `bench.py --workload rl-states-2b` times:
+    # 1024 states of 15-40 tokens stored back to back; state 37 is again those 20 tokens
+    lens = synth.state_lengths(0, 501, 1024, 15, 40)
+    lens[37] = 20
+    wide = synth.token_ids(0, 500, (1024, 40), shape.vocab)
+    wide[37, :20] = ids[37, :20]
+    flat = np.concatenate([wide[i, :n] for i, n in enumerate(lens)]).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    print("encoder 2B shape: packed batch of 1024 states, %d tokens" % cu[-1], flush=True)
+    hp = enc.forward_packed(R.dev(flat), cu, max_len=40).cpu().numpy()
+    assert np.all(np.isfinite(hp))
+    assert _cos(hp[37], h20[0]) >= 0.999
+    assert np.array_equal(hp[37], hl[37])      # padded or packed, among 64 or among 1024 states: the same bits
 
 
 @pytest.mark.timeout(1500)
