@@ -8,11 +8,12 @@ squared-ReLU GLU, subLN, down BitLinear) -> final norm -> mean-pool -> fp32
 policy / value heads, at the 2B BitNet shape with 64 states x 128 tokens.
 Weights, embedding and ids are resident in HBM before the timed region.
 
-Prints ONE JSON line (see README for the fields).  Besides the
-headline states/s it carries the roofline of the dominant kernel (the int8
-MFMA GEMM, durations from HIP events recorded by the library around every
-launch in a second, identically sized region), the 1-token GEMV pair figures
-and the CPU oracle timed on a bounded sample as context.
+Prints ONE JSON line.  Besides the headline states/s it carries the roofline
+of the dominant kernel (the int8 MFMA GEMM, durations from HIP events recorded
+by the library around every launch in a second, identically sized region), the
+1-token GEMV pair figures (one launch per product, and the whole walk as two
+batched launches), the latency of one short state per call, one PPO update of
+the heads, and the CPU oracle timed on a bounded sample as context.
 """
 from __future__ import annotations
 
@@ -58,13 +59,14 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gemv", action="store_true")
     ap.add_argument("--no-ppo", action="store_true")
+    ap.add_argument("--no-single-state", action="store_true")
     ap.add_argument("--cpu-sample-states", type=int, default=2)
     ap.add_argument("--gemv-calls", type=int, default=1000)
     ap.add_argument("--streams", type=int, default=1,
                     help="extra leg: also time the batch as this many concurrent micro-batches on separate HIP streams")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
@@ -215,7 +217,7 @@ def main() -> int:
 
     # ---- one short state per call (the paper's deployment shape: a 15-40 token state per environment step)
     single = None
-    if not args.no_gemv and shape is synth.SHAPE_2B:
+    if not args.no_gemv and not args.no_single_state and shape is synth.SHAPE_2B:
         single = bench_single_state(torch, B, R, synth, np, enc, head, shape)
 
     # ---- PPO update of the heads on a cached rollout (the step after the path)

@@ -144,7 +144,6 @@ int launch_final_pool(const float* x, const float* gain, int B, int S, int M, in
                       const SeqMap& sm, float eps_norm, float* rinv, float* h, hipStream_t s);
 int launch_mlp_layer(const double* in64, const float* in32, const float* W, const float* b, int B, int in_dim,
                      int out_dim, int act, double* out64, float* out32, hipStream_t s);
-int launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s);   // n % 8 == 0
 
 }  // namespace brl

@@ -1,17 +1,10 @@
 // Small kernels around the BitLinear core: embedding gather, final RMSNorm +
-// mean-pool (paper Sec. 3.1, Eq. 3: h_t), the fp32 MLP heads, zero fill.
+// mean-pool (paper Sec. 3.1, Eq. 3: h_t), the fp32 MLP heads.
 #include "common.hpp"
 
 namespace brl {
 
 namespace {
-
-__global__ void fill_zero_kernel(uint4* p, size_t n16, unsigned char* tail, size_t ntail) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t k = i; k < n16; k += stride) p[k] = make_uint4(0, 0, 0, 0);
-    if (i < ntail) tail[i] = 0;
-}
 
 // x[m, :] = widen(E[clamp(ids[m]), :]); eight bf16 per thread
 __global__ void embed_kernel(const uint16_t* __restrict__ table, const int32_t* __restrict__ ids, int M, int d,
@@ -112,19 +105,6 @@ __global__ __launch_bounds__(256) void mlp_layer_kernel(const double* __restrict
 }
 
 }  // namespace
-
-int launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
-    if (bytes == 0) return BRL_OK;
-    const size_t n16 = bytes / 16;
-    size_t blocks = (n16 + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    if (blocks < 1) blocks = 1;
-    LaunchTimer tm(BRL_KC_OTHER, s);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16,
-                       reinterpret_cast<unsigned char*>(p) + n16 * 16, bytes - n16 * 16);
-    BRL_LAUNCH_CHECK("fill_zero_kernel");
-    return BRL_OK;
-}
 
 int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s) {
     const size_t n8 = n / 8;
