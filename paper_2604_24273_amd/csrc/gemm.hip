@@ -14,12 +14,13 @@
 // has to agree between the two operands - it does, by construction of the layouts.
 //
 // Two kernels:
-//   gemm_lds_kernel    many tokens: the activation tile of a workgroup (up to
-//                      256 tokens x 128 k) is staged in LDS with direct
-//                      global->LDS loads, double buffered; the tiny packed weight
-//                      fragments go straight from L2 to registers.
+//   gemm_lds_kernel    many tokens: both operand tiles of a workgroup (128 tokens
+//                      x 128 k, and 256 or 128 weight rows x 128 k still packed)
+//                      are staged in LDS with direct global->LDS loads, double
+//                      buffered; in GLU mode the epilogue writes
+//                      h = max(G,0)^2 U from interleaved gate / up blocks.
 //   gemm_direct_kernel few tokens (weight streaming bound): no LDS staging, the
-//                      four wavefronts of a workgroup may split k.
+//                      4 to 16 wavefronts of a workgroup may split k.
 #include "common.hpp"
 
 namespace brl {
