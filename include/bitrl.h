@@ -172,7 +172,11 @@ int ffn_block_forward(const brl_ffn_weights* w /* HOST */, const void* x, int x_
  * feed-forward block above.  h[b] = mean over the first lengths[b] positions
  * (all S if lengths is NULL) of RMSNorm(x; final_norm_g), summed in fp64.
  * States are independent; large batches are processed in micro-batches of
- * whole states inside the call.
+ * whole states inside the call.  Like every *_forward here the call only
+ * enqueues kernels on `stream` (no allocation, no synchronisation), so a
+ * sequence of calls can be captured into a HIP graph - after one ordinary call
+ * of the same shapes, because the first use of a kernel queries the device's
+ * occupancy limits once.
  * ids [B, S] int32, lengths [B] int32 in [1, S] or NULL, h [B, d] fp32.
  * ------------------------------------------------------------------------ */
 typedef struct brl_layer_weights {

@@ -140,3 +140,20 @@ def test_product_never_imports_the_oracle():
             if fn.endswith(".py"):
                 txt = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in txt.replace("CPU oracle's tests", ""), fn
+
+
+def test_profile_summary_reads_rocprof_csv(tmp_path):
+    """The summariser behind profiles/*.txt: per-kernel averages from a kernel trace and a counter file."""
+    from paper_2604_24273_amd import profile_summary as PS
+    d = tmp_path / "out" / "host"
+    d.mkdir(parents=True)
+    (d / "1_kernel_trace.csv").write_text(
+        '"Kind","Agent_Id","Queue_Id","Kernel_Id","Kernel_Name","Correlation_Id","Start_Timestamp","End_Timestamp"\n'
+        '"KERNEL_DISPATCH",1,1,1,"k_a",1,1000,3000\n"KERNEL_DISPATCH",1,1,1,"k_a",2,5000,9000\n'
+        '"KERNEL_DISPATCH",1,1,2,"k_b",3,100,200\n')
+    (d / "1_counter_collection.csv").write_text(
+        '"Dispatch_Id","Kernel_Name","Counter_Name","Counter_Value"\n1,"k_a","FETCH_SIZE",10\n2,"k_a","FETCH_SIZE",30\n')
+    text = PS.summarise(str(tmp_path / "out"))
+    row_a = [l for l in text.splitlines() if l.startswith("k_a") and "FETCH" not in l][0].split()
+    assert row_a[1] == "2" and abs(float(row_a[2]) - 3.0) < 1e-9          # two calls, 3.00 us on average
+    assert "avg 20" in [l for l in text.splitlines() if "FETCH_SIZE" in l][0]
