@@ -1,11 +1,13 @@
 /*
  * bitrl.h - C ABI of the MI355X (gfx950) forward pass of BitRL's frozen
- * ternary state encoder and its fp32 policy / value heads.
+ * ternary state encoder and its fp32 policy / value heads, and of the PPO
+ * update of those heads on cached encoder outputs.
  *
  * The library computes h_t = f(token ids) and (logits, V) = (g(h_t), v(h_t))
  * (paper Sec. 3.1, Eq. 3) for a BitNet-b1.58 style backbone whose linear
  * layers are BitLinear: ternary weights (Sec. 3.1, Eq. 2), per-token int8
- * activations, integer accumulation, fp32 rescale.
+ * activations, integer accumulation, fp32 rescale; and one clipped-surrogate
+ * update (Sec. 3.1, Eq. 1; Sec. 3.2) of the head parameters.
  *
  * Conventions for every function
  * ------------------------------
@@ -28,8 +30,8 @@
  *    synchronises the stream once so that it can report bad weights.
  *  - Non-finite activations are not checked: results are then unspecified
  *    (never out-of-bounds accesses).  Token ids outside [0, vocab) are clamped.
- *  - Limits: 1 <= K <= 9216 input features per BitLinear (one token row is
- *    held in the registers of one wavefront), any N, any M.
+ *  - Limits: 1 <= K <= 9216 input features per BitLinear (a token row is
+ *    held in the registers of the wavefronts that quantise it), any N, any M.
  */
 #ifndef BITRL_H
 #define BITRL_H

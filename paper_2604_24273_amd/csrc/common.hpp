@@ -46,7 +46,7 @@ struct LaunchTimer {
 constexpr int WAVE = 64;
 constexpr int NB = 32;        // rows of one weight block / tokens of one activation block
 constexpr int SBK = 128;      // columns of one super-block (four MFMA k-steps of 32)
-constexpr int MAX_K = 9216;   // one token row is held in one wavefront's registers
+constexpr int MAX_K = 9216;   // widest token row the quantisation kernels hold in registers (4 wavefronts x 9 float4 per lane)
 
 __host__ __device__ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 __host__ __device__ inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
