@@ -27,6 +27,8 @@
 // the 8 keys a lane's probabilities stand for are 16 contiguous bytes.
 #include "common.hpp"
 
+#include <cstdlib>
+
 namespace brl {
 
 namespace {
@@ -185,12 +187,13 @@ template <int DHP>
 struct AttnTile {
     static constexpr int KS = DHP / 16, DB = DHP / 32;
     static constexpr int KVFR = KS * 2 + DB * 4;      // 1 KB fragments per key block (K hi/lo, then V hi/lo)
-    static constexpr int PPW = KVFR / 4;              // copied per wavefront
-
+    // the WPG wavefronts of a workgroup copy KVFR / WPG fragments each
+    template <int WPG>
     static __device__ inline void issue(const uint4* src, uint4* st, int wave, int lane) {
+        static_assert(KVFR % WPG == 0, "fragments divide evenly over the wavefronts");
 #pragma unroll
-        for (int c = 0; c < PPW; ++c) {
-            const int f = c * 4 + wave;
+        for (int c = 0; c < KVFR / WPG; ++c) {
+            const int f = c * WPG + wave;
             __builtin_amdgcn_global_load_lds(src + f * 64 + lane, st + f * 64, 16, 0, 0);
         }
     }
@@ -248,8 +251,9 @@ struct AttnTile {
     }
 };
 
-template <int DHP, int VW>
-__global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
+// WPG wavefronts (4 or 8) = WPG units of one key/value head share every K / V block.
+template <int DHP, int VW, int WPG>
+__global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a) {
     using T = AttnTile<DHP>;
     constexpr int KS = T::KS, DB = T::DB;
     __shared__ __attribute__((aligned(1024))) uint4 stage0[T::KVFR * 64];
@@ -258,7 +262,7 @@ __global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int group = a.Hq / a.Hkv;
     const int U = group * a.NRB;                      // (head in group, query block) units of one key/value head
-    const int chunks = (U + 3) / 4;
+    const int chunks = (U + WPG - 1) / WPG;
     // consecutive work items (the chunks of one key/value head) run on one XCD and share its L2;
     // the longest chunks of a head come first
     const int per_xcd = (a.n_work + 7) >> 3;
@@ -270,9 +274,9 @@ __global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
     const int len = seq_len(a.sm, b, a.S);
     const int nrb = (len + 31) >> 5;                  // query / key blocks this state really has
     const size_t row0 = (size_t)seq_row0(a.sm, b, a.S);
-    const int u0 = 4 * c, u1 = min(U, u0 + 4) - 1;
+    const int u0 = WPG * c, u1 = min(U, u0 + WPG) - 1;
     const int kb_max = min((u0 / a.NRB != u1 / a.NRB) ? a.NRB - 1 : u1 % a.NRB, nrb - 1);
-    if (kb_max < 0 || (u0 / a.NRB == u1 / a.NRB && u0 % a.NRB >= nrb)) return;   // none of the four units exists
+    if (kb_max < 0 || (u0 / a.NRB == u1 / a.NRB && u0 % a.NRB >= nrb)) return;   // none of the units exists
     const int u = u0 + wave;
     const bool live = u < U && u % a.NRB < nrb;
     const int head = j * group + (live ? u / a.NRB : 0);
@@ -281,21 +285,28 @@ __global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
     v8h qh[KS], ql[KS];
     const int qpos = qb * 32 + (lane & 31);
     {
-        // the stage buffers are free before the first key block arrives: park this wavefront's q rows there
-        char* region = reinterpret_cast<char*>(wave < 2 ? stage0 : stage1) + (wave & 1) * (128 * DHP);
-        if (live) {
-            const int half = a.dh / 2;
-            stage_rope_rows<DHP, VW>(a.qkv + (row0 + qb * 32) * a.ld + head * a.dh, a.ld,
-                                     min(32, len - qb * 32), a.cos_t + (size_t)qb * 32 * half,
-                                     a.sin_t + (size_t)qb * 32 * half, a.dh, a.qscale, region, lane);
-        }
-        __syncthreads();
+        // the stage buffers are free before the first key block arrives: the q rows are parked there,
+        // four wavefronts at a time
+        char* region = reinterpret_cast<char*>((wave & 2) ? stage1 : stage0) + (wave & 1) * (128 * DHP);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            qh[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 0));
-            ql[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 1));
+        for (int rnd = 0; rnd < WPG / 4; ++rnd) {
+            const bool mine = (wave >> 2) == rnd;
+            if (mine && live) {
+                const int half = a.dh / 2;
+                stage_rope_rows<DHP, VW>(a.qkv + (row0 + qb * 32) * a.ld + head * a.dh, a.ld,
+                                         min(32, len - qb * 32), a.cos_t + (size_t)qb * 32 * half,
+                                         a.sin_t + (size_t)qb * 32 * half, a.dh, a.qscale, region, lane);
+            }
+            __syncthreads();
+            if (mine) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    qh[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 0));
+                    ql[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 1));
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
     v16f o[DB];
 #pragma unroll
@@ -305,16 +316,16 @@ __global__ __launch_bounds__(256, 2) void attention_frag_kernel(FragArgs a) {
     float m_run = -INFINITY, l_run = 0.f;
 
     const uint4* kv = a.KVF + (size_t)(b * a.Hkv + j) * a.NRB * T::KVFR * 64;
-    T::issue(kv, stage0, wave, lane);
+    T::template issue<WPG>(kv, stage0, wave, lane);
     int kb = 0;
     for (; kb + 1 <= kb_max; kb += 2) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        T::issue(kv + (size_t)(kb + 1) * T::KVFR * 64, stage1, wave, lane);
+        T::template issue<WPG>(kv + (size_t)(kb + 1) * T::KVFR * 64, stage1, wave, lane);
         if (kb <= qb) T::compute(stage0, qh, ql, o, m_run, l_run, kb == qb, lane);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (kb + 2 <= kb_max) T::issue(kv + (size_t)(kb + 2) * T::KVFR * 64, stage0, wave, lane);
+        if (kb + 2 <= kb_max) T::template issue<WPG>(kv + (size_t)(kb + 2) * T::KVFR * 64, stage0, wave, lane);
         if (kb + 1 <= qb) T::compute(stage1, qh, ql, o, m_run, l_run, kb + 1 == qb, lane);
     }
     if (kb <= kb_max) {
@@ -358,9 +369,13 @@ size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int he
 namespace {
 
 template <int DHP, int VW>
-void launch_pair(const PackArgs& p, const FragArgs& f, dim3 pgrid, dim3 agrid, hipStream_t s) {
+void launch_pair(const PackArgs& p, const FragArgs& f, dim3 pgrid, int n_work, int wpg, hipStream_t s) {
     hipLaunchKernelGGL((attn_pack_kernel<DHP, VW>), pgrid, dim3(256), 0, s, p);
-    hipLaunchKernelGGL((attention_frag_kernel<DHP, VW>), agrid, dim3(256), 0, s, f);
+    const dim3 agrid((unsigned)(8 * ((n_work + 7) / 8)));
+    if (wpg == 8)
+        hipLaunchKernelGGL((attention_frag_kernel<DHP, VW, 8>), agrid, dim3(512), 0, s, f);
+    else
+        hipLaunchKernelGGL((attention_frag_kernel<DHP, VW, 4>), agrid, dim3(256), 0, s, f);
 }
 
 }  // namespace
@@ -375,7 +390,10 @@ int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& 
     const int dhp = padded_head_dim(head_dim);
     const int nrb = (S + 31) / 32;
     const int group = n_heads / n_kv_heads;
-    const int chunks = (group * nrb + 3) / 4;
+    // long multi-head sequences: eight query blocks per workgroup halve the K / V traffic
+    static const int forced = getenv("BRL_ATTN_WPG") ? atoi(getenv("BRL_ATTN_WPG")) : 0;
+    const int wpg = forced ? forced : ((group == 1 && nrb >= 8) ? 8 : 4);
+    const int chunks = (group * nrb + wpg - 1) / wpg;
     PackArgs p;
     p.qkv = qkv; p.ld = ld; p.B = B; p.S = S; p.NRB = nrb; p.Hq = n_heads; p.Hkv = n_kv_heads; p.dh = head_dim;
     p.sm = sm;
@@ -389,15 +407,14 @@ int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& 
     f.n_work = B * n_kv_heads * chunks;
     f.out = out;
     const dim3 pgrid((unsigned)((size_t)B * nrb * n_kv_heads));
-    const dim3 agrid((unsigned)(8 * ((f.n_work + 7) / 8)));
     const bool v4 = (head_dim / 2) % 4 == 0;          // rotary halves and head rows 16-byte aligned
     LaunchTimer tm(BRL_KC_ATTENTION, s);
     if (dhp == 32) {
-        if (v4) launch_pair<32, 4>(p, f, pgrid, agrid, s); else launch_pair<32, 2>(p, f, pgrid, agrid, s);
+        if (v4) launch_pair<32, 4>(p, f, pgrid, f.n_work, wpg, s); else launch_pair<32, 2>(p, f, pgrid, f.n_work, wpg, s);
     } else if (dhp == 64) {
-        if (v4) launch_pair<64, 4>(p, f, pgrid, agrid, s); else launch_pair<64, 2>(p, f, pgrid, agrid, s);
+        if (v4) launch_pair<64, 4>(p, f, pgrid, f.n_work, wpg, s); else launch_pair<64, 2>(p, f, pgrid, f.n_work, wpg, s);
     } else {
-        if (v4) launch_pair<128, 4>(p, f, pgrid, agrid, s); else launch_pair<128, 2>(p, f, pgrid, agrid, s);
+        if (v4) launch_pair<128, 4>(p, f, pgrid, f.n_work, wpg, s); else launch_pair<128, 2>(p, f, pgrid, f.n_work, wpg, s);
     }
     BRL_LAUNCH_CHECK("attention_mfma");
     return BRL_OK;

@@ -242,6 +242,7 @@ def _oracle_encoder(shape, seed, layers_host):
     (dict(n_layers=2, d=200, n_heads=2, n_kv_heads=2, head_dim=100, f=392, vocab=64), 2, 33),
     (dict(n_layers=1, d=256, n_heads=2, n_kv_heads=1, head_dim=128, f=512, vocab=1000), 4, 130),
     (dict(n_layers=2, d=64, n_heads=2, n_kv_heads=1, head_dim=32, f=128, vocab=50), 1, 1),
+    (dict(n_layers=1, d=128, n_heads=4, n_kv_heads=4, head_dim=32, f=264, vocab=300), 2, 300),   # long multi-head states
 ])
 @pytest.mark.parametrize("attn", ["mfma", "f32"])
 def test_encoder_small_shapes(kw, b, s, attn):
