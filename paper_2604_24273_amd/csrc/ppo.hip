@@ -87,19 +87,18 @@ __global__ void gae_kernel(const float* __restrict__ rewards, const float* __res
     }
 }
 
-// out[b, o] = act(sum_i W[o, i] in(b, i) + bias[o]); a wavefront takes one output unit o for FB consecutive samples
-// (the weight row is read once for all of them); each output is summed in fp64 in lane order, then folded.
+// out[b, o] = act(sum_i W[o, i] in(b, i) + bias[o]); a workgroup takes one output unit o for FB consecutive
+// samples (the weight row is read once for all of them); its four wavefronts take a quarter of the inputs each,
+// sum in fp64 in lane order, fold, and wavefront 0 adds the four parts in order.
 // in(b, i) = in64[b, i], or for the first layer the cached encoder output h[rows[b], i].
 constexpr int FB = 4;
 __global__ __launch_bounds__(256) void ppo_forward_kernel(const double* __restrict__ in64, const float* __restrict__ h,
                                                            const int32_t* __restrict__ rows, const float* __restrict__ W,
                                                            const float* __restrict__ bias, int B, int in_dim, int out_dim,
                                                            int act, int last, double* __restrict__ out) {
-    const size_t wid = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    const int bgroups = (B + FB - 1) / FB;
-    if (wid >= (size_t)bgroups * out_dim) return;
-    const int bg = (int)(wid / out_dim), o = (int)(wid % out_dim);
+    __shared__ double part[4][FB];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int bg = (int)(blockIdx.x / out_dim), o = (int)(blockIdx.x % out_dim);
     const float* w = W + (size_t)o * in_dim;
     const float* hrow[FB];
     const double* drow[FB];
@@ -109,11 +108,13 @@ __global__ __launch_bounds__(256) void ppo_forward_kernel(const double* __restri
         hrow[q] = in64 ? nullptr : h + (size_t)rows[b] * in_dim;
         drow[q] = in64 ? in64 + (size_t)b * in_dim : nullptr;
     }
+    const int quarter = (in_dim + 3) / 4;
+    const int i_end = min(in_dim, (wave + 1) * quarter);
     double acc[FB];
 #pragma unroll
     for (int q = 0; q < FB; ++q) acc[q] = 0.0;
 #pragma unroll 4
-    for (int i = lane; i < in_dim; i += 64) {
+    for (int i = wave * quarter + lane; i < i_end; i += 64) {
         const double wi = (double)w[i];
 #pragma unroll
         for (int q = 0; q < FB; ++q) acc[q] += wi * (in64 ? drow[q][i] : (double)hrow[q][i]);
@@ -125,13 +126,15 @@ __global__ __launch_bounds__(256) void ppo_forward_kernel(const double* __restri
     }
     if (lane == 0) {
 #pragma unroll
-        for (int q = 0; q < FB; ++q) {
-            const int b = bg * FB + q;
-            if (b < B) {
-                double z = acc[q] + (double)bias[o];
-                if (!last) z = (act == BRL_ACT_RELU) ? fmax(z, 0.0) : tanh(z);
-                out[(size_t)b * out_dim + o] = z;
-            }
+        for (int q = 0; q < FB; ++q) part[wave][q] = acc[q];
+    }
+    __syncthreads();
+    if (threadIdx.x < FB) {
+        const int q = threadIdx.x, b = bg * FB + q;
+        if (b < B) {
+            double z = ((part[0][q] + part[1][q]) + part[2][q]) + part[3][q] + (double)bias[o];
+            if (!last) z = (act == BRL_ACT_RELU) ? fmax(z, 0.0) : tanh(z);
+            out[(size_t)b * out_dim + o] = z;
         }
     }
 }
@@ -241,53 +244,63 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
     }
 }
 
-// dW[o, i] = sum_b delta[b, o] in(b, i) (samples in order), db[o] = sum_b delta[b, o]; one thread per (group of GO
-// output units, i), i fastest, so an input value is read once for GO gradients; the squares of a workgroup's
-// gradients are summed (fixed tree) to partial[blockIdx.x] for the global norm.
+// dW[o, i] = sum_b delta[b, o] in(b, i), db[o] = sum_b delta[b, o].  A workgroup takes GO output units and 64
+// consecutive inputs; its four wavefronts take a quarter of the samples each (in order), and wavefront 0 adds the
+// four parts in order.  The squares of the workgroup's gradients are summed (fixed tree) to partial[blockIdx.x]
+// for the global norm.
 constexpr int GO = 4;
 __global__ __launch_bounds__(256) void ppo_weight_grad_kernel(const double* __restrict__ delta, const double* __restrict__ in64,
                                                                const float* __restrict__ h, const int32_t* __restrict__ rows,
                                                                int B, int in_dim, int out_dim, double* __restrict__ gW,
                                                                double* __restrict__ gb, double* __restrict__ partial) {
-    __shared__ double red[256];
-    const int ogroups = (out_dim + GO - 1) / GO;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    double sq = 0.0;
-    if (idx < (size_t)ogroups * in_dim) {
-        const int og = (int)(idx / in_dim), i = (int)(idx % in_dim);
-        const int o0 = og * GO;
-        double acc[GO], accb[GO];
+    __shared__ double part[4][GO][64];
+    __shared__ double partb[4][GO];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int ichunks = (in_dim + 63) / 64;
+    const int og = (int)(blockIdx.x / ichunks), ic = (int)(blockIdx.x % ichunks);
+    const int o0 = og * GO;
+    const int i = ic * 64 + lane;
+    const int ii = min(i, in_dim - 1);
+    const int bq = (B + 3) / 4;
+    const int b_end = min(B, (wave + 1) * bq);
+    double acc[GO], accb[GO];
 #pragma unroll
-        for (int q = 0; q < GO; ++q) { acc[q] = 0.0; accb[q] = 0.0; }
-#pragma unroll 8
-        for (int b = 0; b < B; ++b) {
-            const double x = in64 ? in64[(size_t)b * in_dim + i] : (double)h[(size_t)rows[b] * in_dim + i];
-#pragma unroll
-            for (int q = 0; q < GO; ++q) {
-                const double d = delta[(size_t)b * out_dim + min(o0 + q, out_dim - 1)];
-                acc[q] += d * x;
-                accb[q] += d;
-            }
-        }
+    for (int q = 0; q < GO; ++q) { acc[q] = 0.0; accb[q] = 0.0; }
+#pragma unroll 4
+    for (int b = wave * bq; b < b_end; ++b) {
+        const double x = in64 ? in64[(size_t)b * in_dim + ii] : (double)h[(size_t)rows[b] * in_dim + ii];
 #pragma unroll
         for (int q = 0; q < GO; ++q) {
-            if (o0 + q < out_dim) {
-                gW[(size_t)(o0 + q) * in_dim + i] = acc[q];
-                sq += acc[q] * acc[q];
+            const double d = delta[(size_t)b * out_dim + min(o0 + q, out_dim - 1)];
+            acc[q] += d * x;
+            accb[q] += d;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < GO; ++q) {
+        part[wave][q][lane] = acc[q];
+        if (lane == 0) partb[wave][q] = accb[q];
+    }
+    __syncthreads();
+    double sq = 0.0;
+    if (wave == 0) {
+#pragma unroll
+        for (int q = 0; q < GO; ++q) {
+            if (o0 + q < out_dim && i < in_dim) {
+                const double g = ((part[0][q][lane] + part[1][q][lane]) + part[2][q][lane]) + part[3][q][lane];
+                gW[(size_t)(o0 + q) * in_dim + i] = g;
+                sq += g * g;
                 if (i == 0) {
-                    gb[o0 + q] = accb[q];
-                    sq += accb[q] * accb[q];
+                    const double gbv = ((partb[0][q] + partb[1][q]) + partb[2][q]) + partb[3][q];
+                    gb[o0 + q] = gbv;
+                    sq += gbv * gbv;
                 }
             }
         }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sq += __shfl_xor(sq, off, 64);
+        if (lane == 0) partial[blockIdx.x] = sq;
     }
-    red[threadIdx.x] = sq;
-    __syncthreads();
-    for (int s = 128; s >= 1; s >>= 1) {
-        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
 // delta_prev[b, i] = (sum_o delta[b, o] W[o, i]) * act'(a[b, i]), a = the activated output of the layer below
@@ -371,7 +384,7 @@ PpoWs ppo_ws_layout(const Layout& L, int batch) {
     for (int hd = 0; hd < 2; ++hd)
         for (int l = 0; l < L.head[hd].n; ++l) {
             W.partial_first[hd][l] = np;
-            np += (int)(((size_t)((L.head[hd].dims[l + 1] + GO - 1) / GO) * L.head[hd].dims[l] + 255) / 256);
+            np += ((L.head[hd].dims[l + 1] + GO - 1) / GO) * ((L.head[hd].dims[l] + 63) / 64);
         }
     W.n_partials = np;
     W.partial_off = take((size_t)np * 8);
@@ -468,8 +481,8 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                 for (int l = 0; l < H.n; ++l) {
                     const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
                     double* out = reinterpret_cast<double*>(base + W.act_off[hd][l]);
-                    const size_t waves = (size_t)((batch + FB - 1) / FB) * H.dims[l + 1];
-                    hipLaunchKernelGGL(ppo_forward_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, in64, h, rows,
+                    const size_t blocks = (size_t)((batch + FB - 1) / FB) * H.dims[l + 1];
+                    hipLaunchKernelGGL(ppo_forward_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in64, h, rows,
                                        params + H.w_off[l], params + H.b_off[l], batch, H.dims[l], H.dims[l + 1], cfg->act,
                                        l == H.n - 1 ? 1 : 0, out);
                 }
@@ -494,8 +507,8 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                 int pp = 1;                 // next ping-pong buffer (delta[0] holds dlogits until the policy head is done)
                 for (int l = H.n - 1; l >= 0; --l) {
                     const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
-                    const size_t n = (size_t)((H.dims[l + 1] + GO - 1) / GO) * H.dims[l];
-                    hipLaunchKernelGGL(ppo_weight_grad_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dcur, in64, h,
+                    const size_t blocks = (size_t)((H.dims[l + 1] + GO - 1) / GO) * ((H.dims[l] + 63) / 64);
+                    hipLaunchKernelGGL(ppo_weight_grad_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dcur, in64, h,
                                        rows, batch, H.dims[l], H.dims[l + 1], grads + H.w_off[l], grads + H.b_off[l],
                                        partial + W.partial_first[hd][l]);
                     if (l > 0) {

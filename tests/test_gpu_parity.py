@@ -320,3 +320,47 @@ def test_head_parity_and_variants():
         assert_fp_close(value.cpu().numpy(), vr)
         p = O.softmax(logits.cpu().numpy())
         assert np.allclose(p.sum(axis=1), 1.0)
+
+
+def test_entry_points_replay_from_a_hip_graph():
+    """encoder_forward_packed + policy_value_head enqueue kernels only: captured once (after one ordinary call),
+    every replay - with eager calls and synchronisations in between - reproduces the eager result bit for bit."""
+    B, R = _mods()
+    shape = synth.tiny_shape(n_layers=2, d=128, n_heads=4, n_kv_heads=2, head_dim=32, f=264, vocab=300,
+                             n_actions=6, head_hidden=(32,))
+    enc = R.EncoderHandle(shape, seed=3)
+    head = R.HeadHandle(shape, seed=3)
+    lens = [17, 40, 5]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ids = R.dev(synth.token_ids(3, 500, (int(cu[-1]),), shape.vocab))
+    cu_dev = R.dev(cu)
+    ws = R.Workspace(B.brl_encoder_packed_workspace_bytes(enc.struct, 3, int(cu[-1]), 40))
+    hws = R.Workspace(B.brl_head_workspace_bytes(head.struct, 3))
+    h = torch.empty((3, shape.d), dtype=torch.float32, device="cuda")
+    logits = torch.empty((3, 6), dtype=torch.float32, device="cuda")
+    value = torch.empty((3,), dtype=torch.float32, device="cuda")
+
+    def call():
+        B.encoder_forward_packed(enc.struct, ids, cu_dev, cu, 3, 40, h, ws.buf)
+        B.policy_value_head(head.struct, h, 3, logits, value, hws.buf)
+
+    call()
+    torch.cuda.synchronize()
+    ref = (h.clone(), logits.clone(), value.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    for _ in range(4):
+        h.zero_(); logits.zero_(); value.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(h, ref[0]) and torch.equal(logits, ref[1]) and torch.equal(value, ref[2])
+        call()                               # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(h, ref[0])
