@@ -27,7 +27,6 @@
 // the 8 keys a lane's probabilities stand for are 16 contiguous bytes.
 #include "common.hpp"
 
-#include <cstdlib>
 
 namespace brl {
 
@@ -251,7 +250,10 @@ struct AttnTile {
     }
 };
 
-// WPG wavefronts (4 or 8) = WPG units of one key/value head share every K / V block.
+// WPG wavefronts (a multiple of 4) = WPG units of one key/value head share every K / V block.
+// Four is what is launched: eight halved the K / V traffic but ran 12-19 % slower on both
+// measured shapes (fewer resident workgroups, longer tails).
+constexpr int ATTN_WPG = 4;
 template <int DHP, int VW, int WPG>
 __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a) {
     using T = AttnTile<DHP>;
@@ -369,13 +371,10 @@ size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int he
 namespace {
 
 template <int DHP, int VW>
-void launch_pair(const PackArgs& p, const FragArgs& f, dim3 pgrid, int n_work, int wpg, hipStream_t s) {
+void launch_pair(const PackArgs& p, const FragArgs& f, dim3 pgrid, int n_work, hipStream_t s) {
     hipLaunchKernelGGL((attn_pack_kernel<DHP, VW>), pgrid, dim3(256), 0, s, p);
     const dim3 agrid((unsigned)(8 * ((n_work + 7) / 8)));
-    if (wpg == 8)
-        hipLaunchKernelGGL((attention_frag_kernel<DHP, VW, 8>), agrid, dim3(512), 0, s, f);
-    else
-        hipLaunchKernelGGL((attention_frag_kernel<DHP, VW, 4>), agrid, dim3(256), 0, s, f);
+    hipLaunchKernelGGL((attention_frag_kernel<DHP, VW, ATTN_WPG>), agrid, dim3(ATTN_WPG * 64), 0, s, f);
 }
 
 }  // namespace
@@ -390,10 +389,7 @@ int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& 
     const int dhp = padded_head_dim(head_dim);
     const int nrb = (S + 31) / 32;
     const int group = n_heads / n_kv_heads;
-    // long multi-head sequences: eight query blocks per workgroup halve the K / V traffic
-    static const int forced = getenv("BRL_ATTN_WPG") ? atoi(getenv("BRL_ATTN_WPG")) : 0;
-    const int wpg = forced ? forced : ((group == 1 && nrb >= 8) ? 8 : 4);
-    const int chunks = (group * nrb + wpg - 1) / wpg;
+    const int chunks = (group * nrb + ATTN_WPG - 1) / ATTN_WPG;
     PackArgs p;
     p.qkv = qkv; p.ld = ld; p.B = B; p.S = S; p.NRB = nrb; p.Hq = n_heads; p.Hkv = n_kv_heads; p.dh = head_dim;
     p.sm = sm;
@@ -410,11 +406,11 @@ int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& 
     const bool v4 = (head_dim / 2) % 4 == 0;          // rotary halves and head rows 16-byte aligned
     LaunchTimer tm(BRL_KC_ATTENTION, s);
     if (dhp == 32) {
-        if (v4) launch_pair<32, 4>(p, f, pgrid, f.n_work, wpg, s); else launch_pair<32, 2>(p, f, pgrid, f.n_work, wpg, s);
+        if (v4) launch_pair<32, 4>(p, f, pgrid, f.n_work, s); else launch_pair<32, 2>(p, f, pgrid, f.n_work, s);
     } else if (dhp == 64) {
-        if (v4) launch_pair<64, 4>(p, f, pgrid, f.n_work, wpg, s); else launch_pair<64, 2>(p, f, pgrid, f.n_work, wpg, s);
+        if (v4) launch_pair<64, 4>(p, f, pgrid, f.n_work, s); else launch_pair<64, 2>(p, f, pgrid, f.n_work, s);
     } else {
-        if (v4) launch_pair<128, 4>(p, f, pgrid, f.n_work, wpg, s); else launch_pair<128, 2>(p, f, pgrid, f.n_work, wpg, s);
+        if (v4) launch_pair<128, 4>(p, f, pgrid, f.n_work, s); else launch_pair<128, 2>(p, f, pgrid, f.n_work, s);
     }
     BRL_LAUNCH_CHECK("attention_mfma");
     return BRL_OK;

@@ -359,15 +359,18 @@ struct LdsTile {
                 __builtin_amdgcn_global_load_lds(bsrc[c] + (size_t)sb * 64, st + (AFR + c * NW + wave) * 64, 16, 0, 0);
     }
 
-    // One super-block (128 k) of MFMAs from one stage.  The next activation
-    // fragment is requested from LDS before the MFMAs of the current one issue.
+    // One super-block (128 k) of MFMAs from one stage.  Activation fragments
+    // are requested from LDS two uses before the MFMAs that consume them.
     static __device__ inline void compute(v16i (&acc)[TM][TN], const uint4* st, int wm, int wn, int lane) {
         const uint4* sa = st + (wm * TM * 4) * 64 + lane;
         const uint4* sbp = st + (AFR + wn * TN) * 64 + lane;
         uint4 bq[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) bq[j] = sbp[j * 64];
-        uint4 a_cur = sa[0];
+        constexpr int NF = 4 * TM;
+        uint4 fr[NF];
+        fr[0] = sa[0];
+        if (NF > 1) fr[1] = sa[(TM > 1 ? 4 : 1) * 64];
 #pragma unroll
         for (int dd = 0; dd < 4; ++dd) {
             v4i bf[TN];
@@ -375,13 +378,15 @@ struct LdsTile {
             for (int j = 0; j < TN; ++j) bf[j] = expand_codes(pick(bq[j], dd));
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const int nxt = (i + 1 < TM) ? (i + 1) * 4 + dd : (dd + 1 < 4 ? dd + 1 : dd);
-                const uint4 a_nxt = sa[nxt * 64];
-                const v4i af = as_v4i(a_cur);
+                const int g = dd * TM + i;                       // use index of this fragment
+                if (g + 2 < NF) {
+                    const int g2 = g + 2, dd2 = g2 / TM, i2 = g2 % TM;
+                    fr[g2] = sa[(i2 * 4 + dd2) * 64];
+                }
+                const v4i af = as_v4i(fr[g]);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[j], acc[i][j], 0, 0, 0);
-                a_cur = a_nxt;
             }
         }
     }
