@@ -101,14 +101,16 @@ def ternary_matmul(q: np.ndarray, codes: np.ndarray) -> np.ndarray:
     """acc[t, n] = sum_k q[t, k] * codes[n, k], exact, as int32.
 
     The contraction is done by the fp64 BLAS on integer-valued operands: every
-    partial sum is an integer of magnitude <= 127 * K < 2**53, so each fp64
-    operation is exact and the result equals the integer sum in any order.
+    partial sum is an integer of magnitude <= 127 * 127 * K < 2**53 (codes of
+    magnitude up to 127 are allowed: the int8-weight critic variant shares this
+    routine), so each fp64 operation is exact and the result equals the
+    integer sum in any order.
     """
     q = np.asarray(q)
     codes = np.asarray(codes)
     k = q.shape[-1]
     assert codes.shape[-1] == k
-    assert QB * k < 2 ** 31
+    assert QB * QB * k < 2 ** 31
     acc = q.astype(F64) @ codes.astype(F64).T
     return np.rint(acc).astype(np.int32)
 
