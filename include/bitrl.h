@@ -63,6 +63,10 @@ extern "C" {
                              about 21 mantissa bits), fp32 softmax and accumulation; q, k, v must lie
                              within the fp16 range (|x| < 65504) */
 
+/* format of the weight blobs of an encoder */
+#define BRL_W_TERNARY 0   /* 2-bit blobs from bitlinear_quantize_weights */
+#define BRL_W_INT8    1   /* int8 blobs from bitlinear_quantize_weights_int8 (higher-precision critic backbone) */
+
 const char* brl_last_error(void);
 int         brl_abi_version(void);
 
@@ -116,6 +120,37 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K,
                       float* y, const float* residual,
                       int8_t* xq_dbg, float* absmax_dbg, int32_t* acc_dbg,
                       void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Int8-weight BitLinear for a higher-precision critic backbone (Sec. 5.4,
+ * component ablations: the "INT8 critic + 1-bit policy" rows; the paper names
+ * the configuration, the quantiser below is this library's reading of it).
+ *
+ * Weights, one scale per matrix, the mirror of the per-token activation
+ * quantiser: a = max(max|W|, eps); s = 127 / a (fp32 divide); code =
+ * clamp(rne(w * s), -127, 127); scale = a / 127.  Forward: per-token int8
+ * activations exactly as in bitlinear_forward, acc = sum_k q code (int32,
+ * exact), y = (float(acc) * (a_t / 127)) * scale (+ residual).
+ *
+ * Packed format: rows padded to a multiple of 32, columns to a multiple of
+ * 128, one byte per weight, zero padding; the byte of (n, k) sits at
+ * ((((n/32) * (Kp/128) + k/128) * 4 + (k/32)%4) * 64 + 32 * ((k/16)%2) + n%32) * 16 + k%16
+ * (the int8 MFMA operand order, the same layout the quantised activations
+ * use).  The blob carries no header.
+ * Arguments, taps and errors as for the ternary entry points; every M runs
+ * the int8 MFMA kernel (there is no separate 1..4 token path).
+ * An encoder with weight_format = BRL_W_INT8 uses such blobs in every layer.
+ * ------------------------------------------------------------------------ */
+size_t brl_packed_int8_bytes(int n_out, int k_in);
+int bitlinear_quantize_weights_int8(const float* W, int n_out, int k_in, float eps,
+                                    void* packed_out, float* scale_out, int8_t* codes_dbg,
+                                    void* workspace /* brl_quantize_workspace_bytes */, size_t ws_bytes, void* stream);
+int brl_unpack_codes_int8(const void* packed, int n_out, int k_in, int8_t* codes_out, void* stream);
+int bitlinear_int8_forward(const void* packed, const float* scale, int N, int K,
+                           const void* x, int x_dtype, int M, float eps_act,
+                           float* y, const float* residual,
+                           int8_t* xq_dbg, float* absmax_dbg, int32_t* acc_dbg,
+                           void* workspace /* brl_bitlinear_workspace_bytes */, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * Many independent few-token BitLinear problems of one shape in one launch:
@@ -195,6 +230,8 @@ typedef struct brl_encoder {
     int   n_layers, d, n_heads, n_kv_heads, head_dim, f, vocab;
     float rope_theta, eps_norm, eps_act;
     int   attn_precision;               /* BRL_ATTN_* */
+    int   weight_format;                /* BRL_W_*: what every *_packed pointer of the layers holds; with
+                                           BRL_W_INT8 each *_beta is the scale from bitlinear_quantize_weights_int8 */
     const uint16_t* embedding;          /* [vocab, d] bf16 bit patterns */
     const float*    final_norm_g;       /* [d] */
     const brl_layer_weights* layers;    /* HOST array of n_layers entries */
@@ -248,6 +285,21 @@ size_t brl_head_workspace_bytes(const brl_head* head /* HOST */, int B);
 int policy_value_head(const brl_head* head /* HOST */, const float* h, int B,
                       float* logits, float* value,
                       void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Ensemble critic (Sec. 5.4, component ablations: "3x / 5x 1-bit critics
+ * (avg)"): n_members value heads of identical shape read the same h; every
+ * layer of all members runs in one launch.  values_each[e][b] is member e's
+ * head output exactly as policy_value_head computes a value; value_mean[b] =
+ * (sum over members in member order, in fp64) / n_members, rounded to fp32.
+ * members: HOST array of n_members (1..8) heads with equal n_layers, dims and
+ * act, output width 1.  h [B, dims[0]]; value_mean [B]; values_each
+ * [n_members, B] or NULL.
+ * ------------------------------------------------------------------------ */
+size_t brl_value_ensemble_workspace_bytes(const brl_mlp* members /* HOST */, int n_members, int B);
+int value_ensemble_forward(const brl_mlp* members /* HOST */, int n_members, const float* h, int B,
+                           float* value_mean, float* values_each,
+                           void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * Training of the two heads on a cached rollout (Sec. 3.1 Eq. 1; Sec. 3.2;

@@ -20,6 +20,7 @@ BRL_OK, BRL_EINVAL, BRL_ENOSPC, BRL_EHIP = 0, 1, 2, 3
 BRL_F32, BRL_BF16 = 0, 1
 BRL_ACT_TANH, BRL_ACT_RELU = 0, 1
 BRL_ATTN_F32, BRL_ATTN_MFMA = 0, 1
+BRL_W_TERNARY, BRL_W_INT8 = 0, 1
 
 c_void_p, c_int, c_float, c_size_t = C.c_void_p, C.c_int, C.c_float, C.c_size_t
 
@@ -44,7 +45,7 @@ class brl_encoder(C.Structure):
     _fields_ = [("n_layers", c_int), ("d", c_int), ("n_heads", c_int), ("n_kv_heads", c_int),
                 ("head_dim", c_int), ("f", c_int), ("vocab", c_int),
                 ("rope_theta", c_float), ("eps_norm", c_float), ("eps_act", c_float),
-                ("attn_precision", c_int),
+                ("attn_precision", c_int), ("weight_format", c_int),
                 ("embedding", c_void_p), ("final_norm_g", c_void_p),
                 ("layers", C.POINTER(brl_layer_weights))]
 
@@ -87,6 +88,15 @@ _SIGNATURES = {
     "brl_bitlinear_workspace_bytes": (c_size_t, [c_int, c_int, c_int]),
     "bitlinear_forward": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "brl_packed_int8_bytes": (c_size_t, [c_int, c_int]),
+    "bitlinear_quantize_weights_int8": (c_int, [c_void_p, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p,
+                                                c_void_p, c_size_t, c_void_p]),
+    "brl_unpack_codes_int8": (c_int, [c_void_p, c_int, c_int, c_void_p, c_void_p]),
+    "bitlinear_int8_forward": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
+                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "brl_value_ensemble_workspace_bytes": (c_size_t, [C.POINTER(brl_mlp), c_int, c_int]),
+    "value_ensemble_forward": (c_int, [C.POINTER(brl_mlp), c_int, c_void_p, c_int, c_void_p, c_void_p,
+                                       c_void_p, c_size_t, c_void_p]),
     "bitlinear_forward_batch": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
                                         c_void_p, c_int, c_void_p]),
     "brl_ffn_workspace_bytes": (c_size_t, [c_int, c_int, c_int]),
@@ -196,6 +206,30 @@ def bitlinear_forward(packed: torch.Tensor, beta: torch.Tensor, N: int, K: int, 
                                    workspace.numel() * workspace.element_size(), _stream()))
 
 
+def brl_packed_int8_bytes(n_out: int, k_in: int) -> int:
+    return lib().brl_packed_int8_bytes(n_out, k_in)
+
+
+def bitlinear_quantize_weights_int8(W: torch.Tensor, eps: float, packed_out: torch.Tensor, scale_out: torch.Tensor,
+                                    codes_dbg: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    n, k = W.shape
+    _check(lib().bitlinear_quantize_weights_int8(_ptr(W), n, k, eps, _ptr(packed_out), _ptr(scale_out), _ptr(codes_dbg),
+                                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_unpack_codes_int8(packed: torch.Tensor, n_out: int, k_in: int, codes_out: torch.Tensor) -> None:
+    _check(lib().brl_unpack_codes_int8(_ptr(packed), n_out, k_in, _ptr(codes_out), _stream()))
+
+
+def bitlinear_int8_forward(packed: torch.Tensor, scale: torch.Tensor, N: int, K: int, x: torch.Tensor, M: int,
+                           eps_act: float, y: torch.Tensor, residual: Optional[torch.Tensor],
+                           xq_dbg: Optional[torch.Tensor], absmax_dbg: Optional[torch.Tensor],
+                           acc_dbg: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    _check(lib().bitlinear_int8_forward(_ptr(packed), _ptr(scale), N, K, _ptr(x), _dtype_code(x), M, eps_act, _ptr(y),
+                                        _ptr(residual), _ptr(xq_dbg), _ptr(absmax_dbg), _ptr(acc_dbg), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()))
+
+
 def bitlinear_forward_batch(packed_ptrs: torch.Tensor, beta_ptrs: torch.Tensor, N: int, K: int, x_ptrs: torch.Tensor,
                             x_dtype: int, M: int, eps_act: float, y_ptrs: torch.Tensor, count: int) -> None:
     """The four *_ptrs are int64 device tensors holding device addresses (tensor.data_ptr() values)."""
@@ -243,6 +277,17 @@ def policy_value_head(head: brl_head, h: torch.Tensor, B: int, logits: torch.Ten
                       workspace: torch.Tensor) -> None:
     _check(lib().policy_value_head(C.byref(head), _ptr(h), B, _ptr(logits), _ptr(value), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+def brl_value_ensemble_workspace_bytes(members, n_members: int, B: int) -> int:
+    return lib().brl_value_ensemble_workspace_bytes(members, n_members, B)
+
+
+def value_ensemble_forward(members, n_members: int, h: torch.Tensor, B: int, value_mean: torch.Tensor,
+                           values_each: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    """members: a ctypes array of brl_mlp (see make_mlp_array)."""
+    _check(lib().value_ensemble_forward(members, n_members, _ptr(h), B, _ptr(value_mean), _ptr(values_each),
+                                        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def make_ppo_config(policy_dims: Sequence[int], value_dims: Sequence[int], act: int, clip_eps: float = 0.1,
@@ -326,3 +371,9 @@ def make_mlp(weights: Sequence[torch.Tensor], biases: Sequence[torch.Tensor], ac
     bp = (c_void_p * n)(*[_ptr(b) for b in biases])
     m = brl_mlp(n, C.cast(dims, C.POINTER(c_int)), C.cast(wp, C.POINTER(c_void_p)), C.cast(bp, C.POINTER(c_void_p)), act)
     return m, (dims, wp, bp, list(weights), list(biases))
+
+
+def make_mlp_array(mlps: Sequence[brl_mlp]):
+    """A contiguous ctypes array of brl_mlp structs (the member table of an ensemble)."""
+    arr = (brl_mlp * len(mlps))(*mlps)
+    return arr

@@ -101,10 +101,11 @@ int check_linear_shape(int N, int K, const char* who) {
     return BRL_OK;
 }
 
-WeightSegs one_seg(const void* packed, const float* beta, int N) {
+WeightSegs one_seg(const void* packed, const float* beta, int N, int w8 = 0) {
     WeightSegs w;
     memset(&w, 0, sizeof(w));
     w.count = 1;
+    w.w8 = w8;
     w.packed[0] = static_cast<const uint32_t*>(packed);
     w.beta[0] = beta;
     w.nb_end[0] = round_up(N, NB) / NB;
@@ -161,7 +162,7 @@ int check_ffn(const brl_ffn_weights* w, int d, int f, const char* who) {
 }
 
 // shared by ffn_block_forward and encoder_forward: x [M, d] fp32 -> y = x + down(...)
-int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_dtype, int M, int d, int f,
+int run_ffn(const brl_ffn_weights* w, int w8, const float* x32, const void* xin, int x_dtype, int M, int d, int f,
             float eps_norm, float eps_act, float* y, const ActBuf& act1, float* gu, const ActBuf& act2, hipStream_t s) {
     QuantArgs qa;
     memset(&qa, 0, sizeof(qa));
@@ -170,6 +171,7 @@ int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_d
     if (int rc = launch_act_quant(qa, act1, s)) return rc;
     WeightSegs gu_w;
     memset(&gu_w, 0, sizeof(gu_w));
+    gu_w.w8 = w8;
     add_seg(gu_w, w->gate_packed, w->gate_beta, f);
     add_seg(gu_w, w->up_packed, w->up_beta, f);
     // gate | up GEMM with the squared-ReLU GLU in its epilogue: gu receives h [M, f]
@@ -179,7 +181,7 @@ int run_ffn(const brl_ffn_weights* w, const float* x32, const void* xin, int x_d
     qb.x = gu; qb.x_dtype = BRL_F32; qb.gain = w->subln_g;
     qb.eps_norm = eps_norm; qb.eps_act = eps_act; qb.M = M; qb.K = f;
     if (int rc = launch_act_quant(qb, act2, s)) return rc;
-    const WeightSegs dn = one_seg(w->down_packed, w->down_beta, d);
+    const WeightSegs dn = one_seg(w->down_packed, w->down_beta, d, w8);
     return launch_gemm(act2, dn, M, d, f, y, d, x32, nullptr, 0, s);
 }
 
@@ -229,6 +231,8 @@ int check_encoder(const brl_encoder* e) {
                 "encoder: d and f must be multiples of 8");
     BRL_REQUIRE(e->attn_precision == BRL_ATTN_F32 || e->attn_precision == BRL_ATTN_MFMA,
                 "encoder: unknown attn_precision %d", e->attn_precision);
+    BRL_REQUIRE(e->weight_format == BRL_W_TERNARY || e->weight_format == BRL_W_INT8, "encoder: unknown weight_format %d",
+                e->weight_format);
     const int dq = e->n_heads * e->head_dim;
     if (int rc = check_linear_shape(dq, e->d, "encoder")) return rc;
     if (int rc = check_linear_shape(e->d, dq, "encoder")) return rc;
@@ -292,7 +296,7 @@ extern "C" {
 
 const char* brl_last_error(void) { return g_err; }
 
-int brl_abi_version(void) { return 1; }
+int brl_abi_version(void) { return 2; }
 
 int brl_timing_enable(int on) {
     std::lock_guard<std::mutex> lk(g_tm_mu);
@@ -415,6 +419,70 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K, const
     return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, 0, s);
 }
 
+size_t brl_packed_int8_bytes(int n_out, int k_in) {
+    if (n_out < 1 || k_in < 1) return 0;
+    return (size_t)round_up(n_out, NB) * (size_t)round_up(k_in, SBK);
+}
+
+int bitlinear_quantize_weights_int8(const float* W, int n_out, int k_in, float eps, void* packed_out, float* scale_out,
+                                    int8_t* codes_dbg, void* workspace, size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(W && packed_out && scale_out && workspace, "quantize_weights_int8: null pointer");
+    BRL_REQUIRE(aligned16(W) && aligned16(packed_out) && aligned16(workspace), "quantize_weights_int8: misaligned pointer");
+    BRL_REQUIRE(n_out >= 1 && k_in >= 1, "quantize_weights_int8: bad shape %d x %d", n_out, k_in);
+    BRL_REQUIRE(eps > 0.f, "quantize_weights_int8: eps must be positive");
+    if (ws_bytes < brl_quantize_workspace_bytes(n_out, k_in)) {
+        set_error("quantize_weights_int8: workspace %zu < %zu", ws_bytes, brl_quantize_workspace_bytes(n_out, k_in));
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver c(workspace);
+    float* partials = c.take<float>(1024);
+    int* flag = c.take<int>(1);
+    if (int rc = launch_quantize_weights_int8(W, n_out, k_in, eps, static_cast<int8_t*>(packed_out), scale_out, codes_dbg,
+                                              partials, flag, s))
+        return rc;
+    int bad = 0;
+    BRL_HIP_CHECK(hipMemcpyAsync(&bad, flag, sizeof(int), hipMemcpyDeviceToHost, s));
+    BRL_HIP_CHECK(hipStreamSynchronize(s));
+    BRL_REQUIRE(bad == 0, "quantize_weights_int8: max|W| is not finite");
+    return BRL_OK;
+}
+
+int brl_unpack_codes_int8(const void* packed, int n_out, int k_in, int8_t* codes_out, void* stream) {
+    BRL_REQUIRE(packed && codes_out && aligned16(packed), "unpack_codes_int8: null or misaligned pointer");
+    BRL_REQUIRE(n_out >= 1 && k_in >= 1, "unpack_codes_int8: bad shape");
+    return launch_unpack_codes_int8(static_cast<const int8_t*>(packed), n_out, k_in, codes_out,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int bitlinear_int8_forward(const void* packed, const float* scale, int N, int K, const void* x, int x_dtype, int M,
+                           float eps_act, float* y, const float* residual, int8_t* xq_dbg, float* absmax_dbg,
+                           int32_t* acc_dbg, void* workspace, size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(packed && scale && x && y && workspace, "bitlinear_int8_forward: null pointer");
+    BRL_REQUIRE(aligned16(packed) && aligned16(x) && aligned16(y) && aligned16(workspace) &&
+                    (!residual || aligned16(residual)),
+                "bitlinear_int8_forward: pointers must be 16-byte aligned");
+    BRL_REQUIRE(M >= 1, "bitlinear_int8_forward: M = %d", M);
+    BRL_REQUIRE(x_dtype == BRL_F32 || x_dtype == BRL_BF16, "bitlinear_int8_forward: unknown x_dtype %d", x_dtype);
+    BRL_REQUIRE(eps_act > 0.f, "bitlinear_int8_forward: eps_act must be positive");
+    if (int rc = check_linear_shape(N, K, "bitlinear_int8_forward")) return rc;
+    const BitlinearWs L = bitlinear_ws_layout(M, N, K);
+    if (ws_bytes < L.total) {
+        set_error("bitlinear_int8_forward: workspace %zu < %zu", ws_bytes, L.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Carver c(static_cast<char*>(workspace) + L.act_off);
+    const ActBuf act = take_actbuf(c, M, K);
+    QuantArgs qa;
+    memset(&qa, 0, sizeof(qa));
+    qa.x = x; qa.x_dtype = x_dtype; qa.gain = nullptr; qa.eps_norm = 0.f; qa.eps_act = eps_act;
+    qa.M = M; qa.K = K; qa.xq_rowmajor = xq_dbg; qa.absmax_tap = absmax_dbg;
+    if (int rc = launch_act_quant(qa, act, s)) return rc;
+    const WeightSegs w = one_seg(packed, scale, N, 1);
+    return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, 0, s);
+}
+
 int bitlinear_forward_batch(const void* const* packed, const float* const* beta, int N, int K, const void* const* x,
                             int x_dtype, int M, float eps_act, float* const* y, int count, void* stream) {
     BRL_REQUIRE(packed && beta && x && y, "bitlinear_forward_batch: null pointer array");
@@ -458,7 +526,7 @@ int ffn_block_forward(const brl_ffn_weights* w, const void* x, int x_dtype, int 
     Carver c2(base + L.act2_off);
     const ActBuf act2 = take_actbuf(c2, M, f);
     float* gu = reinterpret_cast<float*>(base + L.gu_off);
-    return run_ffn(w, x32, x, x_dtype, M, d, f, eps_norm, eps_act, y, act1, gu, act2, s);
+    return run_ffn(w, 0, x32, x, x_dtype, M, d, f, eps_norm, eps_act, y, act1, gu, act2, s);
 }
 
 size_t brl_encoder_workspace_bytes(const brl_encoder* enc, int B, int S) {
@@ -474,6 +542,7 @@ int run_encoder_microbatch(const brl_encoder* enc, const EncWs& L, char* base, c
                            int rows_cap, const SeqMap& sm, const int32_t* lengths, float* h_out, hipStream_t s) {
     const int d = enc->d, f = enc->f, dh = enc->head_dim;
     const int dq = enc->n_heads * dh, dkv = enc->n_kv_heads * dh;
+    const int w8 = enc->weight_format == BRL_W_INT8 ? 1 : 0;
     float* x = reinterpret_cast<float*>(base + L.x_off);
     float* big = reinterpret_cast<float*>(base + L.big_off);
     float* cos_t = reinterpret_cast<float*>(base + L.cos_off);
@@ -495,6 +564,7 @@ int run_encoder_microbatch(const brl_encoder* enc, const EncWs& L, char* base, c
         if (int rc = launch_act_quant(qa, act, s)) return rc;
         WeightSegs wqkv;
         memset(&wqkv, 0, sizeof(wqkv));
+        wqkv.w8 = w8;
         add_seg(wqkv, w.wq_packed, w.wq_beta, dq);
         add_seg(wqkv, w.wk_packed, w.wk_beta, dkv);
         add_seg(wqkv, w.wv_packed, w.wv_beta, dkv);
@@ -513,9 +583,10 @@ int run_encoder_microbatch(const brl_encoder* enc, const EncWs& L, char* base, c
         qo.x = att; qo.x_dtype = BRL_F32; qo.gain = w.attn_subln_g; qo.eps_norm = enc->eps_norm; qo.eps_act = enc->eps_act;
         qo.M = Mt; qo.K = dq;
         if (int rc = launch_act_quant(qo, act, s)) return rc;
-        const WeightSegs wo = one_seg(w.wo_packed, w.wo_beta, d);
+        const WeightSegs wo = one_seg(w.wo_packed, w.wo_beta, d, w8);
         if (int rc = launch_gemm(act, wo, Mt, d, dq, x, d, x, nullptr, 0, s)) return rc;
-        if (int rc = run_ffn(&w.ffn, x, x, BRL_F32, Mt, d, f, enc->eps_norm, enc->eps_act, x, act, big, act, s)) return rc;
+        if (int rc = run_ffn(&w.ffn, w8, x, x, BRL_F32, Mt, d, f, enc->eps_norm, enc->eps_act, x, act, big, act, s))
+            return rc;
     }
     return launch_final_pool(x, enc->final_norm_g, nb, S, Mt, d, lengths, sm, enc->eps_norm, rinv, h_out, s);
 }
@@ -662,6 +733,77 @@ int policy_value_head(const brl_head* head, const float* h, int B, float* logits
     double* buf1 = reinterpret_cast<double*>(static_cast<char*>(workspace) + need / 2);
     if (int rc = run_mlp(&head->policy, h, B, logits, buf0, buf1, s)) return rc;
     return run_mlp(&head->value, h, B, value, buf0, buf1, s);
+}
+
+namespace {
+
+int check_ensemble(const brl_mlp* members, int n_members, const char* who) {
+    BRL_REQUIRE(members != nullptr, "%s: null member table", who);
+    BRL_REQUIRE(n_members >= 1 && n_members <= MAX_ENSEMBLE, "%s: %d members, 1..%d supported", who, n_members, MAX_ENSEMBLE);
+    for (int e = 0; e < n_members; ++e) {
+        if (int rc = check_mlp(&members[e], "value ensemble member", 1)) return rc;
+        BRL_REQUIRE(members[e].n_layers == members[0].n_layers && members[e].act == members[0].act,
+                    "%s: member %d differs from member 0 in depth or activation", who, e);
+        for (int i = 0; i <= members[0].n_layers; ++i)
+            BRL_REQUIRE(members[e].dims[i] == members[0].dims[i], "%s: member %d differs from member 0 in dims[%d]", who, e, i);
+    }
+    return BRL_OK;
+}
+
+struct EnsembleWs {
+    size_t buf0_off, buf1_off, each_off, total;
+};
+
+EnsembleWs ensemble_ws_layout(const brl_mlp* members, int n_members, int B) {
+    EnsembleWs L;
+    const size_t hid = round_up_sz((size_t)n_members * B * mlp_hidden_max(&members[0]) * sizeof(double), ALIGN);
+    L.buf0_off = 0;
+    L.buf1_off = hid;
+    L.each_off = 2 * hid;
+    L.total = L.each_off + round_up_sz((size_t)n_members * B * sizeof(float), ALIGN);
+    return L;
+}
+
+}  // namespace
+
+size_t brl_value_ensemble_workspace_bytes(const brl_mlp* members, int n_members, int B) {
+    if (!members || n_members < 1 || n_members > MAX_ENSEMBLE || B < 1) return 0;
+    if (!members[0].dims || members[0].n_layers < 1 || members[0].n_layers > 8) return 0;
+    return ensemble_ws_layout(members, n_members, B).total;
+}
+
+int value_ensemble_forward(const brl_mlp* members, int n_members, const float* h, int B, float* value_mean,
+                           float* values_each, void* workspace, size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(h && value_mean && workspace && aligned16(workspace), "value_ensemble_forward: null or misaligned pointer");
+    BRL_REQUIRE(B >= 1, "value_ensemble_forward: B = %d", B);
+    if (int rc = check_ensemble(members, n_members, "value_ensemble_forward")) return rc;
+    const EnsembleWs L = ensemble_ws_layout(members, n_members, B);
+    if (ws_bytes < L.total) {
+        set_error("value_ensemble_forward: workspace %zu < %zu", ws_bytes, L.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    double* bufs[2] = {reinterpret_cast<double*>(base + L.buf0_off), reinterpret_cast<double*>(base + L.buf1_off)};
+    float* each = values_each ? values_each : reinterpret_cast<float*>(base + L.each_off);
+    const brl_mlp& m0 = members[0];
+    const double* in64 = nullptr;
+    for (int i = 0; i < m0.n_layers; ++i) {
+        EnsembleLayer a;
+        memset(&a, 0, sizeof(a));
+        for (int e = 0; e < n_members; ++e) {
+            a.W[e] = members[e].W[i];
+            a.bias[e] = members[e].b[i];
+        }
+        a.n_members = n_members; a.B = B; a.in_dim = m0.dims[i]; a.out_dim = m0.dims[i + 1]; a.act = m0.act;
+        a.last = (i + 1 == m0.n_layers) ? 1 : 0;
+        a.in64 = in64; a.in32 = h;
+        a.out64 = a.last ? nullptr : bufs[i & 1];
+        a.out32 = a.last ? each : nullptr;
+        if (int rc = launch_ensemble_layer(a, s)) return rc;
+        in64 = a.out64;
+    }
+    return launch_ensemble_mean(each, n_members, B, value_mean, s);
 }
 
 }  // extern "C"

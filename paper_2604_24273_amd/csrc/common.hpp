@@ -84,6 +84,7 @@ struct WeightSegs {
     int nb_end[3];    // exclusive end, in 32-row blocks, of each segment
     int n_end[3];     // exclusive end, in rows
     int count;
+    int w8;           // 0: 2-bit ternary blobs; 1: int8 blobs in the activations' fragment layout
 };
 
 // ---- kernel launchers (host) ----
@@ -92,6 +93,10 @@ int launch_quantize_weights(const float* W, int N, int K, float eps, uint32_t* p
                             int8_t* codes_dbg, double* partials, int* flag, hipStream_t s);
 int launch_unpack_codes(const uint32_t* packed, int N, int K, int8_t* codes, hipStream_t s);
 int quantize_partials_count(int N, int K);
+// per-tensor absmax int8 weights, written in the tiled layout of tiled_act_offset (row n in place of token m)
+int launch_quantize_weights_int8(const float* W, int N, int K, float eps, int8_t* packed, float* scale,
+                                 int8_t* codes_dbg, float* partials, int* flag, hipStream_t s);
+int launch_unpack_codes_int8(const int8_t* packed, int N, int K, int8_t* codes, hipStream_t s);
 
 // activation quantisation (plain, or RMSNorm first)
 struct QuantArgs {
@@ -144,6 +149,19 @@ int launch_final_pool(const float* x, const float* gain, int B, int S, int M, in
                       const SeqMap& sm, float eps_norm, float* rinv, float* h, hipStream_t s);
 int launch_mlp_layer(const double* in64, const float* in32, const float* W, const float* b, int B, int in_dim,
                      int out_dim, int act, double* out64, float* out32, hipStream_t s);
+// one layer of up to 8 equally shaped heads (an ensemble of critics) in one launch
+constexpr int MAX_ENSEMBLE = 8;
+struct EnsembleLayer {
+    const float* W[MAX_ENSEMBLE];
+    const float* bias[MAX_ENSEMBLE];
+    int n_members, B, in_dim, out_dim, act, last;
+    const double* in64;     // [n_members, B, in_dim] or nullptr: then every member reads in32
+    const float* in32;      // [B, in_dim]
+    double* out64;          // [n_members, B, out_dim] (hidden layers)
+    float* out32;           // [n_members, B] (last layer, out_dim == 1)
+};
+int launch_ensemble_layer(const EnsembleLayer& a, hipStream_t s);
+int launch_ensemble_mean(const float* each, int n, int B, float* mean, hipStream_t s);
 int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s);   // n % 8 == 0
 
 }  // namespace brl

@@ -12,6 +12,8 @@
 //     epilogue subtracts sum_k q (from the quantisation kernel) to get acc.
 // Integer sums are order independent, so the k-order inside a fragment only
 // has to agree between the two operands - it does, by construction of the layouts.
+// Int8 weights (the higher-precision critic variant) come in the activations' own
+// fragment layout and feed the MFMA as they are: no expansion, no offset correction.
 //
 // Two kernels:
 //   gemm_lds_kernel    many tokens: both operand tiles of a workgroup (128 tokens
@@ -35,6 +37,7 @@ struct GemmArgs {
     const float* dscale;
     const int32_t* sumq;
     const uint4* wp[3];      // packed weights per segment
+    int wfrag;               // uint4 per (32-row block, 128-k super-block) of a weight blob: 64 (2-bit) or 256 (int8)
     const float* beta[3];
     int nb_end[3];
     int n_end[3];
@@ -122,7 +125,7 @@ struct BCols {
             seg[j] = s;
             col0[j] = c0;
             ncols[j] = (nb0 + j < g.nnb) ? nc : 0;
-            ptr[j] = g.wp[s] + (size_t)lnb * g.nsb * 64 + lane;
+            ptr[j] = g.wp[s] + (size_t)lnb * g.nsb * g.wfrag + lane;
         }
     }
 };
@@ -165,7 +168,7 @@ __device__ inline const int2* park_rows(const GemmArgs& g, int mb0, int lane, in
 #pragma unroll
     for (int r = lane; r < TM * 32; r += 64) {
         const int m = min(mb0 * 32 + r, g.M - 1);
-        rows[r] = make_int2(__float_as_int(g.dscale[m]), g.sumq[m]);
+        rows[r] = make_int2(__float_as_int(g.dscale[m]), g.sumq ? g.sumq[m] : 0);   // no offset codes: nothing to subtract
     }
     return rows;
 }
@@ -304,7 +307,7 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
                     int seg, col0, ncols;
                     block_columns(g, nb0 + 2 * jj, seg, col0, ncols);
                     if (m < g.M && cc < ncols) {
-                        const int sq = g.sumq[m];
+                        const int sq = g.sumq ? g.sumq[m] : 0;
                         const float d = g.dscale[m];
                         const float G = ((float)(scr[row * LD + (2 * jj) * 32 + cc] - sq) * d) * (*g.beta[0]);
                         const float U = ((float)(scr[row * LD + (2 * jj + 1) * 32 + cc] - sq) * d) * (*g.beta[1]);
@@ -320,7 +323,7 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
                     int seg, col0, ncols;
                     block_columns(g, nb0 + (c >> 5), seg, col0, ncols);
                     if (m < g.M && (c & 31) < ncols) {
-                        const int a = scr[row * LD + c] - g.sumq[m];
+                        const int a = scr[row * LD + c] - (g.sumq ? g.sumq[m] : 0);
                         const size_t o = (size_t)m * g.ldy + col0 + (c & 31);
                         float val = ((float)a * g.dscale[m]) * (*g.beta[seg]);
                         if (g.residual) val = val + g.residual[o];
@@ -337,11 +340,12 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
 // Many-token kernel: WM x WN wavefronts, each TM x TN tiles; both operands staged
 // through LDS with direct global->LDS loads, double buffered.
 // ---------------------------------------------------------------------------
-template <int TM, int TN, int WM, int WN>
+template <int TM, int TN, int WM, int WN, bool W8>
 struct LdsTile {
     static constexpr int NW = WM * WN;
     static constexpr int AFR = WM * TM * 4;           // 1 KB activation fragments per stage
-    static constexpr int BFR = WN * TN;               // 1 KB packed weight blocks per stage
+    static constexpr int BFR = WN * TN * (W8 ? 4 : 1);   // 1 KB pieces of weights per stage: a packed 2-bit block, or
+                                                      // the four k-step fragments of an int8 block
     static constexpr int STAGE = (AFR + BFR) * 64;    // uint4 elements per stage
     static constexpr int APW = (AFR + NW - 1) / NW, BPW = (BFR + NW - 1) / NW;   // pieces copied per wavefront
 
@@ -356,17 +360,20 @@ struct LdsTile {
 #pragma unroll
         for (int c = 0; c < BPW; ++c)
             if (BFR % NW == 0 || c * NW + wave < BFR)
-                __builtin_amdgcn_global_load_lds(bsrc[c] + (size_t)sb * 64, st + (AFR + c * NW + wave) * 64, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(bsrc[c] + (size_t)sb * (W8 ? 256 : 64), st + (AFR + c * NW + wave) * 64,
+                                                 16, 0, 0);
     }
 
     // One super-block (128 k) of MFMAs from one stage.  Activation fragments
     // are requested from LDS two uses before the MFMAs that consume them.
     static __device__ inline void compute(v16i (&acc)[TM][TN], const uint4* st, int wm, int wn, int lane) {
         const uint4* sa = st + (wm * TM * 4) * 64 + lane;
-        const uint4* sbp = st + (AFR + wn * TN) * 64 + lane;
-        uint4 bq[TN];
+        const uint4* sbp = st + (AFR + wn * TN * (W8 ? 4 : 1)) * 64 + lane;
+        uint4 bq[W8 ? 1 : TN];
+        if constexpr (!W8) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bq[j] = sbp[j * 64];
+            for (int j = 0; j < TN; ++j) bq[j] = sbp[j * 64];
+        }
         constexpr int NF = 4 * TM;
         uint4 fr[NF];
         fr[0] = sa[0];
@@ -375,7 +382,10 @@ struct LdsTile {
         for (int dd = 0; dd < 4; ++dd) {
             v4i bf[TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = expand_codes(pick(bq[j], dd));
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (W8) bf[j] = as_v4i(sbp[(j * 4 + dd) * 64]);
+                else bf[j] = expand_codes(pick(bq[j], dd));
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int g = dd * TM + i;                       // use index of this fragment
@@ -392,9 +402,9 @@ struct LdsTile {
     }
 };
 
-template <int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_kernel(GemmArgs g) {
-    using Tile = LdsTile<TM, TN, WM, WN>;
+template <int TM, int TN, int WM, int WN, bool W8>
+__device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
+    using Tile = LdsTile<TM, TN, WM, WN, W8>;
     constexpr int NW = Tile::NW;
     __shared__ __attribute__((aligned(1024))) uint4 stage0[Tile::STAGE];
     __shared__ __attribute__((aligned(1024))) uint4 stage1[Tile::STAGE];
@@ -421,9 +431,10 @@ __global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_kernel(GemmArgs g) {
     const uint4* bsrc[Tile::BPW];
 #pragma unroll
     for (int c = 0; c < Tile::BPW; ++c) {
+        const int piece = c * NW + wave;
         BCols<1> one;
-        one.init(g, nb_tile0 + c * NW + wave, lane);
-        bsrc[c] = one.ptr[0];
+        one.init(g, nb_tile0 + (W8 ? piece >> 2 : piece), lane);
+        bsrc[c] = one.ptr[0] + (W8 ? (piece & 3) * 64 : 0);
     }
 
     float beta[TN];
@@ -468,6 +479,17 @@ __global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_kernel(GemmArgs g) {
     static_assert((NW / 2) * Epi<TM, TN>::REGION * 4 <= Tile::STAGE * 16, "half of the epilogue regions per stage");
     int* scr = reinterpret_cast<int*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * Epi<TM, TN>::REGION;
     epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
+}
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_kernel(GemmArgs g) {
+    gemm_lds_body<TM, TN, WM, WN, false>(g);
+}
+
+// the same tile loop on int8 weight blobs
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_w8_kernel(GemmArgs g) {
+    gemm_lds_body<TM, TN, WM, WN, true>(g);
 }
 
 // ---------------------------------------------------------------------------
@@ -588,7 +610,7 @@ int launch_direct(GemmArgs& g, hipStream_t s) {
     return BRL_OK;
 }
 
-template <int TM, int TN, int WM, int WN>
+template <int TM, int TN, int WM, int WN, bool W8>
 int launch_lds(GemmArgs& g, hipStream_t s) {
     g.tiles_m = (g.nmb + WM * TM - 1) / (WM * TM);
     g.tiles_n = (g.nnb + WN * TN - 1) / (WN * TN);
@@ -596,7 +618,10 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 7) / 8) * 8;
     LaunchTimer tm(WN == 4 ? BRL_KC_GEMM : BRL_KC_GEMM_NARROW, s, g.ops);
-    hipLaunchKernelGGL((gemm_lds_kernel<TM, TN, WM, WN>), dim3(grid), dim3(WM * WN * 64), 0, s, g);
+    if constexpr (W8)
+        hipLaunchKernelGGL((gemm_lds_w8_kernel<TM, TN, WM, WN>), dim3(grid), dim3(WM * WN * 64), 0, s, g);
+    else
+        hipLaunchKernelGGL((gemm_lds_kernel<TM, TN, WM, WN>), dim3(grid), dim3(WM * WN * 64), 0, s, g);
     BRL_LAUNCH_CHECK("gemm_lds_kernel");
     return BRL_OK;
 }
@@ -608,7 +633,8 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     GemmArgs g;
     g.A = reinterpret_cast<const uint4*>(a.q);
     g.dscale = a.dscale;
-    g.sumq = a.sumq;
+    g.sumq = w.w8 ? nullptr : a.sumq;
+    g.wfrag = w.w8 ? 256 : 64;
     g.nseg = w.count;
     for (int i = 0; i < 3; ++i) {
         g.wp[i] = reinterpret_cast<const uint4*>(w.packed[i < w.count ? i : 0]);
@@ -637,6 +663,8 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     for (int i = 0; i < w.count; ++i)
         if ((w.n_end[i] - (i ? w.n_end[i - 1] : 0)) % 32 != 0) g.fast_epilogue = 0;
     (void)N;
+    // int8 weights: the LDS-staged 128 x 128 tile at every size (32 KB per stage)
+    if (w.w8) return launch_lds<2, 2, 2, 2, true>(g, s);
     // Tile choice: k-split wavefronts for skinny (few-token) problems, where weight
     // streaming bounds the time; LDS-staged big tiles once the grid fills the chip.
     // (up to 16 wavefronts split k for one or two token blocks: the chain of dependent loads per
@@ -665,8 +693,8 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     const long t_narrow = (long)((g.nmb + 3) / 4) * ((g.nnb + 3) / 4);
     const double fill_wide = (double)t_wide / (double)(((t_wide + cus - 1) / cus) * cus);
     const double fill_narrow = (double)t_narrow / (double)(((t_narrow + cus - 1) / cus) * cus);
-    if (t_wide >= 2 * cus && fill_wide >= 0.95 * fill_narrow) return launch_lds<2, 2, 2, 4>(g, s);
-    return launch_lds<2, 2, 2, 2>(g, s);
+    if (t_wide >= 2 * cus && fill_wide >= 0.95 * fill_narrow) return launch_lds<2, 2, 2, 4, false>(g, s);
+    return launch_lds<2, 2, 2, 2, false>(g, s);
 }
 
 }  // namespace brl

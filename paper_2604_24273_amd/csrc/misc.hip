@@ -104,7 +104,60 @@ __global__ __launch_bounds__(256) void mlp_layer_kernel(const double* __restrict
     }
 }
 
+// The same layer for every member of an ensemble of equally shaped heads in one launch: member e
+// reads its own parameters and (after the first layer) its own activations.
+__global__ __launch_bounds__(256) void ensemble_layer_kernel(EnsembleLayer a) {
+    const size_t wid = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const size_t per_member = (size_t)a.B * a.out_dim;
+    if (wid >= per_member * a.n_members) return;
+    const int e = (int)(wid / per_member);
+    const size_t r = wid % per_member;
+    const int b = (int)(r / a.out_dim), o = (int)(r % a.out_dim);
+    const float* w = a.W[e] + (size_t)o * a.in_dim;
+    const double* in64 = a.in64 ? a.in64 + ((size_t)e * a.B + b) * a.in_dim : nullptr;
+    const float* in32 = a.in32 + (size_t)b * a.in_dim;
+    double acc = 0.0;
+    for (int i = lane; i < a.in_dim; i += 64) {
+        const double v = in64 ? in64[i] : (double)in32[i];
+        acc += (double)w[i] * v;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) {
+        double z = acc + (double)a.bias[e][o];
+        if (!a.last) z = (a.act == BRL_ACT_RELU) ? fmax(z, 0.0) : tanh(z);
+        if (a.last) a.out32[(size_t)e * a.B + b] = (float)z;            // out_dim == 1 on the last layer
+        else a.out64[((size_t)e * a.B + b) * a.out_dim + o] = z;
+    }
+}
+
+// mean[b] = (sum over members, in member order, of each[e][b]) / n in fp64, rounded once
+__global__ __launch_bounds__(256) void ensemble_mean_kernel(const float* __restrict__ each, int n, int B,
+                                                             float* __restrict__ mean) {
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    double t = 0.0;
+    for (int e = 0; e < n; ++e) t += (double)each[(size_t)e * B + b];
+    mean[b] = (float)(t / (double)n);
+}
+
 }  // namespace
+
+int launch_ensemble_layer(const EnsembleLayer& a, hipStream_t s) {
+    const size_t waves = (size_t)a.n_members * a.B * a.out_dim;
+    LaunchTimer tm(BRL_KC_OTHER, s);
+    hipLaunchKernelGGL(ensemble_layer_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, a);
+    BRL_LAUNCH_CHECK("ensemble_layer_kernel");
+    return BRL_OK;
+}
+
+int launch_ensemble_mean(const float* each, int n, int B, float* mean, hipStream_t s) {
+    LaunchTimer tm(BRL_KC_OTHER, s);
+    hipLaunchKernelGGL(ensemble_mean_kernel, dim3((B + 255) / 256), dim3(256), 0, s, each, n, B, mean);
+    BRL_LAUNCH_CHECK("ensemble_mean_kernel");
+    return BRL_OK;
+}
 
 int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s) {
     const size_t n8 = n / 8;

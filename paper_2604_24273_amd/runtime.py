@@ -47,20 +47,23 @@ class PackedLinear:
 _qws: Optional[torch.Tensor] = None
 
 
-def quantize_linear(W, eps: float = 1e-5, want_codes: bool = False) -> PackedLinear:
-    """fp32 master weights (numpy or torch, host or device) -> packed ternary weights on the GPU."""
+def quantize_linear(W, eps: float = 1e-5, want_codes: bool = False, int8: bool = False) -> PackedLinear:
+    """fp32 master weights (numpy or torch, host or device) -> packed ternary (or int8) weights on the GPU."""
     global _qws
     if isinstance(W, np.ndarray):
         W = torch.from_numpy(np.ascontiguousarray(W, dtype=np.float32))
     Wd = W.to(DEV, dtype=torch.float32).contiguous()
     n, k = Wd.shape
-    packed = device_bytes(B.brl_packed_bytes(n, k))
+    packed = device_bytes(B.brl_packed_int8_bytes(n, k) if int8 else B.brl_packed_bytes(n, k))
     beta = torch.empty(1, dtype=torch.float32, device=DEV)
     codes = torch.empty((n, k), dtype=torch.int8, device=DEV) if want_codes else None
     need = B.brl_quantize_workspace_bytes(n, k)
     if _qws is None or _qws.numel() < need:
         _qws = device_bytes(need)
-    B.bitlinear_quantize_weights(Wd, eps, packed, beta, codes, _qws)
+    if int8:
+        B.bitlinear_quantize_weights_int8(Wd, eps, packed, beta, codes, _qws)
+    else:
+        B.bitlinear_quantize_weights(Wd, eps, packed, beta, codes, _qws)
     return PackedLinear(packed, beta, n, k, codes)
 
 
@@ -94,7 +97,7 @@ class EncoderHandle:
 
     def __init__(self, shape: synth.EncoderShape, seed: int = 0, eps_norm: float = 1e-5, eps_act: float = 1e-5,
                  layer_sink=None, n_layers: Optional[int] = None,
-                 attn_precision: int = B.BRL_ATTN_MFMA):
+                 attn_precision: int = B.BRL_ATTN_MFMA, int8_weights: bool = False):
         self.shape = shape
         L = shape.n_layers if n_layers is None else n_layers
         self.keep: List[object] = []
@@ -108,7 +111,7 @@ class EncoderHandle:
                 fut = ex.submit(synth.encoder_layer, seed, shape, l + 1) if l + 1 < L else None
                 if layer_sink is not None:
                     layer_sink(l, w)
-                t = {k: (dev(v) if v.ndim == 1 else quantize_linear(v, eps_act)) for k, v in w.items()}
+                t = {k: (dev(v) if v.ndim == 1 else quantize_linear(v, eps_act, int8=int8_weights)) for k, v in w.items()}
                 self.keep.append(t)
                 s = self.layer_structs[l]
                 s.attn_norm_g = t["attn_norm_g"].data_ptr()
@@ -121,6 +124,7 @@ class EncoderHandle:
                                            t["W_up"].beta, t["ffn_subln_g"], t["W_down"].packed, t["W_down"].beta)
         self.struct = B.brl_encoder(L, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f, shape.vocab,
                                     shape.rope_theta, eps_norm, eps_act, attn_precision,
+                                    B.BRL_W_INT8 if int8_weights else B.BRL_W_TERNARY,
                                     self.embedding.data_ptr(), self.final_norm_g.data_ptr(),
                                     C.cast(self.layer_structs, C.POINTER(B.brl_layer_weights)))
         self.ws: Optional[Workspace] = None
@@ -167,6 +171,30 @@ class HeadHandle:
         value = torch.empty((b,), dtype=torch.float32, device=DEV)
         B.policy_value_head(self.struct, h, b, logits, value, self.ws.buf)
         return logits, value
+
+
+class ValueEnsemble:
+    """n value heads of one shape evaluated together and averaged."""
+
+    def __init__(self, members_wb, act: int = B.BRL_ACT_TANH):
+        self._keep = []
+        mlps = []
+        for ws, bs in members_wb:
+            m, k = B.make_mlp([dev(w) for w in ws], [dev(b) for b in bs], act)
+            mlps.append(m)
+            self._keep.append(k)
+        self.n = len(mlps)
+        self.members = B.make_mlp_array(mlps)
+        self.ws: Optional[Workspace] = None
+
+    def forward(self, h: torch.Tensor, want_each: bool = True):
+        b = h.shape[0]
+        need = B.brl_value_ensemble_workspace_bytes(self.members, self.n, b)
+        self.ws = Workspace(need) if self.ws is None else self.ws.ensure(need)
+        mean = torch.empty((b,), dtype=torch.float32, device=DEV)
+        each = torch.empty((self.n, b), dtype=torch.float32, device=DEV) if want_each else None
+        B.value_ensemble_forward(self.members, self.n, h, b, mean, each, self.ws.buf)
+        return mean, each
 
 
 class PPOTrainer:

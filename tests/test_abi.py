@@ -35,7 +35,7 @@ def test_header_symbols_are_exported_and_bound(B):
     for n in names:
         assert hasattr(handle, n), n
     assert set(names) == set(B.EXPORTS)
-    assert B.brl_abi_version() == 1
+    assert B.brl_abi_version() == 2
 
 
 def test_struct_layouts_match_the_header(B):
@@ -93,10 +93,10 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.ffn_block_forward(C.byref(w), fake, 0, 4, 128, 256, 1e-5, 1e-5, fake, fake, 1 << 30, None) == B.BRL_EINVAL
     enc = B.brl_encoder()
     assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
-    enc = B.brl_encoder(0, 256, 4, 3, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
+    enc = B.brl_encoder(0, 256, 4, 3, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 0, 0x1000, 0x1000, None)
     assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
     assert "n_kv_heads" in err()
-    enc = B.brl_encoder(0, 256, 4, 2, 48, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
+    enc = B.brl_encoder(0, 256, 4, 2, 48, 512, 100, 1e4, 1e-5, 1e-5, 0, 0, 0x1000, 0x1000, None)
     assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
     assert "head_dim" in err()
     # PPO head update: shapes and hyper-parameters are checked on the host
@@ -118,7 +118,7 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.ppo_gae(fake, fake, fake, fake, 1, 0, 0.99, 0.95, fake, fake, None) == B.BRL_EINVAL
     assert lib.ppo_gae(fake, fake, fake, fake, 1, 8, 1.5, 0.95, fake, fake, None) == B.BRL_EINVAL
     # packed layout: the host copy of the cumulative lengths is checked before anything is launched
-    enc = B.brl_encoder(0, 256, 4, 2, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 0x1000, 0x1000, None)
+    enc = B.brl_encoder(0, 256, 4, 2, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 0, 0x1000, 0x1000, None)
     import numpy as np
     for cu, max_len in (([1, 5], 8), ([0, 5, 5], 8), ([0, 9], 8), ([0, 3, 2], 8)):
         cu_h = np.asarray(cu, dtype=np.int32)
@@ -131,6 +131,29 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.brl_encoder_packed_workspace_bytes(C.byref(enc), 2, 1, 8) == 0
     head = B.brl_head()
     assert lib.policy_value_head(C.byref(head), fake, 1, fake, fake, fake, 1 << 20, None) == B.BRL_EINVAL
+    # int8-weight variant and ensemble critic
+    enc = B.brl_encoder(0, 256, 4, 2, 64, 512, 100, 1e4, 1e-5, 1e-5, 0, 7, 0x1000, 0x1000, None)
+    assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
+    assert "weight_format" in err()
+    assert lib.brl_packed_int8_bytes(33, 130) == 64 * 256 and lib.brl_packed_int8_bytes(0, 8) == 0
+    assert lib.bitlinear_quantize_weights_int8(fake, 4, 4, 0.0, fake, fake, None, fake, 1 << 20, None) == B.BRL_EINVAL
+    assert lib.bitlinear_quantize_weights_int8(fake, 4, 4, 1e-5, fake, fake, None, fake, 8, None) == B.BRL_ENOSPC
+    assert lib.bitlinear_int8_forward(fake, fake, 32, 100, fake, 0, 1, 1e-5, fake, None, None, None, None, fake, 1 << 20, None) == B.BRL_EINVAL
+    assert lib.bitlinear_int8_forward(fake, fake, 32, 128, fake, 0, 64, 1e-5, fake, None, None, None, None, fake, 16, None) == B.BRL_ENOSPC
+    import ctypes
+    dims_a = (ctypes.c_int * 3)(16, 8, 1)
+    dims_b = (ctypes.c_int * 3)(16, 4, 1)
+    tbl = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    mk = lambda dims: B.brl_mlp(2, ctypes.cast(dims, ctypes.POINTER(ctypes.c_int)), ctypes.cast(tbl, ctypes.POINTER(ctypes.c_void_p)),
+                                ctypes.cast(tbl, ctypes.POINTER(ctypes.c_void_p)), B.BRL_ACT_TANH)
+    same = B.make_mlp_array([mk(dims_a), mk(dims_a), mk(dims_a)])
+    assert lib.brl_value_ensemble_workspace_bytes(same, 3, 10) > 0
+    assert lib.brl_value_ensemble_workspace_bytes(same, 9, 10) == 0
+    assert lib.value_ensemble_forward(same, 3, fake, 10, fake, None, fake, 16, None) == B.BRL_ENOSPC
+    assert lib.value_ensemble_forward(same, 0, fake, 10, fake, None, fake, 1 << 20, None) == B.BRL_EINVAL
+    mixed = B.make_mlp_array([mk(dims_a), mk(dims_b)])
+    assert lib.value_ensemble_forward(mixed, 2, fake, 10, fake, None, fake, 1 << 20, None) == B.BRL_EINVAL
+    assert "differs" in err()
 
 
 def test_product_never_imports_the_oracle():
