@@ -64,6 +64,7 @@ def main() -> int:
     ap.add_argument("--no-gemv", action="store_true")
     ap.add_argument("--no-ppo", action="store_true")
     ap.add_argument("--no-single-state", action="store_true")
+    ap.add_argument("--no-critics", action="store_true", help="skip the int8-weight critic encoder and ensemble legs")
     ap.add_argument("--cpu-sample-states", type=int, default=2)
     ap.add_argument("--gemv-calls", type=int, default=1000)
     ap.add_argument("--streams", type=int, default=1,
@@ -112,7 +113,8 @@ def main() -> int:
             oracle_jobs.append(pool.submit(_oracle_layer, w))
 
     t0 = time.time()
-    enc = R.EncoderHandle(shape, seed=0, layer_sink=sink, n_layers=n_layers)
+    want_critics = not args.no_critics and args.workload == "encoder-2b"
+    enc = R.EncoderHandle(shape, seed=0, layer_sink=sink, n_layers=n_layers, int8_twin=want_critics)
     head = R.HeadHandle(shape, seed=0)
     ids_host = synth.token_ids(0, 500, (Bn, S), shape.vocab)
     if packed:
@@ -229,6 +231,11 @@ def main() -> int:
     if not args.no_ppo and shape is synth.SHAPE_2B:
         ppo = bench_ppo(torch, B, R, synth, np, shape, want_cpu)
 
+    # ---- critic variants of the ablation: int8-weight backbone on the same batch, ensembles of value heads
+    critics = None
+    if want_critics:
+        critics = bench_critics(torch, B, R, synth, enc, ids, Bn, S, shape, args.steps, args.warmup)
+
     # ---- CPU oracle on a bounded sample of the same workload
     cpu = None
     if want_cpu:
@@ -281,6 +288,7 @@ def main() -> int:
         "gemv_pair": gemv,
         "single_state_latency": single,
         "ppo_head_update": ppo,
+        "critic_variants": critics,
         "concurrent_microbatches": concurrent,
         "paper_context": {"hardware": "Raspberry Pi 4 (Cortex-A72 @ 1.5 GHz), bitnet.cpp", "steps_per_s": 40.3,
                           "median_latency_ms": 24.8, "note": "one 15-40 token state per step; context only"},
@@ -347,6 +355,57 @@ def bench_single_state(torch, B, R, synth, np, enc, head, shape, n_tokens: int =
             "hip_graph_replay_ms_per_state": None if graph_ms is None else round(graph_ms, 4),
             "graph_replays_match_eager": same,
             "states_per_s_one_at_a_time": round(1e3 / (graph_ms if graph_ms else eager_ms), 1)}
+
+
+def bench_critics(torch, B, R, synth, enc, ids, Bn: int, S: int, shape, steps: int, warmup: int):
+    """The hybrid-precision and ensemble rows of the paper's ablation table: the same batch through the int8-weight
+    encoder (per-tensor absmax int8 weights of the same master matrices), and 1 / 3 / 5 value heads on the cached h."""
+    twin = enc.int8_twin
+    twin.ws = R.Workspace(B.brl_encoder_workspace_bytes(twin.struct, Bn, S))
+    h8 = torch.empty((Bn, shape.d), dtype=torch.float32, device="cuda")
+
+    def run():
+        B.encoder_forward(twin.struct, ids, Bn, S, None, h8, twin.ws.buf)
+
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    for k in range(len(B.KERNEL_CLASSES)):
+        B.brl_timing_read(k)
+    B.brl_timing_enable(True)
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    B.brl_timing_enable(False)
+    n, gms, ops = B.brl_timing_read_ops(B.BRL_KC_GEMM_NARROW)
+    for k in range(len(B.KERNEL_CLASSES)):
+        B.brl_timing_read(k)
+    h1 = enc.forward(ids)
+    out = {"int8_weight_encoder": {"ms_per_step": round(ms, 4), "states_per_s": round(Bn / ms * 1e3, 1),
+                                   "weight_bytes": int(sum(t[k].packed.numel() for t in enc.keep[1::2] for k in t
+                                                           if hasattr(t[k], "packed"))),
+                                   "gemm_kernel": "gemm_lds_w8_kernel<2,2,2,2>",
+                                   "gemm_ms_per_step": round(gms / steps, 4),
+                                   "gemm_tops": round(ops / (gms * 1e-3) / 1e12, 2) if gms > 0 else 0.0}}
+    dims = [shape.d, 256, 1]
+    ens = {}
+    for n_members in (1, 3, 5):
+        e = R.ValueEnsemble([synth.mlp_params(0, 400 + 20 * i, dims) for i in range(n_members)])
+        for _ in range(5):
+            e.forward(h1, want_each=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(50):
+            e.forward(h1, want_each=False)
+        torch.cuda.synchronize()
+        ens["%d_heads_us" % n_members] = round((time.perf_counter() - t0) / 50 * 1e6, 1)
+    out["value_ensemble"] = dict(ens, batch=Bn, dims=dims, launches_per_call=3)
+    return out
 
 
 def bench_ppo(torch, B, R, synth, np, shape, want_cpu: bool, T: int = 2048, batch: int = 64, epochs: int = 4):

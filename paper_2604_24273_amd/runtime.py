@@ -93,17 +93,22 @@ class FFNHandle:
 
 
 class EncoderHandle:
-    """Device-resident packed encoder: embedding, per-layer packed weights, the ABI structs."""
+    """Device-resident packed encoder: embedding, per-layer packed weights, the ABI structs.
+
+    int8_weights: every BitLinear matrix as an int8 blob (the higher-precision critic backbone).
+    int8_twin: additionally build `self.int8_twin`, the int8-weight encoder of the same master weights
+    (shares the embedding and the gains; the masters are drawn once)."""
 
     def __init__(self, shape: synth.EncoderShape, seed: int = 0, eps_norm: float = 1e-5, eps_act: float = 1e-5,
                  layer_sink=None, n_layers: Optional[int] = None,
-                 attn_precision: int = B.BRL_ATTN_MFMA, int8_weights: bool = False):
+                 attn_precision: int = B.BRL_ATTN_MFMA, int8_weights: bool = False, int8_twin: bool = False):
         self.shape = shape
         L = shape.n_layers if n_layers is None else n_layers
         self.keep: List[object] = []
         self.embedding = torch.from_numpy(synth.embedding_bf16(seed, shape).view(np.int16)).to(DEV)
         self.final_norm_g = dev(synth.final_norm_gain(seed, shape))
         self.layer_structs = (B.brl_layer_weights * max(L, 1))()
+        twin_structs = (B.brl_layer_weights * max(L, 1))() if int8_twin else None
         with ThreadPoolExecutor(max_workers=2) as ex:
             fut = ex.submit(synth.encoder_layer, seed, shape, 0) if L > 0 else None
             for l in range(L):
@@ -113,21 +118,40 @@ class EncoderHandle:
                     layer_sink(l, w)
                 t = {k: (dev(v) if v.ndim == 1 else quantize_linear(v, eps_act, int8=int8_weights)) for k, v in w.items()}
                 self.keep.append(t)
-                s = self.layer_structs[l]
-                s.attn_norm_g = t["attn_norm_g"].data_ptr()
-                s.wq_packed, s.wq_beta = t["Wq"].packed.data_ptr(), t["Wq"].beta.data_ptr()
-                s.wk_packed, s.wk_beta = t["Wk"].packed.data_ptr(), t["Wk"].beta.data_ptr()
-                s.wv_packed, s.wv_beta = t["Wv"].packed.data_ptr(), t["Wv"].beta.data_ptr()
-                s.attn_subln_g = t["attn_subln_g"].data_ptr()
-                s.wo_packed, s.wo_beta = t["Wo"].packed.data_ptr(), t["Wo"].beta.data_ptr()
-                s.ffn = B.make_ffn_weights(t["ffn_norm_g"], t["W_gate"].packed, t["W_gate"].beta, t["W_up"].packed,
-                                           t["W_up"].beta, t["ffn_subln_g"], t["W_down"].packed, t["W_down"].beta)
-        self.struct = B.brl_encoder(L, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f, shape.vocab,
-                                    shape.rope_theta, eps_norm, eps_act, attn_precision,
-                                    B.BRL_W_INT8 if int8_weights else B.BRL_W_TERNARY,
-                                    self.embedding.data_ptr(), self.final_norm_g.data_ptr(),
-                                    C.cast(self.layer_structs, C.POINTER(B.brl_layer_weights)))
+                self._fill(self.layer_structs[l], t)
+                if int8_twin:
+                    t8 = {k: (t[k] if v.ndim == 1 else quantize_linear(v, eps_act, int8=True)) for k, v in w.items()}
+                    self.keep.append(t8)
+                    self._fill(twin_structs[l], t8)
+
+        def make(structs, fmt):
+            return B.brl_encoder(L, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f, shape.vocab,
+                                 shape.rope_theta, eps_norm, eps_act, attn_precision, fmt,
+                                 self.embedding.data_ptr(), self.final_norm_g.data_ptr(),
+                                 C.cast(structs, C.POINTER(B.brl_layer_weights)))
+
+        self.struct = make(self.layer_structs, B.BRL_W_INT8 if int8_weights else B.BRL_W_TERNARY)
         self.ws: Optional[Workspace] = None
+        self.int8_twin: Optional["EncoderHandle"] = None
+        if int8_twin:
+            twin = object.__new__(EncoderHandle)
+            twin.shape, twin.keep, twin.embedding, twin.final_norm_g = shape, self.keep, self.embedding, self.final_norm_g
+            twin.layer_structs = twin_structs
+            twin.struct = make(twin_structs, B.BRL_W_INT8)
+            twin.ws = None
+            twin.int8_twin = None
+            self.int8_twin = twin
+
+    @staticmethod
+    def _fill(s, t) -> None:
+        s.attn_norm_g = t["attn_norm_g"].data_ptr()
+        s.wq_packed, s.wq_beta = t["Wq"].packed.data_ptr(), t["Wq"].beta.data_ptr()
+        s.wk_packed, s.wk_beta = t["Wk"].packed.data_ptr(), t["Wk"].beta.data_ptr()
+        s.wv_packed, s.wv_beta = t["Wv"].packed.data_ptr(), t["Wv"].beta.data_ptr()
+        s.attn_subln_g = t["attn_subln_g"].data_ptr()
+        s.wo_packed, s.wo_beta = t["Wo"].packed.data_ptr(), t["Wo"].beta.data_ptr()
+        s.ffn = B.make_ffn_weights(t["ffn_norm_g"], t["W_gate"].packed, t["W_gate"].beta, t["W_up"].packed,
+                                   t["W_up"].beta, t["ffn_subln_g"], t["W_down"].packed, t["W_down"].beta)
 
     def forward(self, ids: torch.Tensor, lengths: Optional[torch.Tensor] = None) -> torch.Tensor:
         b, s = ids.shape
