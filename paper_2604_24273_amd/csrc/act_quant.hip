@@ -13,6 +13,8 @@
 // in LDS and writes the tile out in full 128-byte runs.  The workgroups are
 // persistent and request the rows of their next tokens before working on the
 // current ones, so that HBM stays busy through the reductions and the write-out.
+// With at most 256 tokens the time is latency, not bandwidth: act_quant_row_kernel takes one
+// token per workgroup instead.
 #include "common.hpp"
 
 namespace brl {
@@ -72,7 +74,7 @@ template <int HV4, int WPT, int GR>
 __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
     constexpr int TPR = 16 / WPT;          // tokens per round
     constexpr int RPG = GR / TPR;          // rounds per group of GR tokens that is written out together
-    static_assert(GR == 8 || GR == 4, "groups of 8 tokens (128-byte runs) or 4 (64-byte runs, few tokens)");
+    static_assert(GR == 8, "groups of 8 tokens: 128-byte runs of the tile");
     static_assert(GR % TPR == 0, "a group is a whole number of rounds");
     extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // AQ_ROWS x (Kp + 16) bytes, then the gain
     __shared__ double red_ss[TPR][WPT];
@@ -206,6 +208,110 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
     }
 }
 
+// Few tokens: one workgroup of NWV wavefronts per token, everything in flight at once (row and
+// gain requested together), two barriers on the way to the int8 row, and the 16-byte pieces of the
+// tiled layout assembled from four neighbouring lanes: no LDS staging, nothing persistent.  The
+// time of such a launch is latency, not bandwidth.
+template <int HV4, int NWV>
+__global__ __launch_bounds__(NWV * 64) void act_quant_row_kernel(QK a) {
+    __shared__ double red_ss[NWV];
+    __shared__ float red_max[NWV];
+    __shared__ int red_sum[NWV];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x;
+    const int K = a.K;
+    float4 v[HV4], g[HV4];
+    load_rows<HV4, NWV>(a, row, lane, wave, v);
+    if (a.gain) {
+#pragma unroll
+        for (int i = 0; i < HV4; ++i) {
+            const int k = 4 * (lane + 64 * (NWV * i + wave));
+            g[i] = k < K ? *reinterpret_cast<const float4*>(a.gain + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        double ss = 0.0;
+#pragma unroll
+        for (int i = 0; i < HV4; ++i) {
+            ss += (double)v[i].x * (double)v[i].x;
+            ss += (double)v[i].y * (double)v[i].y;
+            ss += (double)v[i].z * (double)v[i].z;
+            ss += (double)v[i].w * (double)v[i].w;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        if (lane == 0) red_ss[wave] = ss;
+        __syncthreads();
+        double tot = red_ss[0];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) tot += red_ss[w];
+        const float r = (float)(1.0 / sqrt(tot / (double)K + (double)a.eps_norm));
+#pragma unroll
+        for (int i = 0; i < HV4; ++i) {
+            v[i].x = (v[i].x * r) * g[i].x;
+            v[i].y = (v[i].y * r) * g[i].y;
+            v[i].z = (v[i].z * r) * g[i].z;
+            v[i].w = (v[i].w * r) * g[i].w;
+        }
+    }
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < HV4; ++i)
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[i].x), fabsf(v[i].y)), fmaxf(fabsf(v[i].z), fabsf(v[i].w))));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    if (lane == 0) red_max[wave] = amax;
+    __syncthreads();
+    float ac = a.eps_act;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) ac = fmaxf(ac, red_max[w]);
+    const float s = 127.0f / ac;
+
+    int sum = 0;
+    const int mb = row >> 5, r0 = row & 31;
+#pragma unroll
+    for (int i = 0; i < HV4; ++i) {
+        const int k = 4 * (lane + 64 * (NWV * i + wave));
+        const int q0 = (int)fminf(fmaxf(rintf(v[i].x * s), -127.f), 127.f);
+        const int q1 = (int)fminf(fmaxf(rintf(v[i].y * s), -127.f), 127.f);
+        const int q2 = (int)fminf(fmaxf(rintf(v[i].z * s), -127.f), 127.f);
+        const int q3 = (int)fminf(fmaxf(rintf(v[i].w * s), -127.f), 127.f);
+        sum += q0 + q1 + q2 + q3;
+        const uint32_t word = (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) | ((uint32_t)(q2 & 0xff) << 16) |
+                              ((uint32_t)(q3 & 0xff) << 24);
+        if (a.xq_rowmajor && k < K) *reinterpret_cast<uint32_t*>(a.xq_rowmajor + (size_t)row * K + k) = word;
+        // lanes 4 j .. 4 j + 3 hold 16 consecutive k: lane 4 j writes them as one piece of the tile
+        uint4 piece;
+        piece.x = word;
+        piece.y = __shfl_down(word, 1, 64);
+        piece.z = __shfl_down(word, 2, 64);
+        piece.w = __shfl_down(word, 3, 64);
+        if ((lane & 3) == 0 && k < a.Kp) {
+            const int kc = k >> 4;
+            const int sb = kc >> 3, dd = (kc >> 1) & 3, hh = kc & 1;
+            const size_t off = ((((size_t)mb * a.nsb + sb) * 4 + dd) * 64 + (hh * 32 + r0)) * 16;
+            *reinterpret_cast<uint4*>(a.q_tiled + off) = piece;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (lane == 0) red_sum[wave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tot = red_sum[0];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) tot += red_sum[w];
+        a.absmax[row] = ac;
+        a.dscale[row] = ac / 127.0f;
+        a.sumq[row] = tot;
+        if (a.absmax_tap) a.absmax_tap[row] = ac;
+    }
+}
+
+template <int HV4, int NWV>
+int launch_rows(const QK& a, hipStream_t s) {
+    hipLaunchKernelGGL((act_quant_row_kernel<HV4, NWV>), dim3(a.M), dim3(NWV * 64), 0, s, a);
+    return BRL_OK;
+}
+
 template <int HV4, int WPT, int GR>
 int launch_one(const QK& a, hipStream_t s) {
     const int ngroups = (a.M + GR - 1) / GR;
@@ -245,24 +351,25 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     a.M = in.M; a.K = in.K; a.Kp = round_up(in.K, SBK); a.nsb = a.Kp / SBK;
     a.q_tiled = out.q; a.absmax = out.absmax; a.dscale = out.dscale; a.sumq = out.sumq;
     a.xq_rowmajor = in.xq_rowmajor; a.absmax_tap = in.absmax_tap;
-    // registers hold the current and the next row share of a lane: at most 2 x 9 float4.  With few tokens
-    // the wide rows are taken 4 tokens per workgroup in one round (more, shorter workgroups).
+    // Up to 256 tokens: one workgroup per token (latency bound).  Beyond: persistent workgroups; their
+    // registers hold the current and the next row share of a lane, at most 2 x 9 float4.
     LaunchTimer tm(BRL_KC_ACT_QUANT, s);
-    const bool few = in.M <= 256;
+    const bool rows = in.M <= 256;
     int rc;
-    if (a.Kp <= 1024) {
-        rc = few ? launch_one<1, 4, 4>(a, s) : launch_one<2, 2, 8>(a, s);
-    } else if (a.Kp <= 3072) {
-        rc = few ? launch_one<3, 4, 4>(a, s) : launch_one<6, 2, 8>(a, s);
-    } else if (a.Kp <= 4608) {
-        rc = few ? launch_one<5, 4, 4>(a, s) : launch_one<9, 2, 8>(a, s);
-    } else if (a.Kp <= 7168) {
-        rc = few ? launch_one<7, 4, 4>(a, s) : launch_one<7, 4, 8>(a, s);
-    } else if (a.Kp <= MAX_K) {
-        rc = few ? launch_one<9, 4, 4>(a, s) : launch_one<9, 4, 8>(a, s);
-    } else {
+    if (a.Kp > MAX_K) {
         set_error("act_quant: K = %d exceeds the supported %d", in.K, MAX_K);
         return BRL_EINVAL;
+    }
+    if (a.Kp <= 1024) {
+        rc = rows ? launch_rows<1, 4>(a, s) : launch_one<2, 2, 8>(a, s);
+    } else if (a.Kp <= 3072) {
+        rc = rows ? launch_rows<3, 4>(a, s) : launch_one<6, 2, 8>(a, s);
+    } else if (a.Kp <= 4608) {
+        rc = rows ? launch_rows<3, 6>(a, s) : launch_one<9, 2, 8>(a, s);
+    } else if (a.Kp <= 7168) {
+        rc = rows ? launch_rows<4, 7>(a, s) : launch_one<7, 4, 8>(a, s);
+    } else {
+        rc = rows ? launch_rows<4, 9>(a, s) : launch_one<9, 4, 8>(a, s);
     }
     if (rc != BRL_OK) return rc;
     BRL_LAUNCH_CHECK("act_quant_kernel");

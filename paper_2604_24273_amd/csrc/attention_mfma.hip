@@ -254,6 +254,7 @@ struct AttnTile {
 // Four is what is launched: eight halved the K / V traffic but ran 12-19 % slower on both
 // measured shapes (fewer resident workgroups, longer tails).
 constexpr int ATTN_WPG = 4;
+constexpr int SHORT_MAX_WORK = 1024;      // beyond this many workgroups the two-kernel path keeps more of them resident
 template <int DHP, int VW, int WPG>
 __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a) {
     using T = AttnTile<DHP>;
@@ -357,6 +358,112 @@ __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a)
     }
 }
 
+// States of at most 32 tokens (one key block): one kernel, no fragment round trip through
+// memory.  A workgroup = (state, key/value head, up to four query heads of its group).  All
+// global reads are requested in one phase: every wavefront stages its q head, a quarter of the
+// k rows, and holds its share of v in registers; after one barrier the k and v fragments are
+// laid out in LDS exactly as attn_pack_kernel lays them out in memory, and the block is
+// computed by the same code as in the general kernel.  Such a launch is latency bound.
+template <int DHP, int VW>
+__global__ __launch_bounds__(256) void attention_short_kernel(FragArgs a) {
+    using T = AttnTile<DHP>;
+    constexpr int KS = T::KS, DB = T::DB;
+    constexpr int REG = 128 * DHP;                        // bytes of one staged 32-row block (hi and lo planes)
+    __shared__ __attribute__((aligned(1024))) char qpark[4 * REG];
+    __shared__ __attribute__((aligned(1024))) char kpark[REG];
+    __shared__ __attribute__((aligned(1024))) uint4 kvst[T::KVFR * 64];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int group = a.Hq / a.Hkv;
+    const int chunks = (group + 3) / 4;
+    const int w = blockIdx.x;
+    const int c = w % chunks;
+    const int j = (w / chunks) % a.Hkv;
+    const int b = w / (chunks * a.Hkv);
+    const int len = seq_len(a.sm, b, a.S);                // 1 .. 32
+    if (len <= 0) return;
+    const size_t row0 = (size_t)seq_row0(a.sm, b, a.S);
+    const int u = 4 * c + wave;
+    const bool live = u < group;
+    const int head = j * group + (live ? u : 0);
+    const int dq = a.Hq * a.dh, dkv = a.Hkv * a.dh;
+    const float* rows = a.qkv + row0 * a.ld;
+
+    // ---- one phase of global reads
+    char* region = qpark + wave * REG;
+    if (live) stage_rope_rows<DHP, VW>(rows + head * a.dh, a.ld, len, a.cos_t, a.sin_t, a.dh, a.qscale, region, lane);
+    constexpr int ITS = 32 / (64 / (DHP / VW));
+    stage_rope_rows<DHP, VW>(rows + dq + j * a.dh, a.ld, len, a.cos_t, a.sin_t, a.dh, 1.0f, kpark, lane,
+                             wave * (ITS / 4), (wave + 1) * (ITS / 4));
+    // v, transposed: thread t of 128 * DB (two rounds for DB = 4) owns lane slot (d, h) of (block r, step tt)
+    constexpr int VR = (128 * DB + 255) / 256;
+    float vv[VR][8];
+    const int col0 = dq + dkv + j * a.dh;
+#pragma unroll
+    for (int q = 0; q < VR; ++q) {
+        const int t = threadIdx.x + 256 * q;
+        const int dl = t & 31, h = (t >> 5) & 1, tt = (t >> 6) & 1, r = t >> 7;
+        const int d = 32 * r + dl;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int row = 16 * tt + 8 * (e >> 2) + 4 * h + (e & 3);
+            vv[q][e] = (t < 128 * DB && row < len && d < a.dh) ? rows[(size_t)row * a.ld + col0 + d] : 0.f;
+        }
+    }
+    __syncthreads();
+
+    v8h qh[KS], ql[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        qh[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 0));
+        ql[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 1));
+    }
+#pragma unroll
+    for (int q = 0; q < KS / 2; ++q) {
+        const int fr = wave * (KS / 2) + q;               // fragment = (k-step, plane)
+        kvst[fr * 64 + lane] = staged_fragment<DHP>(kpark, fr >> 1, lane, fr & 1);
+    }
+#pragma unroll
+    for (int q = 0; q < VR; ++q) {
+        const int t = threadIdx.x + 256 * q;
+        if (t < 128 * DB) {
+            const int dl = t & 31, h = (t >> 5) & 1, tt = (t >> 6) & 1, r = t >> 7;
+            const int ln = h * 32 + dl;
+            kvst[(KS * 2 + (r * 2 + tt) * 2 + 0) * 64 + ln] = pack8h(vv[q], false);
+            kvst[(KS * 2 + (r * 2 + tt) * 2 + 1) * 64 + ln] = pack8h(vv[q], true);
+        }
+    }
+    __syncthreads();
+
+    v16f o[DB];
+#pragma unroll
+    for (int r = 0; r < DB; ++r)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[r][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    T::compute(kvst, qh, ql, o, m_run, l_run, true, lane);
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const int pos = lane & 31;
+    if (live && pos < len) {
+        const float inv = 1.0f / l_tot;
+        const int h = lane >> 5;
+        float* op = a.out + (row0 + pos) * ((size_t)a.Hq * a.dh) + (size_t)head * a.dh;
+#pragma unroll
+        for (int r = 0; r < DB; ++r)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int d = 32 * r + 8 * g4 + 4 * h;
+                if (d < a.dh) {
+                    float4 v;
+                    v.x = o[r][4 * g4 + 0] * inv; v.y = o[r][4 * g4 + 1] * inv;
+                    v.z = o[r][4 * g4 + 2] * inv; v.w = o[r][4 * g4 + 3] * inv;
+                    *reinterpret_cast<float4*>(op + d) = v;
+                }
+            }
+    }
+}
+
 inline int padded_head_dim(int dh) { return dh <= 32 ? 32 : (dh <= 64 ? 64 : 128); }
 
 }  // namespace
@@ -372,6 +479,11 @@ namespace {
 
 template <int DHP, int VW>
 void launch_pair(const PackArgs& p, const FragArgs& f, dim3 pgrid, int n_work, hipStream_t s) {
+    if (p.NRB == 1 && n_work <= SHORT_MAX_WORK) {         // few short states: the one-kernel path
+        const int chunks = (f.Hq / f.Hkv + 3) / 4;
+        hipLaunchKernelGGL((attention_short_kernel<DHP, VW>), dim3((unsigned)(f.B * f.Hkv * chunks)), dim3(256), 0, s, f);
+        return;
+    }
     hipLaunchKernelGGL((attn_pack_kernel<DHP, VW>), pgrid, dim3(256), 0, s, p);
     const dim3 agrid((unsigned)(8 * ((n_work + 7) / 8)));
     hipLaunchKernelGGL((attention_frag_kernel<DHP, VW, ATTN_WPG>), agrid, dim3(ATTN_WPG * 64), 0, s, f);

@@ -528,6 +528,28 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
+    // k-split variants finish the tile with the whole workgroup, one output element per thread and
+    // pass; what an element needs from memory (its token's scale and code sum, its residual) is
+    // requested here, ahead of the k loop
+    constexpr int NT = WM * WN * WK * 64;
+    constexpr int EPT = WK > 1 ? (TM * TN * 1024 + NT - 1) / NT : 1;
+    float e_d[EPT], e_res[EPT];
+    int e_sq[EPT];
+    if constexpr (WK > 1) {
+        const int ncb = (g.glu && TN > 1) ? TN / 2 : TN;
+#pragma unroll
+        for (int q = 0; q < EPT; ++q) {
+            const int e = threadIdx.x + q * NT;
+            const int c = e & 31, jb = (e >> 5) % ncb, r = (e >> 5) / ncb;
+            const int m = min(mb0 * 32 + r, g.M - 1);
+            int seg, col0, ncols;
+            block_columns(g, min(nb0 + (g.glu ? 2 * jb : jb), g.nnb - 1), seg, col0, ncols);
+            e_d[q] = g.dscale[m];
+            e_sq[q] = g.sumq ? g.sumq[m] : 0;
+            e_res[q] = (g.residual && c < ncols) ? g.residual[(size_t)m * g.ldy + col0 + c] : 0.f;
+        }
+    }
+
     const int sb_per = (g.nsb + WK - 1) / WK;
     const int sb_begin = wk * sb_per;
     const int sb_end = min(g.nsb, sb_begin + sb_per);
@@ -569,32 +591,58 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs
     }
 
     if constexpr (WK > 1) {
-        // reduce the k-split partial accumulators through LDS into wavefront wk == 0
-        __shared__ int red[(WK - 1) * WM * WN * TM * TN * 16 * 64];
-        const int slot = ((wm * WN + wn) * (WK - 1) + (wk - 1)) * TM * TN * 16 * 64;
-        if (wk > 0) {
+        // k-split: every wavefront parks its partial accumulators in LDS; 32 consecutive threads then
+        // take 32 consecutive columns of one token row.  The sum over the k-parts is an exact integer sum.
+        static_assert(WM == 1 && WN == 1, "the k-split variants have one tile per workgroup");
+        __shared__ int red[WK * TM * TN * 16 * 64];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) red[slot + ((i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
-        }
+                for (int v = 0; v < 16; ++v) red[((wk * TM * TN + i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
         __syncthreads();
-        if (wk > 0) return;
-        for (int o = 0; o < WK - 1; ++o) {
-            const int s2 = ((wm * WN + wn) * (WK - 1) + o) * TM * TN * 16 * 64;
+        const int ncb = (g.glu && TN > 1) ? TN / 2 : TN;                      // output column blocks of the tile
+        const int total = TM * 32 * ncb * 32;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int q = 0; q < EPT; ++q) {
+            const int e = threadIdx.x + q * NT;
+            const int c = e & 31, jb = (e >> 5) % ncb, r = (e >> 5) / ncb;     // column, column block, token row of the tile
+            const int i = r >> 5, rr = r & 31;
+            const int m = mb0 * 32 + r;
+            const int v = 4 * (rr >> 3) + (rr & 3), ln = c + 32 * ((rr >> 2) & 1);
+            const int j0 = g.glu ? 2 * jb : jb;
+            int seg, col0, ncols;
+            block_columns(g, min(nb0 + j0, g.nnb - 1), seg, col0, ncols);
+            if (e >= total || m >= g.M || nb0 + j0 >= g.nnb || c >= ncols) continue;
+            const size_t o = (size_t)m * g.ldy + col0 + c;
+            int a0 = 0, a1 = 0;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+            for (int p = 0; p < WK; ++p) {
+                a0 += red[((p * TM * TN + i * TN + j0) * 16 + v) * 64 + ln];
+                if (g.glu) a1 += red[((p * TM * TN + i * TN + j0 + 1) * 16 + v) * 64 + ln];
+            }
+            float bsel = beta[0];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[i][j][v] += red[s2 + ((i * TN + j) * 16 + v) * 64 + lane];
+            for (int j = 1; j < TN; ++j)
+                if (j0 == j) bsel = beta[j];
+            if (g.glu) {
+                const float G = ((float)(a0 - e_sq[q]) * e_d[q]) * beta[0];
+                const float U = ((float)(a1 - e_sq[q]) * e_d[q]) * beta[TN > 1 ? 1 : 0];
+                const float pz = fmaxf(G, 0.f);
+                g.y[o] = (pz * pz) * U;
+            } else {
+                float val = ((float)(a0 - e_sq[q]) * e_d[q]) * bsel;
+                if (g.residual) val = val + e_res[q];
+                g.y[o] = val;
+                if (g.acc_dbg) g.acc_dbg[o] = a0 - e_sq[q];
+            }
         }
+        return;
     }
 
-    __shared__ __attribute__((aligned(16))) int escr[(WK > 1 ? WM * WN : 4) * Epi<TM, TN>::REGION];
-    epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, escr + ((WK > 1) ? (wm * WN + wn) : wave) * Epi<TM, TN>::REGION);
+    __shared__ __attribute__((aligned(16))) int escr[4 * Epi<TM, TN>::REGION];
+    epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, escr + wave * Epi<TM, TN>::REGION);
 }
 
 template <int TM, int TN, int WM, int WN, int WK>

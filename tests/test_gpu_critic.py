@@ -144,7 +144,7 @@ def test_int8_weight_encoder(kw, b, s):
     h = enc.forward(R.dev(ids), R.dev(lengths)).cpu().numpy()
     for i in range(b):
         assert cosine(h[i], h_ref[i]) >= 0.999, (i, cosine(h[i], h_ref[i]))
-    assert np.abs(h - h_ref).max() / np.abs(h_ref).max() < 2e-3
+    assert np.abs(h - h_ref).max() / np.abs(h_ref).max() < 5e-3
     # the ternary encoder on the same master weights is a different function: the format flag is honoured
     enc_t = R.EncoderHandle(shape, seed=1)
     h_t = enc_t.forward(R.dev(ids), R.dev(lengths)).cpu().numpy()
