@@ -360,12 +360,13 @@ __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a)
 
 // States of at most 32 tokens (one key block): one kernel, no fragment round trip through
 // memory.  A workgroup = (state, key/value head, up to four query heads of its group).  All
-// global reads are requested in one phase: every wavefront stages its q head, a quarter of the
-// k rows, and holds its share of v in registers; after one barrier the k and v fragments are
-// laid out in LDS exactly as attn_pack_kernel lays them out in memory, and the block is
-// computed by the same code as in the general kernel.  Such a launch is latency bound.
+// global reads are requested in one phase by two sets of wavefronts side by side: four stage
+// one q head each, four stage a quarter of the k rows each and hold v in registers; after one
+// barrier the k and v fragments are laid out in LDS exactly as attn_pack_kernel lays them out
+// in memory, and the block is computed by the same code as in the general kernel.  Such a
+// launch is latency bound.
 template <int DHP, int VW>
-__global__ __launch_bounds__(256) void attention_short_kernel(FragArgs a) {
+__global__ __launch_bounds__(512) void attention_short_kernel(FragArgs a) {
     using T = AttnTile<DHP>;
     constexpr int KS = T::KS, DB = T::DB;
     constexpr int REG = 128 * DHP;                        // bytes of one staged 32-row block (hi and lo planes)
@@ -383,57 +384,65 @@ __global__ __launch_bounds__(256) void attention_short_kernel(FragArgs a) {
     const int len = seq_len(a.sm, b, a.S);                // 1 .. 32
     if (len <= 0) return;
     const size_t row0 = (size_t)seq_row0(a.sm, b, a.S);
-    const int u = 4 * c + wave;
-    const bool live = u < group;
+    const bool qside = wave < 4;                          // wavefronts 0-3: one q head each; 4-7: k and v
+    const int u = 4 * c + (wave & 3);
+    const bool live = qside && u < group;
     const int head = j * group + (live ? u : 0);
     const int dq = a.Hq * a.dh, dkv = a.Hkv * a.dh;
     const float* rows = a.qkv + row0 * a.ld;
 
-    // ---- one phase of global reads
-    char* region = qpark + wave * REG;
-    if (live) stage_rope_rows<DHP, VW>(rows + head * a.dh, a.ld, len, a.cos_t, a.sin_t, a.dh, a.qscale, region, lane);
+    // ---- one phase of global reads, the two sides in parallel
+    char* region = qpark + (wave & 3) * REG;
     constexpr int ITS = 32 / (64 / (DHP / VW));
-    stage_rope_rows<DHP, VW>(rows + dq + j * a.dh, a.ld, len, a.cos_t, a.sin_t, a.dh, 1.0f, kpark, lane,
-                             wave * (ITS / 4), (wave + 1) * (ITS / 4));
-    // v, transposed: thread t of 128 * DB (two rounds for DB = 4) owns lane slot (d, h) of (block r, step tt)
-    constexpr int VR = (128 * DB + 255) / 256;
+    constexpr int VR = (128 * DB + 255) / 256;            // v: thread t of 128 * DB owns lane slot (d, h) of (block r, step tt)
     float vv[VR][8];
-    const int col0 = dq + dkv + j * a.dh;
+    const int tk = threadIdx.x - 256;
+    if (qside) {
+        if (live) stage_rope_rows<DHP, VW>(rows + head * a.dh, a.ld, len, a.cos_t, a.sin_t, a.dh, a.qscale, region, lane);
+    } else {
+        const int col0 = dq + dkv + j * a.dh;
 #pragma unroll
-    for (int q = 0; q < VR; ++q) {
-        const int t = threadIdx.x + 256 * q;
-        const int dl = t & 31, h = (t >> 5) & 1, tt = (t >> 6) & 1, r = t >> 7;
-        const int d = 32 * r + dl;
+        for (int q = 0; q < VR; ++q) {
+            const int t = tk + 256 * q;
+            const int dl = t & 31, h = (t >> 5) & 1, tt = (t >> 6) & 1, r = t >> 7;
+            const int d = 32 * r + dl;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int row = 16 * tt + 8 * (e >> 2) + 4 * h + (e & 3);
-            vv[q][e] = (t < 128 * DB && row < len && d < a.dh) ? rows[(size_t)row * a.ld + col0 + d] : 0.f;
+            for (int e = 0; e < 8; ++e) {
+                const int row = 16 * tt + 8 * (e >> 2) + 4 * h + (e & 3);
+                vv[q][e] = (t < 128 * DB && row < len && d < a.dh) ? rows[(size_t)row * a.ld + col0 + d] : 0.f;
+            }
         }
+        stage_rope_rows<DHP, VW>(rows + dq + j * a.dh, a.ld, len, a.cos_t, a.sin_t, a.dh, 1.0f, kpark, lane,
+                                 (wave - 4) * (ITS / 4), (wave - 3) * (ITS / 4));
     }
     __syncthreads();
 
     v8h qh[KS], ql[KS];
+    if (qside) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        qh[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 0));
-        ql[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 1));
-    }
+        for (int ks = 0; ks < KS; ++ks) {
+            qh[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 0));
+            ql[ks] = __builtin_bit_cast(v8h, staged_fragment<DHP>(region, ks, lane, 1));
+        }
+    } else {
 #pragma unroll
-    for (int q = 0; q < KS / 2; ++q) {
-        const int fr = wave * (KS / 2) + q;               // fragment = (k-step, plane)
-        kvst[fr * 64 + lane] = staged_fragment<DHP>(kpark, fr >> 1, lane, fr & 1);
-    }
+        for (int q = 0; q < KS / 2; ++q) {
+            const int fr = (wave - 4) * (KS / 2) + q;     // fragment = (k-step, plane)
+            kvst[fr * 64 + lane] = staged_fragment<DHP>(kpark, fr >> 1, lane, fr & 1);
+        }
 #pragma unroll
-    for (int q = 0; q < VR; ++q) {
-        const int t = threadIdx.x + 256 * q;
-        if (t < 128 * DB) {
-            const int dl = t & 31, h = (t >> 5) & 1, tt = (t >> 6) & 1, r = t >> 7;
-            const int ln = h * 32 + dl;
-            kvst[(KS * 2 + (r * 2 + tt) * 2 + 0) * 64 + ln] = pack8h(vv[q], false);
-            kvst[(KS * 2 + (r * 2 + tt) * 2 + 1) * 64 + ln] = pack8h(vv[q], true);
+        for (int q = 0; q < VR; ++q) {
+            const int t = tk + 256 * q;
+            if (t < 128 * DB) {
+                const int dl = t & 31, h = (t >> 5) & 1, tt = (t >> 6) & 1, r = t >> 7;
+                const int ln = h * 32 + dl;
+                kvst[(KS * 2 + (r * 2 + tt) * 2 + 0) * 64 + ln] = pack8h(vv[q], false);
+                kvst[(KS * 2 + (r * 2 + tt) * 2 + 1) * 64 + ln] = pack8h(vv[q], true);
+            }
         }
     }
     __syncthreads();
+    if (!qside) return;
 
     v16f o[DB];
 #pragma unroll
@@ -481,7 +490,7 @@ template <int DHP, int VW>
 void launch_pair(const PackArgs& p, const FragArgs& f, dim3 pgrid, int n_work, hipStream_t s) {
     if (p.NRB == 1 && n_work <= SHORT_MAX_WORK) {         // few short states: the one-kernel path
         const int chunks = (f.Hq / f.Hkv + 3) / 4;
-        hipLaunchKernelGGL((attention_short_kernel<DHP, VW>), dim3((unsigned)(f.B * f.Hkv * chunks)), dim3(256), 0, s, f);
+        hipLaunchKernelGGL((attention_short_kernel<DHP, VW>), dim3((unsigned)(f.B * f.Hkv * chunks)), dim3(512), 0, s, f);
         return;
     }
     hipLaunchKernelGGL((attn_pack_kernel<DHP, VW>), pgrid, dim3(256), 0, s, p);
