@@ -27,19 +27,31 @@ def _oracle_layers(host):
             for w in host]
 
 
-def _build(shape, seed):
+def _oracle_layers_int8(host):
+    from oracle import critic_oracle as C
+    T = C.Int8Linear.from_fp32
+    return [O.LayerWeights(w["attn_norm_g"], T(w["Wq"]), T(w["Wk"]), T(w["Wv"]), w["attn_subln_g"], T(w["Wo"]),
+                           O.FFNWeights(w["ffn_norm_g"], T(w["W_gate"]), T(w["W_up"]), w["ffn_subln_g"], T(w["W_down"])))
+            for w in host]
+
+
+def _build(shape, seed, int8_twin=False):
     from paper_2604_24273_amd import binding as B
     from paper_2604_24273_amd import runtime as R
     B.lib()
-    layers = []
+    layers, layers8 = [], []
 
     def sink(l, w):
         # quantise the oracle's copy right away so the fp32 masters can be dropped
         layers.extend(_oracle_layers([w]))
+        if int8_twin:
+            layers8.extend(_oracle_layers_int8([w]))
 
-    enc = R.EncoderHandle(shape, seed=seed, layer_sink=sink)
+    enc = R.EncoderHandle(shape, seed=seed, layer_sink=sink, int8_twin=int8_twin)
     cfg = O.EncoderConfig(shape.n_layers, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f,
                           shape.vocab, shape.rope_theta)
+    if int8_twin:
+        return B, R, enc, cfg, layers, layers8
     return B, R, enc, cfg, layers
 
 
@@ -48,7 +60,7 @@ def test_encoder_2b_shape_full_batch_sampled_states():
     """30 layers, hidden 2560, 20/5 heads, FFN 6912, vocab 128256; 64 states x 128 tokens; heads 2560->256->18 / 1."""
     shape = synth.SHAPE_2B
     print("encoder 2B shape: building", flush=True)
-    B, R, enc, cfg, layers = _build(shape, 0)
+    B, R, enc, cfg, layers, layers8 = _build(shape, 0, int8_twin=True)
     head = R.HeadHandle(shape, seed=0)
     ids = synth.token_ids(0, 500, (64, 128), shape.vocab)
     print("encoder 2B shape: GPU forward", flush=True)
@@ -90,6 +102,19 @@ def test_encoder_2b_shape_full_batch_sampled_states():
     assert np.all(np.isfinite(hp))
     assert _cos(hp[37], h20[0]) >= 0.999
     assert np.array_equal(hp[37], hl[37])      # padded or packed, among 64 or among 1024 states: the same bits
+    # one short state per call (the deployment shape): per-token quantisation, k-split GEMMs, one-kernel attention
+    print("encoder 2B shape: one 20-token state", flush=True)
+    h1 = enc.forward_packed(R.dev(ids[37, :20].astype(np.int32)), np.asarray([0, 20], np.int32)).cpu().numpy()
+    assert _cos(h1[0], h20[0]) >= 0.999
+    assert np.abs(h1[0] - hl[37]).max() <= 1e-3 * np.abs(hl[37]).max()
+    # the int8-weight encoder of the same master weights (critic backbone), same batch, sampled state
+    print("encoder 2B shape: int8-weight twin", flush=True)
+    h8 = enc.int8_twin.forward(R.dev(ids)).cpu().numpy()
+    assert np.all(np.isfinite(h8))
+    h8_ref = O.encoder_forward(ids[37:38], emb, layers8, gfin, cfg)
+    c8 = _cos(h8[37], h8_ref[0])
+    print("int8 weights, state 37: cosine %.7f" % c8, flush=True)
+    assert c8 >= 0.999
 
 
 @pytest.mark.timeout(1500)
