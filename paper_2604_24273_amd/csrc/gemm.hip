@@ -462,10 +462,12 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         Tile::issue(asrc, bsrc, sb + 1, stage1, wave);
+        __builtin_amdgcn_sched_barrier(0);       // the copy requests stay ahead of the MFMAs that hide them
         Tile::compute(acc, stage0, wm, wn, lane);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (sb + 2 < g.nsb) Tile::issue(asrc, bsrc, sb + 2, stage0, wave);
+        __builtin_amdgcn_sched_barrier(0);
         Tile::compute(acc, stage1, wm, wn, lane);
     }
     if (sb < g.nsb) {
