@@ -81,7 +81,7 @@ struct Carver {
 
 size_t actbuf_bytes(int M, int K) {
     const size_t Mp = round_up(M, NB), Kp = round_up(K, SBK);
-    return round_up_sz(Mp * Kp, ALIGN) + 3 * round_up_sz(Mp * 4, ALIGN);
+    return round_up_sz(Mp * Kp, ALIGN) + 3 * round_up_sz(Mp * 4, ALIGN) + round_up_sz(splitk_capacity_ints(M) * 4, ALIGN);
 }
 
 ActBuf take_actbuf(Carver& c, int M, int K) {
@@ -91,6 +91,8 @@ ActBuf take_actbuf(Carver& c, int M, int K) {
     a.absmax = c.take<float>(Mp);
     a.dscale = c.take<float>(Mp);
     a.sumq = c.take<int32_t>(Mp);
+    a.splitk_ints = splitk_capacity_ints(M);
+    a.splitk = a.splitk_ints ? c.take<int32_t>(a.splitk_ints) : nullptr;
     return a;
 }
 

@@ -75,7 +75,20 @@ struct ActBuf {
     float* absmax;    // [Mp] clamped absmax a'
     float* dscale;    // [Mp] a' / 127
     int32_t* sumq;    // [Mp] sum_k q (for the offset-code correction)
+    int32_t* splitk;  // scratch for the partial tiles of a k-split GEMM reading this buffer (or nullptr)
+    size_t splitk_ints;
 };
+
+// k-split GEMM: used when fewer than SPLITK_MAX_TILES 128 x 128 tiles exist; aims at SPLITK_TARGET_WGS
+// workgroups.  splits * tiles <= target + tiles, so the partial tiles never exceed SPLITK_INTS.
+constexpr int SPLITK_MAX_TILES = 128;
+constexpr int SPLITK_TARGET_WGS = 512;
+constexpr int SPLITK_MIN_SB = 32;           // super-blocks of k (4096 columns) below which k is never cut
+constexpr size_t SPLITK_INTS = (size_t)(SPLITK_TARGET_WGS + SPLITK_MAX_TILES) * 128 * 128;
+inline size_t splitk_capacity_ints(int M) {       // by token count alone: 0 where no k-split can happen
+    const int nmb = round_up(M, NB) / NB;
+    return (nmb <= 4 || (nmb + 3) / 4 >= SPLITK_MAX_TILES) ? 0 : SPLITK_INTS;
+}
 
 // ---- up to three weight matrices sharing one activation (q|k|v, gate|up) ----
 struct WeightSegs {

@@ -52,6 +52,9 @@ struct GemmArgs {
     double ops;              // int8 operations of the product (for the timing hooks)
     int glu;                 // 1: segments are (gate, up) of equal size, interleaved block by block;
                              //    the epilogue emits h = (max(G,0) * max(G,0)) * U, one column per pair
+    int splits;              // > 1: k is cut into `splits` ranges of sb_per_split super-blocks, one workgroup per
+    int sb_per_split;        //      (tile, range); raw int32 partial tiles go to `partials` [splits][M][nnb * 32]
+    int32_t* partials;       //      and splitk_epilogue_kernel finishes the product
 };
 
 __device__ inline v4i expand_codes(uint32_t p) {
@@ -76,11 +79,14 @@ __device__ inline v4i as_v4i(const uint4& u) {
 // XCD-aware tile order: workgroup w runs on XCD (w & 7); each XCD gets a
 // contiguous run of tiles, walked in groups of `group_m` row tiles so that the
 // tiles resident on one XCD share activation and weight panels in its L2.
-__device__ inline bool tile_of_block(const GemmArgs& g, int& tile_m, int& tile_n) {
-    const int total = g.tiles_m * g.tiles_n;
+__device__ inline bool tile_of_block(const GemmArgs& g, int& tile_m, int& tile_n, int& split) {
+    const int tiles = g.tiles_m * g.tiles_n;
+    const int total = tiles * g.splits;
     const int per_xcd = (total + 7) / 8;
-    const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return false;
+    const int T0 = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || T0 >= total) return false;
+    split = T0 / tiles;
+    const int T = T0 - split * tiles;
     const int gsz = g.group_m * g.tiles_n;
     const int grp = T / gsz;
     const int first_m = grp * g.group_m;
@@ -336,6 +342,75 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
     }
 }
 
+// k-split launches: the raw accumulators of this workgroup's k range, row-major, 16 bytes per lane
+template <int TM, int TN>
+__device__ inline void epilogue_partial(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, int split, int lane,
+                                        int* scr) {
+    constexpr int LD = Epi<TM, TN>::LD;
+    constexpr int LPR = TN * 8;
+    constexpr int RPP = 64 / LPR;
+    constexpr int NP = 16 / RPP;
+    static_assert(64 % LPR == 0, "TN must be a power of two");
+    const int c4 = lane % LPR, r0 = lane / LPR;
+    const int ldp = g.nnb * 32;
+    const bool col_ok = nb0 + (c4 >> 3) < g.nnb;
+    int32_t* dst = g.partials + (size_t)split * g.M * ldp + nb0 * 32 + 4 * c4;
+#pragma unroll
+    for (int idx = 0; idx < 2 * TM; ++idx) {
+        const int mbase = (mb0 + (idx >> 1)) * 32 + (idx & 1) * 16;
+        scatter_half<TM, TN>(acc, idx >> 1, idx & 1, lane, scr);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int row = p * RPP + r0;
+            const int4 a = *reinterpret_cast<const int4*>(&scr[row * LD + 4 * c4]);
+            if (col_ok && mbase + row < g.M) *reinterpret_cast<int4*>(dst + (size_t)(mbase + row) * ldp) = a;
+        }
+    }
+}
+
+// Sums the partial tiles of a k-split launch (exact integer sums) and applies the same rescale as the
+// one-pass epilogues.  One thread per token row and four columns of a weight block (a gate / up pair in
+// GLU mode).
+__global__ __launch_bounds__(256) void splitk_epilogue_kernel(GemmArgs g) {
+    const int nob = g.glu ? g.nnb / 2 : g.nnb;                 // output column blocks
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (size_t)g.M * nob * 8) return;
+    const int c = 4 * (int)(t & 7), ob = (int)((t >> 3) % nob), m = (int)((t >> 3) / nob);
+    const int gnb = g.glu ? 2 * ob : ob;
+    int seg, col0, ncols;
+    block_columns(g, gnb, seg, col0, ncols);
+    if (c >= ncols) return;
+    const int ldp = g.nnb * 32;
+    int a0[4] = {0, 0, 0, 0}, a1[4] = {0, 0, 0, 0};
+    for (int sp = 0; sp < g.splits; ++sp) {
+        const int32_t* src = g.partials + ((size_t)sp * g.M + m) * ldp + gnb * 32 + c;
+        const int4 v = *reinterpret_cast<const int4*>(src);
+        a0[0] += v.x; a0[1] += v.y; a0[2] += v.z; a0[3] += v.w;
+        if (g.glu) {
+            const int4 u = *reinterpret_cast<const int4*>(src + 32);
+            a1[0] += u.x; a1[1] += u.y; a1[2] += u.z; a1[3] += u.w;
+        }
+    }
+    const float d = g.dscale[m];
+    const int sq = g.sumq ? g.sumq[m] : 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (c + e >= ncols) break;
+        const size_t o = (size_t)m * g.ldy + col0 + c + e;
+        if (g.glu) {
+            const float G = ((float)(a0[e] - sq) * d) * (*g.beta[0]);
+            const float U = ((float)(a1[e] - sq) * d) * (*g.beta[1]);
+            const float pz = fmaxf(G, 0.f);
+            g.y[o] = (pz * pz) * U;
+        } else {
+            float val = ((float)(a0[e] - sq) * d) * (*g.beta[seg]);
+            if (g.residual) val = val + g.residual[o];
+            g.y[o] = val;
+            if (g.acc_dbg) g.acc_dbg[o] = a0[e] - sq;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Many-token kernel: WM x WN wavefronts, each TM x TN tiles; both operands staged
 // through LDS with direct global->LDS loads, double buffered.
@@ -412,8 +487,8 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wn = wave % WN, wm = wave / WN;
-    int tile_m, tile_n;
-    if (!tile_of_block(g, tile_m, tile_n)) return;
+    int tile_m, tile_n, split;
+    if (!tile_of_block(g, tile_m, tile_n, split)) return;
 
     const int mb_tile0 = tile_m * WM * TM;
     const int mb0 = mb_tile0 + wm * TM;
@@ -456,9 +531,11 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     // Double buffering with two distinct LDS objects: while one is read, the
     // other is filled.  A stage requested in one step is waited for (vmcnt 0)
     // at the top of the next, so its latency hides behind 4*TM*TN MFMAs.
-    Tile::issue(asrc, bsrc, 0, stage0, wave);
-    int sb = 0;
-    for (; sb + 1 < g.nsb; sb += 2) {
+    const int sb_first = split * g.sb_per_split;
+    const int sb_last = min(g.nsb, sb_first + g.sb_per_split);     // (one range covering all of k when splits == 1)
+    Tile::issue(asrc, bsrc, sb_first, stage0, wave);
+    int sb = sb_first;
+    for (; sb + 1 < sb_last; sb += 2) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         Tile::issue(asrc, bsrc, sb + 1, stage1, wave);
@@ -466,11 +543,11 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
         Tile::compute(acc, stage0, wm, wn, lane);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (sb + 2 < g.nsb) Tile::issue(asrc, bsrc, sb + 2, stage0, wave);
+        if (sb + 2 < sb_last) Tile::issue(asrc, bsrc, sb + 2, stage0, wave);
         __builtin_amdgcn_sched_barrier(0);
         Tile::compute(acc, stage1, wm, wn, lane);
     }
-    if (sb < g.nsb) {
+    if (sb < sb_last) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         Tile::compute(acc, stage0, wm, wn, lane);
@@ -480,7 +557,8 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     __syncthreads();
     static_assert((NW / 2) * Epi<TM, TN>::REGION * 4 <= Tile::STAGE * 16, "half of the epilogue regions per stage");
     int* scr = reinterpret_cast<int*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * Epi<TM, TN>::REGION;
-    epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
+    if (g.splits > 1) epilogue_partial<TM, TN>(g, acc, mb0, nb0, split, lane, scr);
+    else epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
 }
 
 template <int TM, int TN, int WM, int WN>
@@ -505,8 +583,8 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs
     const int wk = wave % WK;
     const int wn = (wave / WK) % WN;
     const int wm = wave / (WK * WN);
-    int tile_m, tile_n;
-    if (!tile_of_block(g, tile_m, tile_n)) return;
+    int tile_m, tile_n, split;
+    if (!tile_of_block(g, tile_m, tile_n, split)) return;      // splits == 1 here
 
     const int mb0 = (tile_m * WM + wm) * TM;
     const int nb0 = (tile_n * WN + wn) * TN;
@@ -665,7 +743,7 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
     g.tiles_m = (g.nmb + WM * TM - 1) / (WM * TM);
     g.tiles_n = (g.nnb + WN * TN - 1) / (WN * TN);
     g.group_m = 4;
-    const int total = g.tiles_m * g.tiles_n;
+    const int total = g.tiles_m * g.tiles_n * g.splits;
     const int grid = ((total + 7) / 8) * 8;
     LaunchTimer tm(WN == 4 ? BRL_KC_GEMM : BRL_KC_GEMM_NARROW, s, g.ops);
     if constexpr (W8)
@@ -673,6 +751,11 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
     else
         hipLaunchKernelGGL((gemm_lds_kernel<TM, TN, WM, WN>), dim3(grid), dim3(WM * WN * 64), 0, s, g);
     BRL_LAUNCH_CHECK("gemm_lds_kernel");
+    if (g.splits > 1) {
+        const size_t threads = (size_t)g.M * (g.glu ? g.nnb / 2 : g.nnb) * 8;
+        hipLaunchKernelGGL(splitk_epilogue_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, g);
+        BRL_LAUNCH_CHECK("splitk_epilogue_kernel");
+    }
     return BRL_OK;
 }
 
@@ -709,10 +792,36 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     g.ldy = ldy;
     g.residual = residual;
     g.acc_dbg = acc_dbg;
+    g.splits = 1;
+    g.sb_per_split = g.nsb;
+    g.partials = nullptr;
     g.fast_epilogue = (acc_dbg == nullptr && ldy % 4 == 0) ? 1 : 0;
     for (int i = 0; i < w.count; ++i)
         if ((w.n_end[i] - (i ? w.n_end[i - 1] : 0)) % 32 != 0) g.fast_epilogue = 0;
     (void)N;
+    // Few 128 x 128 tiles and a long k (a few hundred tokens, or a narrow output): k is cut so that about
+    // two workgroups per compute unit run; the partial tiles go through the scratch area of the
+    // activation buffer and a second small kernel.  Integer partial sums: the result is the same.
+    {
+        const long tiles = (long)((g.nmb + 3) / 4) * ((g.nnb + 3) / 4);
+        if (a.splitk && tiles < SPLITK_MAX_TILES) {
+            // (measured at the 2B layer shapes, 160 to 1024 tokens: with k = 2560 the second kernel costs more
+            //  than the idle compute units, with k = 6912 the cut saves 20 to 30 %)
+            int want = (int)((SPLITK_TARGET_WGS + tiles - 1) / tiles);
+            const int maxs = g.nsb >= SPLITK_MIN_SB ? g.nsb / 6 : 1;     // long k only, at least 768 k per range
+            if (want > maxs) want = maxs;
+            if (want >= 2) {
+                const int per = (g.nsb + want - 1) / want;
+                const int splits = (g.nsb + per - 1) / per;
+                if (splits >= 2 && (size_t)splits * M * g.nnb * 32 <= a.splitk_ints) {
+                    g.splits = splits;
+                    g.sb_per_split = per;
+                    g.partials = a.splitk;
+                    return w.w8 ? launch_lds<2, 2, 2, 2, true>(g, s) : launch_lds<2, 2, 2, 2, false>(g, s);
+                }
+            }
+        }
+    }
     // int8 weights: the LDS-staged 128 x 128 tile at every size (32 KB per stage)
     if (w.w8) return launch_lds<2, 2, 2, 2, true>(g, s);
     // Tile choice: k-split wavefronts for skinny (few-token) problems, where weight

@@ -99,7 +99,8 @@ def _run_bitlinear(B, R, pl, X, residual=None, taps=True):
     (16, 2048, 2048),     # single-layer config
     (1, 6912, 2560), (1, 2560, 6912), (2, 2560, 6912), (3, 200, 264), (4, 6912, 2560),   # GEMV path
     (5, 96, 128), (33, 200, 264), (64, 2560, 2560), (100, 640, 2560), (300, 1000, 520),
-    (256, 6912, 2560), (257, 2560, 6912), (1100, 3200, 3200),
+    (256, 6912, 2560), (257, 2560, 6912), (1100, 3200, 3200),   # the second: few tiles, long k -> a k-split launch
+    (200, 1000, 4608), (700, 264, 6912),                         # k-split with a ragged last column block
     (2050, 8192, 264), (2048, 8200, 128),      # enough tiles for the 8-wavefront kernel, ragged edges
 ])
 def test_bitlinear_forward_parity(m, n, k):
@@ -201,7 +202,8 @@ def test_bitlinear_forward_batch(m, n, k, count, bf16):
 
 # ---------------------------------------------------------------------- FFN
 
-@pytest.mark.parametrize("m,d,f,bf16", [(256, 2560, 6912, True), (37, 256, 392, False), (3, 128, 264, True), (130, 3200, 8640, False)])
+@pytest.mark.parametrize("m,d,f,bf16", [(256, 2560, 6912, True), (37, 256, 392, False), (3, 128, 264, True), (130, 3200, 8640, False),
+                                        (160, 256, 4224, False), (160, 4224, 512, False)])   # k-split down / k-split gate|up (GLU)
 def test_ffn_block_parity(m, d, f, bf16):
     B, R = _mods()
     print("ffn_block_forward", m, d, f, flush=True)
