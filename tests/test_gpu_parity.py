@@ -99,8 +99,9 @@ def _run_bitlinear(B, R, pl, X, residual=None, taps=True):
     (16, 2048, 2048),     # single-layer config
     (1, 6912, 2560), (1, 2560, 6912), (2, 2560, 6912), (3, 200, 264), (4, 6912, 2560),   # GEMV path
     (5, 96, 128), (33, 200, 264), (64, 2560, 2560), (100, 640, 2560), (300, 1000, 520),
-    (256, 6912, 2560), (257, 2560, 6912), (1100, 3200, 3200),   # the second: few tiles, long k -> a k-split launch
-    (200, 1000, 4608), (700, 264, 6912),                         # k-split with a ragged last column block
+    (256, 6912, 2560), (257, 2560, 6912), (1100, 3200, 3200),
+    (600, 2560, 6912), (1300, 1000, 4608),                       # few 128 x 128 tiles, long k: k-split launches (ragged N in the second)
+    (200, 1000, 4608), (700, 264, 6912),                         # 64 x 32 tiles, k split inside the workgroup
     (2050, 8192, 264), (2048, 8200, 128),      # enough tiles for the 8-wavefront kernel, ragged edges
 ])
 def test_bitlinear_forward_parity(m, n, k):
