@@ -13,7 +13,7 @@
 // in LDS and writes the tile out in full 128-byte runs.  The workgroups are
 // persistent and request the rows of their next tokens before working on the
 // current ones, so that HBM stays busy through the reductions and the write-out.
-// With at most 256 tokens the time is latency, not bandwidth: act_quant_row_kernel takes one
+// With at most 1024 tokens the time is latency, not bandwidth: act_quant_row_kernel takes one
 // token per workgroup instead.
 #include "common.hpp"
 
@@ -351,10 +351,10 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     a.M = in.M; a.K = in.K; a.Kp = round_up(in.K, SBK); a.nsb = a.Kp / SBK;
     a.q_tiled = out.q; a.absmax = out.absmax; a.dscale = out.dscale; a.sumq = out.sumq;
     a.xq_rowmajor = in.xq_rowmajor; a.absmax_tap = in.absmax_tap;
-    // Up to 256 tokens: one workgroup per token (latency bound).  Beyond: persistent workgroups; their
+    // Up to 1024 tokens: one workgroup per token (latency bound).  Beyond: persistent workgroups; their
     // registers hold the current and the next row share of a lane, at most 2 x 9 float4.
     LaunchTimer tm(BRL_KC_ACT_QUANT, s);
-    const bool rows = in.M <= 256;
+    const bool rows = in.M <= 1024;      // measured crossover: about 1500 tokens at both layer widths
     int rc;
     if (a.Kp > MAX_K) {
         set_error("act_quant: K = %d exceeds the supported %d", in.K, MAX_K);
