@@ -699,7 +699,14 @@ int encoder_forward_packed(const brl_encoder* enc, const int32_t* ids, const int
         sm.cu = cu_seqlens;
         sm.b0 = b0;
         const int Mt = cu_seqlens_host[b1] - cu_seqlens_host[b0];
-        if (int rc = run_encoder_microbatch(enc, L, base, ids + cu_seqlens_host[b0], b1 - b0, Mt, max_len, rows_cap, sm,
+        // the longest state of this micro-batch bounds its attention (states of at most 32 tokens take the
+        // one-kernel path whatever max_len says); results do not depend on the bound
+        int longest = 1;
+        for (int b = b0; b < b1; ++b) {
+            const int n = cu_seqlens_host[b + 1] - cu_seqlens_host[b];
+            if (n > longest) longest = n;
+        }
+        if (int rc = run_encoder_microbatch(enc, L, base, ids + cu_seqlens_host[b0], b1 - b0, Mt, longest, rows_cap, sm,
                                             nullptr, h + (size_t)b0 * enc->d, s))
             return rc;
         b0 = b1;

@@ -32,7 +32,9 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr long DIRECT_MAX_WGS = 640;
+constexpr long DIRECT_MAX_WGS = 640;          // 64 x 32 tiles, 8 wavefronts
+constexpr long DIRECT16_MAX_WGS = 512;        // 32 x 32 tiles, 16 wavefronts
+constexpr long DIRECT16_MAX_WGS_GLU = 900;    // 32 x 32 output tiles of the GLU form, 8 wavefronts
 
 struct GemmArgs {
     const uint4* A;          // tiled activations, 16 bytes per lane per fragment
@@ -801,6 +803,25 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     for (int i = 0; i < w.count; ++i)
         if ((w.n_end[i] - (i ? w.n_end[i - 1] : 0)) % 32 != 0) g.fast_epilogue = 0;
     (void)N;
+    // Tile choice: k-split wavefronts for skinny (few-token) problems, where weight
+    // streaming bounds the time; LDS-staged big tiles once the grid fills the chip.
+    // (up to 16 wavefronts split k for one or two token blocks: the chain of dependent loads per
+    // wavefront is what a short state waits for)
+    if (w.w8) {
+        // int8 weights: LDS-staged tiles at every size
+    } else if (glu) {   // a wavefront needs the gate and the up block of a column pair: even TN only
+        if (g.nmb <= 1 || (long)g.nmb * (g.nnb / 2) <= DIRECT16_MAX_WGS_GLU) return launch_direct<1, 2, 1, 1, 8>(g, s);
+        if (g.nmb <= 2) return launch_direct<2, 2, 1, 1, 4>(g, s);
+    } else {
+        // Measured at the 2B layer shapes: one 32-row block per workgroup with k over 16 wavefronts wins
+        // while that makes at most ~500 workgroups (M <= 128 ... 192); then 64 x 32 tiles with k over 8
+        // wavefronts up to ~640 workgroups (M <= ~400 at N = 2560), 1.5 to 3 times faster there than one
+        // 128 x 128 tile per compute unit on a fraction of the chip - also with a long k, where they beat
+        // the k-split tile launch below.
+        if (g.nmb <= 1 || (long)g.nmb * g.nnb <= DIRECT16_MAX_WGS) return launch_direct<1, 1, 1, 1, 16>(g, s);
+        if (g.nmb <= 2 || (long)((g.nmb + 1) / 2) * g.nnb <= DIRECT_MAX_WGS) return launch_direct<2, 1, 1, 1, 8>(g, s);
+        if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
+    }
     // Few 128 x 128 tiles and a long k (a few hundred tokens, or a narrow output): k is cut so that about
     // two workgroups per compute unit run; the partial tiles go through the scratch area of the
     // activation buffer and a second small kernel.  Integer partial sums: the result is the same.
@@ -826,21 +847,6 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     }
     // int8 weights: the LDS-staged 128 x 128 tile at every size (32 KB per stage)
     if (w.w8) return launch_lds<2, 2, 2, 2, true>(g, s);
-    // Tile choice: k-split wavefronts for skinny (few-token) problems, where weight
-    // streaming bounds the time; LDS-staged big tiles once the grid fills the chip.
-    // (up to 16 wavefronts split k for one or two token blocks: the chain of dependent loads per
-    // wavefront is what a short state waits for)
-    if (glu) {   // a wavefront needs the gate and the up block of a column pair: even TN only
-        if (g.nmb <= 1) return launch_direct<1, 2, 1, 1, 8>(g, s);
-        if (g.nmb <= 2) return launch_direct<2, 2, 1, 1, 4>(g, s);
-    } else {
-        if (g.nmb <= 1) return launch_direct<1, 1, 1, 1, 16>(g, s);
-        // 64 x 32 tiles with k split over 8 wavefronts while they make at most DIRECT_MAX_WGS workgroups
-        // (a few hundred tokens): measured 1.5 to 3 times faster there than one 128 x 128 tile per
-        // compute unit on a fraction of the chip
-        if (g.nmb <= 2 || (long)((g.nmb + 1) / 2) * g.nnb <= DIRECT_MAX_WGS) return launch_direct<2, 1, 1, 1, 8>(g, s);
-        if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
-    }
     // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64, two workgroups per CU) or 128 x 128 tiles
     // (4 wavefronts, four per CU).  The wide tile does about 5 % more work per unit time; the narrow
     // one wins when it spreads the tiles more evenly over the compute units.
