@@ -422,47 +422,51 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(GemmArgs g) {
 template <int TM, int TN, int WM, int WN, bool W8>
 struct LdsTile {
     static constexpr int NW = WM * WN;
-    static constexpr int AFR = WM * TM * 4;           // 1 KB activation fragments per stage
-    static constexpr int BFR = WN * TN * (W8 ? 4 : 1);   // 1 KB pieces of weights per stage: a packed 2-bit block, or
-                                                      // the four k-step fragments of an int8 block
+    // k-steps (of 32) per stage: a whole super-block for the 2-bit weights; half of one for int8
+    // weights, whose stage would otherwise be 32 KB and leave two wavefronts per SIMD
+    static constexpr int KD = W8 ? 2 : 4;
+    static constexpr int SPB = 4 / KD;                // stages per super-block
+    static constexpr int AFR = WM * TM * KD;          // 1 KB activation fragments per stage
+    static constexpr int BFR = WN * TN * (W8 ? KD : 1);   // 1 KB pieces of weights per stage: a packed 2-bit block, or
+                                                      // the k-step fragments of an int8 block
     static constexpr int STAGE = (AFR + BFR) * 64;    // uint4 elements per stage
     static constexpr int APW = (AFR + NW - 1) / NW, BPW = (BFR + NW - 1) / NW;   // pieces copied per wavefront
 
-    // Request super-block sb of this wavefront's share of a stage: piece c of
-    // wavefront w is fragment c*NW + w (lane i's 16 bytes land at offset 16 i).
-    static __device__ inline void issue(const uint4* const (&asrc)[APW], const uint4* const (&bsrc)[BPW], int sb,
+    // Request stage t (k-steps t * KD ...) of this wavefront's share: piece c of wavefront w is
+    // fragment c*NW + w (lane i's 16 bytes land at offset 16 i).
+    static __device__ inline void issue(const uint4* const (&asrc)[APW], const uint4* const (&bsrc)[BPW], int t,
                                         uint4* st, int wave) {
 #pragma unroll
         for (int c = 0; c < APW; ++c)
             if (AFR % NW == 0 || c * NW + wave < AFR)
-                __builtin_amdgcn_global_load_lds(asrc[c] + (size_t)sb * 256, st + (c * NW + wave) * 64, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(asrc[c] + (size_t)t * (KD * 64), st + (c * NW + wave) * 64, 16, 0, 0);
 #pragma unroll
         for (int c = 0; c < BPW; ++c)
             if (BFR % NW == 0 || c * NW + wave < BFR)
-                __builtin_amdgcn_global_load_lds(bsrc[c] + (size_t)sb * (W8 ? 256 : 64), st + (AFR + c * NW + wave) * 64,
+                __builtin_amdgcn_global_load_lds(bsrc[c] + (size_t)t * (W8 ? KD * 64 : 64), st + (AFR + c * NW + wave) * 64,
                                                  16, 0, 0);
     }
 
-    // One super-block (128 k) of MFMAs from one stage.  Activation fragments
-    // are requested from LDS two uses before the MFMAs that consume them.
+    // The MFMAs of one stage.  Activation fragments are requested from LDS two uses before the
+    // MFMAs that consume them.
     static __device__ inline void compute(v16i (&acc)[TM][TN], const uint4* st, int wm, int wn, int lane) {
-        const uint4* sa = st + (wm * TM * 4) * 64 + lane;
-        const uint4* sbp = st + (AFR + wn * TN * (W8 ? 4 : 1)) * 64 + lane;
+        const uint4* sa = st + (wm * TM * KD) * 64 + lane;
+        const uint4* sbp = st + (AFR + wn * TN * (W8 ? KD : 1)) * 64 + lane;
         uint4 bq[W8 ? 1 : TN];
         if constexpr (!W8) {
 #pragma unroll
             for (int j = 0; j < TN; ++j) bq[j] = sbp[j * 64];
         }
-        constexpr int NF = 4 * TM;
+        constexpr int NF = KD * TM;
         uint4 fr[NF];
         fr[0] = sa[0];
-        if (NF > 1) fr[1] = sa[(TM > 1 ? 4 : 1) * 64];
+        if (NF > 1) fr[1] = sa[(TM > 1 ? KD : 1) * 64];
 #pragma unroll
-        for (int dd = 0; dd < 4; ++dd) {
+        for (int dd = 0; dd < KD; ++dd) {
             v4i bf[TN];
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                if constexpr (W8) bf[j] = as_v4i(sbp[(j * 4 + dd) * 64]);
+                if constexpr (W8) bf[j] = as_v4i(sbp[(j * KD + dd) * 64]);
                 else bf[j] = expand_codes(pick(bq[j], dd));
             }
 #pragma unroll
@@ -470,7 +474,7 @@ struct LdsTile {
                 const int g = dd * TM + i;                       // use index of this fragment
                 if (g + 2 < NF) {
                     const int g2 = g + 2, dd2 = g2 / TM, i2 = g2 % TM;
-                    fr[g2] = sa[(i2 * 4 + dd2) * 64];
+                    fr[g2] = sa[(i2 * KD + dd2) * 64];
                 }
                 const v4i af = as_v4i(fr[g]);
 #pragma unroll
@@ -503,17 +507,17 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     const uint4* asrc[Tile::APW];
 #pragma unroll
     for (int c = 0; c < Tile::APW; ++c) {
-        const int f = c * NW + wave;                              // fragment = (token block, k-step)
-        const int mb = min(mb_tile0 + (f >> 2), g.nmb - 1);
-        asrc[c] = g.A + ((size_t)mb * g.nsb * 4 + (f & 3)) * 64 + lane;
+        const int f = c * NW + wave;                              // fragment = (token block, k-step of the stage)
+        const int mb = min(mb_tile0 + f / Tile::KD, g.nmb - 1);
+        asrc[c] = g.A + ((size_t)mb * g.nsb * 4 + f % Tile::KD) * 64 + lane;
     }
     const uint4* bsrc[Tile::BPW];
 #pragma unroll
     for (int c = 0; c < Tile::BPW; ++c) {
         const int piece = c * NW + wave;
         BCols<1> one;
-        one.init(g, nb_tile0 + (W8 ? piece >> 2 : piece), lane);
-        bsrc[c] = one.ptr[0] + (W8 ? (piece & 3) * 64 : 0);
+        one.init(g, nb_tile0 + (W8 ? piece / Tile::KD : piece), lane);
+        bsrc[c] = one.ptr[0] + (W8 ? (piece % Tile::KD) * 64 : 0);
     }
 
     float beta[TN];
@@ -535,8 +539,9 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     // Double buffering with two distinct LDS objects: while one is read, the
     // other is filled.  A stage requested in one step is waited for (vmcnt 0)
     // at the top of the next, so its latency hides behind 4*TM*TN MFMAs.
-    const int sb_first = split * g.sb_per_split;
-    const int sb_last = min(g.nsb, sb_first + g.sb_per_split);     // (one range covering all of k when splits == 1)
+    // stages of this workgroup's k range (one range covering all of k when splits == 1)
+    const int sb_first = split * g.sb_per_split * Tile::SPB;
+    const int sb_last = min(g.nsb, (split + 1) * g.sb_per_split) * Tile::SPB;
     Tile::issue(asrc, bsrc, sb_first, stage0, wave);
     int sb = sb_first;
     for (; sb + 1 < sb_last; sb += 2) {
