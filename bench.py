@@ -34,8 +34,8 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by what
 # the same counters read for a copy kernel of known size); null until measured for the kernel as it stands.
-# encoder-2b: (76 444 KiB FETCH_SIZE x 2.0 + 172 032 KiB WRITE_SIZE x 1.0) per launch of gemm_lds_kernel<2,2,2,4>.
-ROOFLINE_TRAFFIC = {"encoder-2b": 332.7e6, "prefill-3b": None, "rl-states-2b": None}
+# encoder-2b: (75 742 KiB FETCH_SIZE x 2.0 + 172 032 KiB WRITE_SIZE x 1.0) per launch of gemm_lds_kernel<2,2,2,4>.
+ROOFLINE_TRAFFIC = {"encoder-2b": 331.3e6, "prefill-3b": None, "rl-states-2b": None}
 # decode pair walk, 16 pairs per launch pair: 35 532.5 KiB FETCH_SIZE x 2.0 per launch against 71.2 MB of
 # packed weights per launch: the batched GEMV fetches 1.02 x its algorithmic bytes (scaled to the pool in use)
 GEMV_BATCH_FETCH_RATIO = 1.022
