@@ -125,6 +125,36 @@ def test_bitlinear_forward_parity(m, n, k):
         assert np.all(y.cpu().numpy()[1] == 0)
 
 
+def test_bitlinear_forward_shape_sweep():
+    """Seeded random shapes across the dispatch boundaries (1-4 token path, 16- and 8-wavefront k-split tiles,
+    k-split tile launches, narrow and wide LDS tiles): integer stages exact, outputs identical, with and
+    without the taps (the two epilogue families) and with a residual."""
+    B, R = _mods()
+    rng = np.random.default_rng(20241)
+    shapes = []
+    for _ in range(28):
+        m = int(rng.choice([rng.integers(1, 9), rng.integers(9, 200), rng.integers(200, 1400)]))
+        n = int(rng.choice([rng.integers(1, 97), 32 * rng.integers(1, 130), rng.integers(97, 3000)]))
+        k = 8 * int(rng.choice([rng.integers(1, 48), rng.integers(48, 400), rng.integers(400, 1153)]))
+        shapes.append((m, n, k))
+    for idx, (m, n, k) in enumerate(shapes):
+        print("bitlinear_forward sweep", m, n, k, flush=True)
+        case = synth.bitlinear_case(1000 + idx, n, k, m)
+        codes, beta = O.ternary_quantize(case["W"])
+        taps = {}
+        y_ref = O.bitlinear_forward(case["X"], codes, beta, taps=taps)
+        pl = R.quantize_linear(case["W"])
+        x = R.dev(case["X"])
+        y, xq, am, acc, ws = _run_bitlinear(B, R, pl, x)
+        assert np.array_equal(xq.cpu().numpy(), taps["xq"]), (m, n, k)
+        assert np.array_equal(acc.cpu().numpy(), taps["acc"]), (m, n, k)
+        assert np.array_equal(y.cpu().numpy(), y_ref), (m, n, k)
+        res = synth.normal(1000 + idx, 7, (m, n))
+        y2 = R.dev(res)
+        B.bitlinear_forward(pl.packed, pl.beta, n, k, x, m, 1e-5, y2, y2, None, None, None, ws.buf)
+        assert np.array_equal(y2.cpu().numpy(), O.bitlinear_forward(case["X"], codes, beta, residual=res)), (m, n, k)
+
+
 @pytest.mark.parametrize("m", [1, 4, 48])
 def test_bitlinear_residual_bf16_and_no_taps(m):
     B, R = _mods()
