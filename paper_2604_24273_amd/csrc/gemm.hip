@@ -584,7 +584,7 @@ __global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_w8_kernel(GemmArgs g
 // ---------------------------------------------------------------------------
 // Few-token kernel: operands straight from L2 to registers; WK wavefronts split k.
 // ---------------------------------------------------------------------------
-template <int TM, int TN, int WM, int WN, int WK>
+template <int TM, int TN, int WM, int WN, int WK, bool W8 = false>
 __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs g) {
     static_assert(WM * WN * WK == 4 || WM * WN * WK == 8 || WM * WN * WK == 16, "4, 8 or 16 wavefronts per workgroup");
     const int lane = threadIdx.x & 63;
@@ -644,25 +644,35 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs
     const int sb_end = min(g.nsb, sb_begin + sb_per);
 
     if (sb_begin < sb_end) {
+        // weights of a super-block per 32-row block: one packed 16-byte piece per lane (2-bit), or the four
+        // k-step fragments themselves (int8)
+        constexpr int BW = W8 ? 4 : 1;
         uint4 aq[4][TM];
-        uint4 bq[TN];
+        uint4 bq[BW][TN];
 #pragma unroll
         for (int dd = 0; dd < 4; ++dd)
 #pragma unroll
             for (int i = 0; i < TM; ++i) aq[dd][i] = aptr[i][((size_t)sb_begin * 4 + dd) * 64];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bq[j] = bc.ptr[j][(size_t)sb_begin * 64];
+        for (int q = 0; q < BW; ++q)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bq[q][j] = bc.ptr[j][((size_t)sb_begin * BW + q) * 64];
 
         for (int sb = sb_begin; sb < sb_end; ++sb) {
             const int nxt = min(sb + 1, sb_end - 1);
-            uint4 bnext[TN];
+            uint4 bnext[BW][TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bnext[j] = bc.ptr[j][(size_t)nxt * 64];
+            for (int q = 0; q < BW; ++q)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bnext[q][j] = bc.ptr[j][((size_t)nxt * BW + q) * 64];
 #pragma unroll
             for (int dd = 0; dd < 4; ++dd) {
                 v4i bf[TN];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bf[j] = expand_codes(pick(bq[j], dd));
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (W8) bf[j] = as_v4i(bq[dd][j]);
+                    else bf[j] = expand_codes(pick(bq[0][j], dd));
+                }
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
                     const v4i af = as_v4i(aq[dd][i]);
@@ -675,7 +685,9 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs
                 for (int i = 0; i < TM; ++i) aq[dd][i] = aptr[i][((size_t)nxt * 4 + dd) * 64];
             }
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bq[j] = bnext[j];
+            for (int q = 0; q < BW; ++q)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bq[q][j] = bnext[q][j];
         }
     }
 
@@ -735,14 +747,17 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs
 }
 
 template <int TM, int TN, int WM, int WN, int WK>
-int launch_direct(GemmArgs& g, hipStream_t s) {
+int launch_direct(GemmArgs& g, hipStream_t s, bool w8 = false) {
     g.tiles_m = (g.nmb + WM * TM - 1) / (WM * TM);
     g.tiles_n = (g.nnb + WN * TN - 1) / (WN * TN);
     g.group_m = 4;
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 7) / 8) * 8;
     LaunchTimer tm(BRL_KC_GEMM_NARROW, s, g.ops);
-    hipLaunchKernelGGL((gemm_direct_kernel<TM, TN, WM, WN, WK>), dim3(grid), dim3(WM * WN * WK * 64), 0, s, g);
+    if (w8)
+        hipLaunchKernelGGL((gemm_direct_kernel<TM, TN, WM, WN, WK, true>), dim3(grid), dim3(WM * WN * WK * 64), 0, s, g);
+    else
+        hipLaunchKernelGGL((gemm_direct_kernel<TM, TN, WM, WN, WK, false>), dim3(grid), dim3(WM * WN * WK * 64), 0, s, g);
     BRL_LAUNCH_CHECK("gemm_direct_kernel");
     return BRL_OK;
 }
@@ -812,20 +827,20 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     // streaming bounds the time; LDS-staged big tiles once the grid fills the chip.
     // (up to 16 wavefronts split k for one or two token blocks: the chain of dependent loads per
     // wavefront is what a short state waits for)
-    if (w.w8) {
-        // int8 weights: LDS-staged tiles at every size
-    } else if (glu) {   // a wavefront needs the gate and the up block of a column pair: even TN only
-        if (g.nmb <= 1 || (long)g.nmb * (g.nnb / 2) <= DIRECT16_MAX_WGS_GLU) return launch_direct<1, 2, 1, 1, 8>(g, s);
-        if (g.nmb <= 2) return launch_direct<2, 2, 1, 1, 4>(g, s);
+    const bool w8 = w.w8 != 0;
+    if (glu) {   // a wavefront needs the gate and the up block of a column pair: even TN only
+        if (g.nmb <= 1 || (long)g.nmb * (g.nnb / 2) <= DIRECT16_MAX_WGS_GLU) return launch_direct<1, 2, 1, 1, 8>(g, s, w8);
+        if (g.nmb <= 2) return launch_direct<2, 2, 1, 1, 4>(g, s, w8);
     } else {
         // Measured at the 2B layer shapes: one 32-row block per workgroup with k over 16 wavefronts wins
         // while that makes at most ~500 workgroups (M <= 128 ... 192); then 64 x 32 tiles with k over 8
         // wavefronts up to ~640 workgroups (M <= ~400 at N = 2560), 1.5 to 3 times faster there than one
         // 128 x 128 tile per compute unit on a fraction of the chip - also with a long k, where they beat
-        // the k-split tile launch below.
-        if (g.nmb <= 1 || (long)g.nmb * g.nnb <= DIRECT16_MAX_WGS) return launch_direct<1, 1, 1, 1, 16>(g, s);
-        if (g.nmb <= 2 || (long)((g.nmb + 1) / 2) * g.nnb <= DIRECT_MAX_WGS) return launch_direct<2, 1, 1, 1, 8>(g, s);
-        if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s);
+        // the k-split tile launch below.  (The limits were measured with 2-bit weights and are applied to
+        // int8 weights as they are.)
+        if (g.nmb <= 1 || (long)g.nmb * g.nnb <= DIRECT16_MAX_WGS) return launch_direct<1, 1, 1, 1, 16>(g, s, w8);
+        if (g.nmb <= 2 || (long)((g.nmb + 1) / 2) * g.nnb <= DIRECT_MAX_WGS) return launch_direct<2, 1, 1, 1, 8>(g, s, w8);
+        if (g.nmb <= 4) return launch_direct<2, 1, 2, 2, 1>(g, s, w8);
     }
     // Few 128 x 128 tiles and a long k (a few hundred tokens, or a narrow output): k is cut so that about
     // two workgroups per compute unit run; the partial tiles go through the scratch area of the
@@ -850,7 +865,7 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
             }
         }
     }
-    // int8 weights: the LDS-staged 128 x 128 tile at every size (32 KB per stage)
+    // int8 weights: the LDS-staged 128 x 128 tile (16 KB per stage)
     if (w.w8) return launch_lds<2, 2, 2, 2, true>(g, s);
     // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64, two workgroups per CU) or 128 x 128 tiles
     // (4 wavefronts, four per CU).  The wide tile does about 5 % more work per unit time; the narrow
