@@ -15,14 +15,20 @@
 // Int8 weights (the higher-precision critic variant) come in the activations' own
 // fragment layout and feed the MFMA as they are: no expansion, no offset correction.
 //
-// Two kernels:
+// Kernels:
 //   gemm_lds_kernel    many tokens: both operand tiles of a workgroup (128 tokens
 //                      x 128 k, and 256 or 128 weight rows x 128 k still packed)
 //                      are staged in LDS with direct global->LDS loads, double
 //                      buffered; in GLU mode the epilogue writes
 //                      h = max(G,0)^2 U from interleaved gate / up blocks.
-//   gemm_direct_kernel few tokens (weight streaming bound): no LDS staging, the
-//                      4 to 16 wavefronts of a workgroup may split k.
+//                      gemm_lds_w8_kernel is the same loop on int8 weight blobs.
+//                      With few tiles and a long k several workgroups share a
+//                      tile, each on its own k range (raw int32 partial tiles,
+//                      splitk_epilogue_kernel sums and rescales them).
+//   gemm_direct_kernel up to a few hundred tokens: no LDS staging, the 4 to 16
+//                      wavefronts of a workgroup split k and finish the tile
+//                      together through LDS.
+// launch_gemm picks among them by how many workgroups each would make.
 #include "common.hpp"
 
 namespace brl {
