@@ -351,10 +351,71 @@ def bench_single_state(torch, B, R, synth, np, enc, head, shape, n_tokens: int =
         graph_ms = (time.perf_counter() - t0) / calls * 1e3
     except Exception as e:                      # capture is an extra; the eager figure stands on its own
         graph_ms, same = None, "capture failed: %s" % (str(e)[:120],)
-    return {"tokens": n_tokens, "calls": calls, "launch_per_kernel_ms_per_state": round(eager_ms, 4),
-            "hip_graph_replay_ms_per_state": None if graph_ms is None else round(graph_ms, 4),
-            "graph_replays_match_eager": same,
-            "states_per_s_one_at_a_time": round(1e3 / (graph_ms if graph_ms else eager_ms), 1)}
+    out = {"tokens": n_tokens, "calls": calls, "launch_per_kernel_ms_per_state": round(eager_ms, 4),
+           "hip_graph_replay_ms_per_state": None if graph_ms is None else round(graph_ms, 4),
+           "graph_replays_match_eager": same,
+           "states_per_s_one_at_a_time": round(1e3 / (graph_ms if graph_ms else eager_ms), 1)}
+    if graph_ms is not None:
+        try:
+            out["independent_agents"] = _concurrent_agents(torch, B, R, synth, np, enc, head, shape)
+        except Exception as e:
+            out["independent_agents"] = "failed: %s" % (str(e)[:120],)
+    return out
+
+
+def _concurrent_agents(torch, B, R, synth, np, enc, head, shape, n_agents: int = 8, rounds: int = 30):
+    """n_agents independent callers, each with its own short state, buffers, stream (default priority) and captured
+    graph of encoder_forward_packed + heads; every round replays all graphs, one per stream.  The library keeps no
+    state between calls, so the replays may overlap on the GPU: one short state leaves most of it idle."""
+    agents = []
+    for a in range(n_agents):
+        n = 15 + (a * 7) % 26                    # 15 .. 40 tokens
+        ids = R.dev(synth.token_ids(0, 520 + a, (n,), shape.vocab))
+        cu_host = np.asarray([0, n], dtype=np.int32)
+        ag = {"n": n, "ids": ids, "cu_host": cu_host, "cu_dev": R.dev(cu_host),
+              "ws": R.Workspace(B.brl_encoder_packed_workspace_bytes(enc.struct, 1, n, n)),
+              "hws": R.Workspace(B.brl_head_workspace_bytes(head.struct, 1)),
+              "h": torch.empty((1, shape.d), dtype=torch.float32, device="cuda"),
+              "logits": torch.empty((1, head.n_actions), dtype=torch.float32, device="cuda"),
+              "value": torch.empty((1,), dtype=torch.float32, device="cuda"),
+              "stream": torch.cuda.Stream()}
+
+        def call(ag=ag):
+            B.encoder_forward_packed(enc.struct, ag["ids"], ag["cu_dev"], ag["cu_host"], 1, ag["n"], ag["h"], ag["ws"].buf)
+            B.policy_value_head(head.struct, ag["h"], 1, ag["logits"], ag["value"], ag["hws"].buf)
+
+        call()
+        torch.cuda.synchronize()
+        ag["ref"] = ag["h"].clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            call()
+        ag["graph"] = g
+        agents.append(ag)
+    main = torch.cuda.current_stream()
+
+    def one_round():
+        for ag in agents:
+            ag["stream"].wait_stream(main)
+            with torch.cuda.stream(ag["stream"]):
+                ag["graph"].replay()
+        for ag in agents:
+            main.wait_stream(ag["stream"])
+
+    same = True
+    for _ in range(3):
+        for ag in agents:
+            ag["h"].zero_()
+        one_round()
+        torch.cuda.synchronize()
+        same = same and all(bool(torch.equal(ag["h"], ag["ref"])) for ag in agents)
+    t0 = time.perf_counter()
+    for _ in range(rounds):
+        one_round()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / rounds * 1e3
+    return {"agents": n_agents, "tokens_per_state": [ag["n"] for ag in agents], "ms_per_round": round(ms, 4),
+            "states_per_s": round(n_agents / ms * 1e3, 1), "each_matches_its_own_call": same}
 
 
 def bench_critics(torch, B, R, synth, enc, ids, Bn: int, S: int, shape, steps: int, warmup: int):
