@@ -16,7 +16,8 @@ Readings taken here (also listed in the design document):
   the per-token activation quantiser: a' = max(max|W|, eps); s = 127 / a' (fp32 divide);
   code = clamp(round_half_even(W * s), -127, 127); dequantisation scale a' / 127.
   Activations, accumulation and the rescale are those of the ternary BitLinear
-  (W8A8, int32 accumulation, y = (float(acc) * (a_t / 127)) * scale).
+  (W8A8, int32 accumulation, y = (float(acc) * (a_t / 127)) * scale).  The table's
+  "INT4 critic" is taken as the same quantiser on the grid -7..7 (qmax = 7).
 * ensemble: n value heads of identical shape read the same h_t; each member's value is the
   fp32 head output, and the ensemble value is their arithmetic mean (summed in member order
   in fp64, divided by n, rounded to fp32 once).
@@ -38,11 +39,15 @@ F64 = np.float64
 QB = 127
 
 
-def int8_quantize(W: np.ndarray, eps: float = 1e-5) -> Tuple[np.ndarray, np.float32]:
-    """Per-tensor absmax int8 code of W[N, K] (Sec. 5.4, hybrid-precision critic; reading above).
+def int8_quantize(W: np.ndarray, eps: float = 1e-5, qmax: int = QB) -> Tuple[np.ndarray, np.float32]:
+    """Per-tensor absmax integer code of W[N, K] (Sec. 5.4, hybrid-precision critic; reading above).
 
-    Returns (codes int8 [N, K] in [-127, 127], scale float32 = a' / 127).
+    qmax = 127 is the int8 critic; qmax = 7 is the grid of the table's int4 critic (codes in
+    [-7, 7], here still one code per int8 element: the definition does not depend on storage).
+    Returns (codes int8 [N, K] in [-qmax, qmax], scale float32 = a' / qmax).
     """
+    if not 1 <= int(qmax) <= QB:
+        raise ValueError("qmax must be in 1..127")
     W = np.asarray(W, dtype=F32)
     if W.ndim != 2:
         raise ValueError("W must be [N, K]")
@@ -50,10 +55,10 @@ def int8_quantize(W: np.ndarray, eps: float = 1e-5) -> Tuple[np.ndarray, np.floa
     if not np.isfinite(a):
         raise ValueError("non-finite weights")
     a_c = np.maximum(F32(a), F32(eps)).astype(F32)
-    s = F32(F32(QB) / a_c)
+    s = F32(F32(qmax) / a_c)
     t = (W * s).astype(F32)
-    codes = np.clip(np.rint(t), -QB, QB).astype(np.int8)
-    scale = F32(a_c / F32(QB))
+    codes = np.clip(np.rint(t), -qmax, qmax).astype(np.int8)
+    scale = F32(a_c / F32(qmax))
     return codes, scale
 
 
@@ -67,8 +72,8 @@ class Int8Linear:
     beta: np.float32
 
     @staticmethod
-    def from_fp32(W: np.ndarray, eps: float = 1e-5) -> "Int8Linear":
-        c, s = int8_quantize(W, eps)
+    def from_fp32(W: np.ndarray, eps: float = 1e-5, qmax: int = QB) -> "Int8Linear":
+        c, s = int8_quantize(W, eps, qmax)
         return Int8Linear(c, s)
 
 

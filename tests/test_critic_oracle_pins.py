@@ -186,6 +186,32 @@ def test_linear_members_average_like_their_parameters():
     assert np.abs(mean - ref[:, 0]).max() <= 5e-7 * np.abs(ref).max() + 1e-7
 
 
+def test_int4_grid_hand_case_and_bounds():
+    # max 1 -> s = 7: 0.5 -> 3.5 -> 4 (even), 0.25 -> 1.75 -> 2, -0.75 -> -5.25 -> -5, 0.0714 -> 0.4998 -> 0
+    W = np.array([[1.0, -0.5, 0.25, 0.0], [0.5, -0.75, -1.0, 0.0714]], dtype=F32)
+    codes, s = C.int8_quantize(W, qmax=7)
+    assert codes.tolist() == [[7, -4, 2, 0], [4, -5, -7, 0]]
+    assert abs(float(s) - 1.0 / 7.0) <= 1e-8
+    rng = np.random.default_rng(11)
+    W = (rng.standard_normal((30, 50)) * 0.02).astype(F32)
+    c7, s7 = C.int8_quantize(W, qmax=7)
+    assert c7.min() >= -7 and c7.max() <= 7 and np.abs(c7).max() == 7
+    a = float(np.abs(W).max())
+    assert np.abs(c7.astype(np.float64) * float(s7) - W).max() <= a / 14.0 * (1 + 1e-5)
+    # an integer matrix with max 7 is reproduced exactly, and the coarser grid is coarser
+    Wi = rng.integers(-7, 8, size=(6, 9)).astype(F32); Wi[0, 0] = 7
+    ci, si = C.int8_quantize(Wi, qmax=7)
+    assert np.array_equal(ci.astype(F32), Wi) and si == F32(1.0)
+    c127, s127 = C.int8_quantize(W)
+    e7 = np.abs(c7.astype(np.float64) * float(s7) - W).mean()
+    e127 = np.abs(c127.astype(np.float64) * float(s127) - W).mean()
+    assert e7 > 10 * e127
+    with pytest.raises(ValueError):
+        C.int8_quantize(W, qmax=0)
+    with pytest.raises(ValueError):
+        C.int8_quantize(W, qmax=128)
+
+
 def test_errors():
     with pytest.raises(ValueError):
         C.value_ensemble(np.zeros((2, 4), F32), [])
