@@ -127,8 +127,11 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K,
  * the configuration, the quantiser below is this library's reading of it).
  *
  * Weights, one scale per matrix, the mirror of the per-token activation
- * quantiser: a = max(max|W|, eps); s = 127 / a (fp32 divide); code =
- * clamp(rne(w * s), -127, 127); scale = a / 127.  Forward: per-token int8
+ * quantiser: a = max(max|W|, eps); s = qmax / a (fp32 divide); code =
+ * clamp(rne(w * s), -qmax, qmax); scale = a / qmax.  qmax = 127 is the int8
+ * critic; qmax = 7 gives the grid of the table's "INT4 critic" (1 <= qmax <=
+ * 127; the codes are stored one per byte whatever qmax is, so this reproduces
+ * the int4 critic's arithmetic, not its memory footprint).  Forward: per-token int8
  * activations exactly as in bitlinear_forward, acc = sum_k q code (int32,
  * exact), y = (float(acc) * (a_t / 127)) * scale (+ residual).
  *
@@ -142,7 +145,7 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K,
  * An encoder with weight_format = BRL_W_INT8 uses such blobs in every layer.
  * ------------------------------------------------------------------------ */
 size_t brl_packed_int8_bytes(int n_out, int k_in);
-int bitlinear_quantize_weights_int8(const float* W, int n_out, int k_in, float eps,
+int bitlinear_quantize_weights_int8(const float* W, int n_out, int k_in, float eps, int qmax,
                                     void* packed_out, float* scale_out, int8_t* codes_dbg,
                                     void* workspace /* brl_quantize_workspace_bytes */, size_t ws_bytes, void* stream);
 int brl_unpack_codes_int8(const void* packed, int n_out, int k_in, int8_t* codes_out, void* stream);

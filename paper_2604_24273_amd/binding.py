@@ -89,7 +89,7 @@ _SIGNATURES = {
     "bitlinear_forward": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "brl_packed_int8_bytes": (c_size_t, [c_int, c_int]),
-    "bitlinear_quantize_weights_int8": (c_int, [c_void_p, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p,
+    "bitlinear_quantize_weights_int8": (c_int, [c_void_p, c_int, c_int, c_float, c_int, c_void_p, c_void_p, c_void_p,
                                                 c_void_p, c_size_t, c_void_p]),
     "brl_unpack_codes_int8": (c_int, [c_void_p, c_int, c_int, c_void_p, c_void_p]),
     "bitlinear_int8_forward": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
@@ -210,10 +210,11 @@ def brl_packed_int8_bytes(n_out: int, k_in: int) -> int:
     return lib().brl_packed_int8_bytes(n_out, k_in)
 
 
-def bitlinear_quantize_weights_int8(W: torch.Tensor, eps: float, packed_out: torch.Tensor, scale_out: torch.Tensor,
-                                    codes_dbg: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+def bitlinear_quantize_weights_int8(W: torch.Tensor, eps: float, qmax: int, packed_out: torch.Tensor,
+                                    scale_out: torch.Tensor, codes_dbg: Optional[torch.Tensor],
+                                    workspace: torch.Tensor) -> None:
     n, k = W.shape
-    _check(lib().bitlinear_quantize_weights_int8(_ptr(W), n, k, eps, _ptr(packed_out), _ptr(scale_out), _ptr(codes_dbg),
+    _check(lib().bitlinear_quantize_weights_int8(_ptr(W), n, k, eps, qmax, _ptr(packed_out), _ptr(scale_out), _ptr(codes_dbg),
                                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 

@@ -426,12 +426,13 @@ size_t brl_packed_int8_bytes(int n_out, int k_in) {
     return (size_t)round_up(n_out, NB) * (size_t)round_up(k_in, SBK);
 }
 
-int bitlinear_quantize_weights_int8(const float* W, int n_out, int k_in, float eps, void* packed_out, float* scale_out,
-                                    int8_t* codes_dbg, void* workspace, size_t ws_bytes, void* stream) {
+int bitlinear_quantize_weights_int8(const float* W, int n_out, int k_in, float eps, int qmax, void* packed_out,
+                                    float* scale_out, int8_t* codes_dbg, void* workspace, size_t ws_bytes, void* stream) {
     BRL_REQUIRE(W && packed_out && scale_out && workspace, "quantize_weights_int8: null pointer");
     BRL_REQUIRE(aligned16(W) && aligned16(packed_out) && aligned16(workspace), "quantize_weights_int8: misaligned pointer");
     BRL_REQUIRE(n_out >= 1 && k_in >= 1, "quantize_weights_int8: bad shape %d x %d", n_out, k_in);
     BRL_REQUIRE(eps > 0.f, "quantize_weights_int8: eps must be positive");
+    BRL_REQUIRE(qmax >= 1 && qmax <= 127, "quantize_weights_int8: qmax = %d out of 1..127", qmax);
     if (ws_bytes < brl_quantize_workspace_bytes(n_out, k_in)) {
         set_error("quantize_weights_int8: workspace %zu < %zu", ws_bytes, brl_quantize_workspace_bytes(n_out, k_in));
         return BRL_ENOSPC;
@@ -440,7 +441,7 @@ int bitlinear_quantize_weights_int8(const float* W, int n_out, int k_in, float e
     Carver c(workspace);
     float* partials = c.take<float>(1024);
     int* flag = c.take<int>(1);
-    if (int rc = launch_quantize_weights_int8(W, n_out, k_in, eps, static_cast<int8_t*>(packed_out), scale_out, codes_dbg,
+    if (int rc = launch_quantize_weights_int8(W, n_out, k_in, eps, qmax, static_cast<int8_t*>(packed_out), scale_out, codes_dbg,
                                               partials, flag, s))
         return rc;
     int bad = 0;

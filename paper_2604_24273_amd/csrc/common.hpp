@@ -107,7 +107,7 @@ int launch_quantize_weights(const float* W, int N, int K, float eps, uint32_t* p
 int launch_unpack_codes(const uint32_t* packed, int N, int K, int8_t* codes, hipStream_t s);
 int quantize_partials_count(int N, int K);
 // per-tensor absmax int8 weights, written in the tiled layout of tiled_act_offset (row n in place of token m)
-int launch_quantize_weights_int8(const float* W, int N, int K, float eps, int8_t* packed, float* scale,
+int launch_quantize_weights_int8(const float* W, int N, int K, float eps, int qmax, int8_t* packed, float* scale,
                                  int8_t* codes_dbg, float* partials, int* flag, hipStream_t s);
 int launch_unpack_codes_int8(const int8_t* packed, int N, int K, int8_t* codes, hipStream_t s);
 

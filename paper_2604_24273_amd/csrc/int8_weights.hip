@@ -2,7 +2,8 @@
 // (paper Sec. 5.4, hybrid-precision rows; the quantiser mirrors the per-token
 // activation quantiser on the whole matrix):
 //
-//   a = max(max |W|, eps);  s = 127 / a;  code = clamp(rne(w * s), -127, 127);  scale = a / 127
+//   a = max(max |W|, eps);  s = qmax / a;  code = clamp(rne(w * s), -qmax, qmax);  scale = a / qmax
+//   (qmax = 127: the int8 critic; qmax = 7: the grid of the int4 critic, still one code per byte)
 //
 // The codes are written in the int8 MFMA fragment layout of the activations
 // (32 rows x 128 columns = four 1 KB fragments, lane (n & 31) + 32 ((k >> 4) & 1)
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(W8_THREADS) void absmax_partials_kernel(const float
 
 // one 16-byte lane slot of the tiled layout per thread
 __global__ __launch_bounds__(W8_THREADS) void int8_pack_kernel(const float* __restrict__ W, int N, int K, int nsb,
-                                                                size_t n_slots, float eps, const float* __restrict__ partials,
+                                                                size_t n_slots, float eps, float qmax, const float* __restrict__ partials,
                                                                 int n_partials, uint4* __restrict__ packed,
                                                                 float* __restrict__ scale_out, int8_t* __restrict__ codes_dbg,
                                                                 int* __restrict__ flag) {
@@ -63,9 +64,9 @@ __global__ __launch_bounds__(W8_THREADS) void int8_pack_kernel(const float* __re
     for (int i = threadIdx.x; i < n_partials; i += W8_THREADS) m = fmaxf(m, partials[i]);
     const float a = block_max(m, lds);
     const float ac = fmaxf(a, eps);
-    const float s = 127.0f / ac;
+    const float s = qmax / ac;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        *scale_out = ac / 127.0f;
+        *scale_out = ac / qmax;
         *flag = isfinite(a) ? 0 : 1;
     }
     const size_t u = (size_t)blockIdx.x * W8_THREADS + threadIdx.x;
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(W8_THREADS) void int8_pack_kernel(const float* __re
         int code = 0;
         if (n < N && k < K) {
             const float v = W[(size_t)n * K + k];
-            code = (int)fminf(fmaxf(rintf(v * s), -127.f), 127.f);
+            code = (int)fminf(fmaxf(rintf(v * s), -qmax), qmax);
             if (codes_dbg) codes_dbg[(size_t)n * K + k] = (int8_t)code;
         }
         word[i >> 2] |= ((uint32_t)code & 0xffu) << (8 * (i & 3));
@@ -115,8 +116,8 @@ __global__ __launch_bounds__(W8_THREADS) void int8_unpack_kernel(const uint4* __
 
 }  // namespace
 
-int launch_quantize_weights_int8(const float* W, int N, int K, float eps, int8_t* packed, float* scale, int8_t* codes_dbg,
-                                 float* partials, int* flag, hipStream_t s) {
+int launch_quantize_weights_int8(const float* W, int N, int K, float eps, int qmax, int8_t* packed, float* scale,
+                                 int8_t* codes_dbg, float* partials, int* flag, hipStream_t s) {
     const size_t total = (size_t)N * (size_t)K;
     const int g = quantize_partials_count(N, K);
     size_t chunk = (total + g - 1) / g;
@@ -127,7 +128,7 @@ int launch_quantize_weights_int8(const float* W, int N, int K, float eps, int8_t
     const int nsb = round_up(K, SBK) / SBK;
     const size_t n_slots = (size_t)(round_up(N, NB) / NB) * nsb * 256;
     const size_t blocks = (n_slots + W8_THREADS - 1) / W8_THREADS;
-    hipLaunchKernelGGL(int8_pack_kernel, dim3((unsigned)blocks), dim3(W8_THREADS), 0, s, W, N, K, nsb, n_slots, eps, partials,
+    hipLaunchKernelGGL(int8_pack_kernel, dim3((unsigned)blocks), dim3(W8_THREADS), 0, s, W, N, K, nsb, n_slots, eps, (float)qmax, partials,
                        g, reinterpret_cast<uint4*>(packed), scale, codes_dbg, flag);
     BRL_LAUNCH_CHECK("int8_pack_kernel");
     return BRL_OK;

@@ -47,7 +47,7 @@ class PackedLinear:
 _qws: Optional[torch.Tensor] = None
 
 
-def quantize_linear(W, eps: float = 1e-5, want_codes: bool = False, int8: bool = False) -> PackedLinear:
+def quantize_linear(W, eps: float = 1e-5, want_codes: bool = False, int8: bool = False, qmax: int = 127) -> PackedLinear:
     """fp32 master weights (numpy or torch, host or device) -> packed ternary (or int8) weights on the GPU."""
     global _qws
     if isinstance(W, np.ndarray):
@@ -61,7 +61,7 @@ def quantize_linear(W, eps: float = 1e-5, want_codes: bool = False, int8: bool =
     if _qws is None or _qws.numel() < need:
         _qws = device_bytes(need)
     if int8:
-        B.bitlinear_quantize_weights_int8(Wd, eps, packed, beta, codes, _qws)
+        B.bitlinear_quantize_weights_int8(Wd, eps, qmax, packed, beta, codes, _qws)
     else:
         B.bitlinear_quantize_weights(Wd, eps, packed, beta, codes, _qws)
     return PackedLinear(packed, beta, n, k, codes)

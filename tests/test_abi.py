@@ -136,8 +136,10 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.encoder_forward(C.byref(enc), fake, 1, 1, None, fake, fake, 1 << 30, None) == B.BRL_EINVAL
     assert "weight_format" in err()
     assert lib.brl_packed_int8_bytes(33, 130) == 64 * 256 and lib.brl_packed_int8_bytes(0, 8) == 0
-    assert lib.bitlinear_quantize_weights_int8(fake, 4, 4, 0.0, fake, fake, None, fake, 1 << 20, None) == B.BRL_EINVAL
-    assert lib.bitlinear_quantize_weights_int8(fake, 4, 4, 1e-5, fake, fake, None, fake, 8, None) == B.BRL_ENOSPC
+    assert lib.bitlinear_quantize_weights_int8(fake, 4, 4, 0.0, 127, fake, fake, None, fake, 1 << 20, None) == B.BRL_EINVAL
+    assert lib.bitlinear_quantize_weights_int8(fake, 4, 4, 1e-5, 127, fake, fake, None, fake, 8, None) == B.BRL_ENOSPC
+    assert lib.bitlinear_quantize_weights_int8(fake, 4, 4, 1e-5, 128, fake, fake, None, fake, 1 << 20, None) == B.BRL_EINVAL
+    assert "qmax" in err()
     assert lib.bitlinear_int8_forward(fake, fake, 32, 100, fake, 0, 1, 1e-5, fake, None, None, None, None, fake, 1 << 20, None) == B.BRL_EINVAL
     assert lib.bitlinear_int8_forward(fake, fake, 32, 128, fake, 0, 64, 1e-5, fake, None, None, None, None, fake, 16, None) == B.BRL_ENOSPC
     import ctypes

@@ -54,6 +54,26 @@ def test_int8_weight_quantisation_is_bit_exact(n, k):
     assert int(pl.packed.view(torch.int8).to(torch.int64).abs().sum().item()) == int(np.abs(codes_ref.astype(np.int64)).sum())
 
 
+@pytest.mark.parametrize("qmax", [7, 1, 100])
+def test_weight_quantisation_on_other_grids(qmax):
+    """qmax = 7 is the grid of the int4 critic; the layer built on it matches the oracle like the int8 one."""
+    B, R = _mods()
+    n, k, m = 200, 520, 37
+    c = synth.bitlinear_case(8, n, k, m)
+    codes_ref, s_ref = C.int8_quantize(c["W"], qmax=qmax)
+    pl = R.quantize_linear(c["W"], want_codes=True, int8=True, qmax=qmax)
+    assert np.array_equal(pl.codes.cpu().numpy(), codes_ref) and np.float32(pl.beta.item()) == s_ref
+    assert int(pl.codes.abs().max().item()) == qmax
+    y = torch.empty((m, n), dtype=torch.float32, device="cuda")
+    acc = torch.empty((m, n), dtype=torch.int32, device="cuda")
+    ws = R.Workspace(B.brl_bitlinear_workspace_bytes(m, n, k))
+    B.bitlinear_int8_forward(pl.packed, pl.beta, n, k, R.dev(c["X"]), m, 1e-5, y, None, None, None, acc, ws.buf)
+    taps = {}
+    y_ref = C.int8_bitlinear_forward(c["X"], codes_ref, s_ref, taps=taps)
+    assert np.array_equal(acc.cpu().numpy(), taps["acc"])
+    _close(y.cpu().numpy(), y_ref)
+
+
 def test_int8_weight_quantisation_special_cases():
     B, R = _mods()
     Z = np.zeros((40, 64), np.float32)
