@@ -87,52 +87,72 @@ __global__ void gae_kernel(const float* __restrict__ rewards, const float* __res
     }
 }
 
-// out[b, o] = act(sum_i W[o, i] in(b, i) + bias[o]); a workgroup takes one output unit o for FB consecutive
-// samples (the weight row is read once for all of them); its four wavefronts take a quarter of the inputs each,
-// sum in fp64 in lane order, fold, and wavefront 0 adds the four parts in order.
+// out[b, o] = act(sum_i W[o, i] in(b, i) + bias[o]); a workgroup takes FO output units for FB consecutive
+// samples (weight rows and inputs are read once for all of them); its four wavefronts take a quarter of the
+// inputs each, sum in fp64 in lane order, fold, and the four parts are added in order.
 // in(b, i) = in64[b, i], or for the first layer the cached encoder output h[rows[b], i].
-constexpr int FB = 4;
+constexpr int FB = 4;        // samples per workgroup
+constexpr int FO = 4;        // output units per workgroup
 __global__ __launch_bounds__(256) void ppo_forward_kernel(const double* __restrict__ in64, const float* __restrict__ h,
                                                            const int32_t* __restrict__ rows, const float* __restrict__ W,
                                                            const float* __restrict__ bias, int B, int in_dim, int out_dim,
                                                            int act, int last, double* __restrict__ out) {
-    __shared__ double part[4][FB];
+    // FO output units x FB samples per workgroup: a lane's weights and inputs are each loaded once and meet
+    // in FO * FB accumulators.  Per (sample, unit) the sum is what it was with one unit per workgroup: lane-
+    // strided over a quarter of the inputs per wavefront, butterfly, the four quarters in order.
+    __shared__ double part[4][FO][FB];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int bg = (int)(blockIdx.x / out_dim), o = (int)(blockIdx.x % out_dim);
-    const float* w = W + (size_t)o * in_dim;
+    const int ogroups = (out_dim + FO - 1) / FO;
+    const int bg = (int)(blockIdx.x / ogroups), og = (int)(blockIdx.x % ogroups);
+    const float* w[FO];
+#pragma unroll
+    for (int u = 0; u < FO; ++u) w[u] = W + (size_t)min(og * FO + u, out_dim - 1) * in_dim;   // clamped duplicates are not stored
     const float* hrow[FB];
     const double* drow[FB];
 #pragma unroll
     for (int q = 0; q < FB; ++q) {
-        const int b = min(bg * FB + q, B - 1);          // a clamped duplicate is computed and not stored
+        const int b = min(bg * FB + q, B - 1);
         hrow[q] = in64 ? nullptr : h + (size_t)rows[b] * in_dim;
         drow[q] = in64 ? in64 + (size_t)b * in_dim : nullptr;
     }
     const int quarter = (in_dim + 3) / 4;
     const int i_end = min(in_dim, (wave + 1) * quarter);
-    double acc[FB];
+    double acc[FO][FB];
 #pragma unroll
-    for (int q = 0; q < FB; ++q) acc[q] = 0.0;
-#pragma unroll 4
+    for (int u = 0; u < FO; ++u)
+#pragma unroll
+        for (int q = 0; q < FB; ++q) acc[u][q] = 0.0;
+#pragma unroll 2
     for (int i = wave * quarter + lane; i < i_end; i += 64) {
-        const double wi = (double)w[i];
+        double wi[FO], xi[FB];
 #pragma unroll
-        for (int q = 0; q < FB; ++q) acc[q] += wi * (in64 ? drow[q][i] : (double)hrow[q][i]);
+        for (int u = 0; u < FO; ++u) wi[u] = (double)w[u][i];
+#pragma unroll
+        for (int q = 0; q < FB; ++q) xi[q] = in64 ? drow[q][i] : (double)hrow[q][i];
+#pragma unroll
+        for (int u = 0; u < FO; ++u)
+#pragma unroll
+            for (int q = 0; q < FB; ++q) acc[u][q] += wi[u] * xi[q];
     }
 #pragma unroll
-    for (int q = 0; q < FB; ++q) {
+    for (int u = 0; u < FO; ++u)
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) acc[q] += __shfl_xor(acc[q], off, 64);
-    }
+        for (int q = 0; q < FB; ++q) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) acc[u][q] += __shfl_xor(acc[u][q], off, 64);
+        }
     if (lane == 0) {
 #pragma unroll
-        for (int q = 0; q < FB; ++q) part[wave][q] = acc[q];
+        for (int u = 0; u < FO; ++u)
+#pragma unroll
+            for (int q = 0; q < FB; ++q) part[wave][u][q] = acc[u][q];
     }
     __syncthreads();
-    if (threadIdx.x < FB) {
-        const int q = threadIdx.x, b = bg * FB + q;
-        if (b < B) {
-            double z = ((part[0][q] + part[1][q]) + part[2][q]) + part[3][q] + (double)bias[o];
+    if (threadIdx.x < FO * FB) {
+        const int u = threadIdx.x / FB, q = threadIdx.x % FB;
+        const int b = bg * FB + q, o = og * FO + u;
+        if (b < B && o < out_dim) {
+            double z = ((part[0][u][q] + part[1][u][q]) + part[2][u][q]) + part[3][u][q] + (double)bias[o];
             if (!last) z = (act == BRL_ACT_RELU) ? fmax(z, 0.0) : tanh(z);
             out[(size_t)b * out_dim + o] = z;
         }
@@ -481,7 +501,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                 for (int l = 0; l < H.n; ++l) {
                     const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
                     double* out = reinterpret_cast<double*>(base + W.act_off[hd][l]);
-                    const size_t blocks = (size_t)((batch + FB - 1) / FB) * H.dims[l + 1];
+                    const size_t blocks = (size_t)((batch + FB - 1) / FB) * ((H.dims[l + 1] + FO - 1) / FO);
                     hipLaunchKernelGGL(ppo_forward_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in64, h, rows,
                                        params + H.w_off[l], params + H.b_off[l], batch, H.dims[l], H.dims[l + 1], cfg->act,
                                        l == H.n - 1 ? 1 : 0, out);
