@@ -19,10 +19,10 @@
 //                     apart from one exchange with lane ^ 32.  The probabilities
 //                     stay in registers and become the B operand of
 //                     O^T = V^T P^T, which again keeps one query per lane.  The
-//                     four wavefronts of a workgroup (heads of one key/value
-//                     group, or neighbouring query blocks) share each K / V
-//                     block through LDS, filled by direct global->LDS loads,
-//                     double buffered.
+//                     four wavefronts of a workgroup (the heads of one key/value
+//                     group on one query block, so all four need the same
+//                     causal range of keys) share each K / V block through LDS,
+//                     filled by direct global->LDS loads, double buffered.
 // V fragments are stored transposed with the keys of a block permuted so that
 // the 8 keys a lane's probabilities stand for are 16 contiguous bytes.
 #include "common.hpp"
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a)
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int group = a.Hq / a.Hkv;
-    const int U = group * a.NRB;                      // (head in group, query block) units of one key/value head
+    const int U = group * a.NRB;                      // (query block, head in group) units of one key/value head
     const int chunks = (U + WPG - 1) / WPG;
     // consecutive work items (the chunks of one key/value head) run on one XCD and share its L2;
     // the longest chunks of a head come first
@@ -277,13 +277,15 @@ __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a)
     const int len = seq_len(a.sm, b, a.S);
     const int nrb = (len + 31) >> 5;                  // query / key blocks this state really has
     const size_t row0 = (size_t)seq_row0(a.sm, b, a.S);
+    // unit u = (query block u / group, head u % group of the group): the wavefronts of a workgroup sit on
+    // the same query block (or neighbouring ones), so they need the same key blocks and finish together
     const int u0 = WPG * c, u1 = min(U, u0 + WPG) - 1;
-    const int kb_max = min((u0 / a.NRB != u1 / a.NRB) ? a.NRB - 1 : u1 % a.NRB, nrb - 1);
-    if (kb_max < 0 || (u0 / a.NRB == u1 / a.NRB && u0 % a.NRB >= nrb)) return;   // none of the units exists
+    if (u0 / group >= nrb) return;                    // none of the units exists in this state
+    const int kb_max = min(u1 / group, nrb - 1);
     const int u = u0 + wave;
-    const bool live = u < U && u % a.NRB < nrb;
-    const int head = j * group + (live ? u / a.NRB : 0);
-    const int qb = live ? u % a.NRB : -1;
+    const bool live = u < U && u / group < nrb;
+    const int head = j * group + (live ? u % group : 0);
+    const int qb = live ? u / group : -1;
 
     v8h qh[KS], ql[KS];
     const int qpos = qb * 32 + (lane & 31);
