@@ -497,7 +497,7 @@ def bench_ppo(torch, B, R, synth, np, shape, want_cpu: bool, T: int = 2048, batc
     steps = epochs * (T // batch)
     out = {"rollout_steps": T, "batch": batch, "epochs": epochs, "optimiser_steps": steps, "ms_per_update": round(ms, 3),
            "us_per_optimiser_step": round(ms / steps * 1e3, 2), "trainable_params": int(tr.params.numel()),
-           "kernel_launches_per_update": steps * 13, "cpu_oracle": None}
+           "kernel_launches_per_update": steps * 8, "cpu_oracle": None}
     if want_cpu:
         from oracle import ppo_oracle as P
         adv_ref, ret_ref = P.gae(c["rewards"][0], c["values"][0], c["dones"][0], c["last_value"][0], 0.99, 0.95)

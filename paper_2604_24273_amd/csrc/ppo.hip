@@ -93,17 +93,43 @@ __global__ void gae_kernel(const float* __restrict__ rewards, const float* __res
 // in(b, i) = in64[b, i], or for the first layer the cached encoder output h[rows[b], i].
 constexpr int FB = 4;        // samples per workgroup
 constexpr int FO = 4;        // output units per workgroup
-__global__ __launch_bounds__(256) void ppo_forward_kernel(const double* __restrict__ in64, const float* __restrict__ h,
-                                                           const int32_t* __restrict__ rows, const float* __restrict__ W,
-                                                           const float* __restrict__ bias, int B, int in_dim, int out_dim,
-                                                           int act, int last, double* __restrict__ out) {
+// One launch runs the same layer level of both heads (they read the same rows of h and depend on nothing of
+// each other): the workgroups of problem 0 come first, then those of problem 1.
+struct FwdProblem {
+    const double* in64;      // null: first layer, inputs are rows of h
+    const float* W;
+    const float* bias;
+    double* out;
+    int in_dim, out_dim, last;
+    unsigned blocks;
+};
+struct FwdArgs {
+    FwdProblem p[2];
+    int n;                   // 1 or 2 problems
+    const float* h;
+    const int32_t* rows;
+    int B, act;
+};
+__global__ __launch_bounds__(256) void ppo_forward_kernel(FwdArgs a) {
+    const int which = (a.n > 1 && blockIdx.x >= a.p[0].blocks) ? 1 : 0;
+    const unsigned block = blockIdx.x - (which ? a.p[0].blocks : 0u);
+    const double* __restrict__ in64 = which ? a.p[1].in64 : a.p[0].in64;
+    const float* __restrict__ W = which ? a.p[1].W : a.p[0].W;
+    const float* __restrict__ bias = which ? a.p[1].bias : a.p[0].bias;
+    double* __restrict__ out = which ? a.p[1].out : a.p[0].out;
+    const int in_dim = which ? a.p[1].in_dim : a.p[0].in_dim;
+    const int out_dim = which ? a.p[1].out_dim : a.p[0].out_dim;
+    const int last = which ? a.p[1].last : a.p[0].last;
+    const float* __restrict__ h = a.h;
+    const int32_t* __restrict__ rows = a.rows;
+    const int B = a.B, act = a.act;
     // FO output units x FB samples per workgroup: a lane's weights and inputs are each loaded once and meet
     // in FO * FB accumulators.  Per (sample, unit) the sum is what it was with one unit per workgroup: lane-
     // strided over a quarter of the inputs per wavefront, butterfly, the four quarters in order.
     __shared__ double part[4][FO][FB];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ogroups = (out_dim + FO - 1) / FO;
-    const int bg = (int)(blockIdx.x / ogroups), og = (int)(blockIdx.x % ogroups);
+    const int bg = (int)(block / ogroups), og = (int)(block % ogroups);
     const float* w[FO];
 #pragma unroll
     for (int u = 0; u < FO; ++u) w[u] = W + (size_t)min(og * FO + u, out_dim - 1) * in_dim;   // clamped duplicates are not stored
@@ -269,15 +295,40 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
 // four parts in order.  The squares of the workgroup's gradients are summed (fixed tree) to partial[blockIdx.x]
 // for the global norm.
 constexpr int GO = 4;
-__global__ __launch_bounds__(256) void ppo_weight_grad_kernel(const double* __restrict__ delta, const double* __restrict__ in64,
-                                                               const float* __restrict__ h, const int32_t* __restrict__ rows,
-                                                               int B, int in_dim, int out_dim, double* __restrict__ gW,
-                                                               double* __restrict__ gb, double* __restrict__ partial) {
+struct GradProblem {
+    const double* delta;
+    const double* in64;      // null: first layer, inputs are rows of h
+    double* gW;
+    double* gb;
+    double* partial;
+    int in_dim, out_dim;
+    unsigned blocks;
+};
+struct GradArgs {
+    GradProblem p[2];
+    int n;
+    const float* h;
+    const int32_t* rows;
+    int B;
+};
+__global__ __launch_bounds__(256) void ppo_weight_grad_kernel(GradArgs a) {
+    const int which = (a.n > 1 && blockIdx.x >= a.p[0].blocks) ? 1 : 0;
+    const unsigned block = blockIdx.x - (which ? a.p[0].blocks : 0u);
+    const double* __restrict__ delta = which ? a.p[1].delta : a.p[0].delta;
+    const double* __restrict__ in64 = which ? a.p[1].in64 : a.p[0].in64;
+    double* __restrict__ gW = which ? a.p[1].gW : a.p[0].gW;
+    double* __restrict__ gb = which ? a.p[1].gb : a.p[0].gb;
+    double* __restrict__ partial = which ? a.p[1].partial : a.p[0].partial;
+    const int in_dim = which ? a.p[1].in_dim : a.p[0].in_dim;
+    const int out_dim = which ? a.p[1].out_dim : a.p[0].out_dim;
+    const float* __restrict__ h = a.h;
+    const int32_t* __restrict__ rows = a.rows;
+    const int B = a.B;
     __shared__ double part[4][GO][64];
     __shared__ double partb[4][GO];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ichunks = (in_dim + 63) / 64;
-    const int og = (int)(blockIdx.x / ichunks), ic = (int)(blockIdx.x % ichunks);
+    const int og = (int)(block / ichunks), ic = (int)(block % ichunks);
     const int o0 = og * GO;
     const int i = ic * 64 + lane;
     const int ii = min(i, in_dim - 1);
@@ -319,21 +370,40 @@ __global__ __launch_bounds__(256) void ppo_weight_grad_kernel(const double* __re
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) sq += __shfl_xor(sq, off, 64);
-        if (lane == 0) partial[blockIdx.x] = sq;
+        if (lane == 0) partial[block] = sq;
     }
 }
 
 // delta_prev[b, i] = (sum_o delta[b, o] W[o, i]) * act'(a[b, i]), a = the activated output of the layer below
-__global__ __launch_bounds__(256) void ppo_delta_kernel(const double* __restrict__ delta, const float* __restrict__ W,
-                                                         const double* __restrict__ a_prev, int B, int in_dim, int out_dim,
-                                                         int act, double* __restrict__ delta_prev) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+struct DeltaProblem {
+    const double* delta;
+    const float* W;
+    const double* a_prev;
+    double* delta_prev;
+    int in_dim, out_dim;
+    unsigned blocks;
+};
+struct DeltaArgs {
+    DeltaProblem p[2];
+    int n, B, act;
+};
+__global__ __launch_bounds__(256) void ppo_delta_kernel(DeltaArgs a) {
+    const int which = (a.n > 1 && blockIdx.x >= a.p[0].blocks) ? 1 : 0;
+    const unsigned block = blockIdx.x - (which ? a.p[0].blocks : 0u);
+    const double* __restrict__ delta = which ? a.p[1].delta : a.p[0].delta;
+    const float* __restrict__ W = which ? a.p[1].W : a.p[0].W;
+    const double* __restrict__ a_prev = which ? a.p[1].a_prev : a.p[0].a_prev;
+    double* __restrict__ delta_prev = which ? a.p[1].delta_prev : a.p[0].delta_prev;
+    const int in_dim = which ? a.p[1].in_dim : a.p[0].in_dim;
+    const int out_dim = which ? a.p[1].out_dim : a.p[0].out_dim;
+    const int B = a.B, act = a.act;
+    const size_t idx = (size_t)block * 256 + threadIdx.x;
     if (idx >= (size_t)B * in_dim) return;
     const int b = (int)(idx / in_dim), i = (int)(idx % in_dim);
     double acc = 0.0;
     for (int o = 0; o < out_dim; ++o) acc += delta[(size_t)b * out_dim + o] * (double)W[(size_t)o * in_dim + i];
-    const double a = a_prev[idx];
-    delta_prev[idx] = acc * (act == BRL_ACT_RELU ? (a > 0.0 ? 1.0 : 0.0) : 1.0 - a * a);
+    const double av = a_prev[idx];
+    delta_prev[idx] = acc * (act == BRL_ACT_RELU ? (av > 0.0 ? 1.0 : 0.0) : 1.0 - av * av);
 }
 
 // scal[0] = global L2 norm of the gradients, scal[1] = min(1, max_norm / (norm + 1e-6)); the partial sums are
@@ -377,7 +447,7 @@ __global__ __launch_bounds__(256) void ppo_adam_kernel(float* __restrict__ p, fl
 
 struct PpoWs {
     size_t act_off[2][PPO_MAX_LAYERS];   // layer outputs [batch, dims[l+1]] fp64
-    size_t delta_off[2];                 // ping-pong deltas [batch, max_dim] fp64
+    size_t delta_off[2][2];              // ping-pong deltas per head [batch, max_dim] fp64
     size_t dv_off, grad_off, partial_off, scal_off, rows_off, total;
     int n_partials;
     int partial_first[2][PPO_MAX_LAYERS];
@@ -396,8 +466,8 @@ PpoWs ppo_ws_layout(const Layout& L, int batch) {
     };
     for (int hd = 0; hd < 2; ++hd)
         for (int l = 0; l < L.head[hd].n; ++l) W.act_off[hd][l] = take((size_t)batch * L.head[hd].dims[l + 1] * 8);
-    W.delta_off[0] = take((size_t)batch * L.max_dim * 8);
-    W.delta_off[1] = take((size_t)batch * L.max_dim * 8);
+    for (int hd = 0; hd < 2; ++hd)
+        for (int k = 0; k < 2; ++k) W.delta_off[hd][k] = take((size_t)batch * L.max_dim * 8);
     W.dv_off = take((size_t)batch * 8);
     W.grad_off = take(L.n_params * 8);
     int np = 0;
@@ -486,7 +556,9 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
     double* partial = reinterpret_cast<double*>(base + W.partial_off);
     double* scal = reinterpret_cast<double*>(base + W.scal_off);
     double* dv = reinterpret_cast<double*>(base + W.dv_off);
-    double* delta[2] = {reinterpret_cast<double*>(base + W.delta_off[0]), reinterpret_cast<double*>(base + W.delta_off[1])};
+    double* delta[2][2];
+    for (int hd = 0; hd < 2; ++hd)
+        for (int k = 0; k < 2; ++k) delta[hd][k] = reinterpret_cast<double*>(base + W.delta_off[hd][k]);
     const int A = L.head[0].dims[L.head[0].n];
     const int steps_per_epoch = T / batch;
     LaunchTimer tm(BRL_KC_OTHER, s);
@@ -495,17 +567,26 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
         for (int mb = 0; mb < steps_per_epoch; ++mb) {
             const int32_t* rows = perm + (size_t)e * T + (size_t)mb * batch;
             float* st = stats ? stats + ((size_t)e * steps_per_epoch + mb) * 5 : nullptr;
-            // forward, both heads
-            for (int hd = 0; hd < 2; ++hd) {
-                const HeadShape& H = L.head[hd];
-                for (int l = 0; l < H.n; ++l) {
-                    const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
-                    double* out = reinterpret_cast<double*>(base + W.act_off[hd][l]);
-                    const size_t blocks = (size_t)((batch + FB - 1) / FB) * ((H.dims[l + 1] + FO - 1) / FO);
-                    hipLaunchKernelGGL(ppo_forward_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in64, h, rows,
-                                       params + H.w_off[l], params + H.b_off[l], batch, H.dims[l], H.dims[l + 1], cfg->act,
-                                       l == H.n - 1 ? 1 : 0, out);
+            // forward: level l of both heads in one launch
+            const int depth = L.head[0].n > L.head[1].n ? L.head[0].n : L.head[1].n;
+            for (int l = 0; l < depth; ++l) {
+                FwdArgs fa;
+                memset(&fa, 0, sizeof(fa));
+                fa.h = h; fa.rows = rows; fa.B = batch; fa.act = cfg->act;
+                unsigned blocks = 0;
+                for (int hd = 0; hd < 2; ++hd) {
+                    const HeadShape& H = L.head[hd];
+                    if (l >= H.n) continue;
+                    FwdProblem& P = fa.p[fa.n++];
+                    P.in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
+                    P.W = params + H.w_off[l];
+                    P.bias = params + H.b_off[l];
+                    P.out = reinterpret_cast<double*>(base + W.act_off[hd][l]);
+                    P.in_dim = H.dims[l]; P.out_dim = H.dims[l + 1]; P.last = l == H.n - 1 ? 1 : 0;
+                    P.blocks = (unsigned)(((batch + FB - 1) / FB) * ((H.dims[l + 1] + FO - 1) / FO));
+                    blocks += P.blocks;
                 }
+                hipLaunchKernelGGL(ppo_forward_kernel, dim3(blocks), dim3(256), 0, s, fa);
             }
             // gradients at the outputs
             LossArgs la;
@@ -515,31 +596,51 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
             la.B = batch; la.A = A;
             la.clip_eps = (double)cfg->clip_eps; la.ent_coef = (double)cfg->ent_coef; la.adv_eps = (double)cfg->adv_eps;
             la.normalize_adv = cfg->normalize_adv;
-            la.dlogits = delta[0];
+            la.dlogits = delta[0][0];
             la.dv = dv;
             la.stats = st;
             la.row_terms = reinterpret_cast<double*>(base + W.rows_off);
             hipLaunchKernelGGL(ppo_loss_kernel, dim3(1), dim3(256), 0, s, la);
-            // backward, both heads
-            for (int hd = 0; hd < 2; ++hd) {
-                const HeadShape& H = L.head[hd];
-                const double* dcur = hd == 0 ? delta[0] : dv;
-                int pp = 1;                 // next ping-pong buffer (delta[0] holds dlogits until the policy head is done)
-                for (int l = H.n - 1; l >= 0; --l) {
+            // backward: the same distance from the output of both heads in one launch; each head ping-pongs
+            // between its own two delta buffers (the policy head's first one holds dlogits)
+            const double* dcur[2] = {delta[0][0], dv};
+            int pp[2] = {1, 0};
+            for (int t = 0; t < depth; ++t) {
+                GradArgs ga;
+                DeltaArgs da;
+                memset(&ga, 0, sizeof(ga));
+                memset(&da, 0, sizeof(da));
+                ga.h = h; ga.rows = rows; ga.B = batch;
+                da.B = batch; da.act = cfg->act;
+                unsigned gblocks = 0, dblocks = 0;
+                const double* dnext[2] = {dcur[0], dcur[1]};
+                for (int hd = 0; hd < 2; ++hd) {
+                    const HeadShape& H = L.head[hd];
+                    const int l = H.n - 1 - t;
+                    if (l < 0) continue;
                     const double* in64 = l == 0 ? nullptr : reinterpret_cast<const double*>(base + W.act_off[hd][l - 1]);
-                    const size_t blocks = (size_t)((H.dims[l + 1] + GO - 1) / GO) * ((H.dims[l] + 63) / 64);
-                    hipLaunchKernelGGL(ppo_weight_grad_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dcur, in64, h,
-                                       rows, batch, H.dims[l], H.dims[l + 1], grads + H.w_off[l], grads + H.b_off[l],
-                                       partial + W.partial_first[hd][l]);
+                    GradProblem& G = ga.p[ga.n++];
+                    G.delta = dcur[hd]; G.in64 = in64;
+                    G.gW = grads + H.w_off[l]; G.gb = grads + H.b_off[l];
+                    G.partial = partial + W.partial_first[hd][l];
+                    G.in_dim = H.dims[l]; G.out_dim = H.dims[l + 1];
+                    G.blocks = (unsigned)(((H.dims[l + 1] + GO - 1) / GO) * ((H.dims[l] + 63) / 64));
+                    gblocks += G.blocks;
                     if (l > 0) {
-                        double* dprev = delta[pp];
-                        const size_t m = (size_t)batch * H.dims[l];
-                        hipLaunchKernelGGL(ppo_delta_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, dcur,
-                                           params + H.w_off[l], in64, batch, H.dims[l], H.dims[l + 1], cfg->act, dprev);
-                        dcur = dprev;
-                        pp ^= 1;
+                        DeltaProblem& D = da.p[da.n++];
+                        D.delta = dcur[hd]; D.W = params + H.w_off[l]; D.a_prev = in64;
+                        D.delta_prev = delta[hd][pp[hd]];
+                        D.in_dim = H.dims[l]; D.out_dim = H.dims[l + 1];
+                        D.blocks = (unsigned)(((size_t)batch * H.dims[l] + 255) / 256);
+                        dblocks += D.blocks;
+                        dnext[hd] = D.delta_prev;
+                        pp[hd] ^= 1;
                     }
                 }
+                hipLaunchKernelGGL(ppo_weight_grad_kernel, dim3(gblocks), dim3(256), 0, s, ga);
+                if (da.n > 0) hipLaunchKernelGGL(ppo_delta_kernel, dim3(dblocks), dim3(256), 0, s, da);
+                dcur[0] = dnext[0];
+                dcur[1] = dnext[1];
             }
             hipLaunchKernelGGL(ppo_norm_kernel, dim3(1), dim3(256), 0, s, partial, W.n_partials, (double)cfg->max_grad_norm, scal, st);
             ++step;

@@ -54,6 +54,8 @@ def _run_case(B, R, dims_p, dims_v, act, T, batch, epochs, seed, **hyper):
     ([2560, 256, 18], [2560, 256, 1], "tanh", 256, 64, 2),       # the measured head shape
     ([96, 32, 16, 5], [96, 32, 16, 1], "relu", 200, 48, 3),      # two hidden layers, ragged rollout (8 steps dropped per epoch)
     ([64, 7], [64, 1], "tanh", 40, 40, 1),                        # single layer, one step
+    ([96, 32, 16, 5], [96, 24, 1], "tanh", 128, 32, 2),           # heads of unequal depth: the deeper one's extra level runs alone
+    ([64, 7], [64, 16, 8, 1], "relu", 96, 32, 2),
 ])
 def test_head_update_matches_oracle(dims_p, dims_v, act, T, batch, epochs):
     B, R = _mods()
