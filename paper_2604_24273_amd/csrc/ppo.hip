@@ -290,10 +290,10 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
     }
 }
 
-// dW[o, i] = sum_b delta[b, o] in(b, i), db[o] = sum_b delta[b, o].  A workgroup takes GO output units and 64
-// consecutive inputs; its four wavefronts take a quarter of the samples each (in order), and wavefront 0 adds the
-// four parts in order.  The squares of the workgroup's gradients are summed (fixed tree) to partial[blockIdx.x]
-// for the global norm.
+// dW[o, i] = sum_b delta[b, o] in(b, i), db[o] = sum_b delta[b, o].  A wavefront takes GO output units and 64
+// consecutive inputs and sums over the samples in order; the four wavefronts of a workgroup take neighbouring
+// input chunks and share nothing.  The squares of a wavefront's gradients are summed (fixed tree) to one slot
+// of partial[] for the global norm.
 constexpr int GO = 4;
 struct GradProblem {
     const double* delta;
@@ -324,21 +324,19 @@ __global__ __launch_bounds__(256) void ppo_weight_grad_kernel(GradArgs a) {
     const float* __restrict__ h = a.h;
     const int32_t* __restrict__ rows = a.rows;
     const int B = a.B;
-    __shared__ double part[4][GO][64];
-    __shared__ double partb[4][GO];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ichunks = (in_dim + 63) / 64;
-    const int og = (int)(block / ichunks), ic = (int)(block % ichunks);
+    const int cpw = (ichunks + 3) / 4;                 // groups of four input chunks, one chunk per wavefront
+    const int og = (int)(block / cpw), chunk = (int)(block % cpw) * 4 + wave;
+    if (chunk >= ichunks) return;
     const int o0 = og * GO;
-    const int i = ic * 64 + lane;
+    const int i = chunk * 64 + lane;
     const int ii = min(i, in_dim - 1);
-    const int bq = (B + 3) / 4;
-    const int b_end = min(B, (wave + 1) * bq);
     double acc[GO], accb[GO];
 #pragma unroll
     for (int q = 0; q < GO; ++q) { acc[q] = 0.0; accb[q] = 0.0; }
-#pragma unroll 4
-    for (int b = wave * bq; b < b_end; ++b) {
+#pragma unroll 8
+    for (int b = 0; b < B; ++b) {
         const double x = in64 ? in64[(size_t)b * in_dim + ii] : (double)h[(size_t)rows[b] * in_dim + ii];
 #pragma unroll
         for (int q = 0; q < GO; ++q) {
@@ -347,31 +345,21 @@ __global__ __launch_bounds__(256) void ppo_weight_grad_kernel(GradArgs a) {
             accb[q] += d;
         }
     }
+    double sq = 0.0;
 #pragma unroll
     for (int q = 0; q < GO; ++q) {
-        part[wave][q][lane] = acc[q];
-        if (lane == 0) partb[wave][q] = accb[q];
-    }
-    __syncthreads();
-    double sq = 0.0;
-    if (wave == 0) {
-#pragma unroll
-        for (int q = 0; q < GO; ++q) {
-            if (o0 + q < out_dim && i < in_dim) {
-                const double g = ((part[0][q][lane] + part[1][q][lane]) + part[2][q][lane]) + part[3][q][lane];
-                gW[(size_t)(o0 + q) * in_dim + i] = g;
-                sq += g * g;
-                if (i == 0) {
-                    const double gbv = ((partb[0][q] + partb[1][q]) + partb[2][q]) + partb[3][q];
-                    gb[o0 + q] = gbv;
-                    sq += gbv * gbv;
-                }
+        if (o0 + q < out_dim && i < in_dim) {
+            gW[(size_t)(o0 + q) * in_dim + i] = acc[q];
+            sq += acc[q] * acc[q];
+            if (i == 0) {
+                gb[o0 + q] = accb[q];
+                sq += accb[q] * accb[q];
             }
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) sq += __shfl_xor(sq, off, 64);
-        if (lane == 0) partial[block] = sq;
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sq += __shfl_xor(sq, off, 64);
+    if (lane == 0) partial[og * ichunks + chunk] = sq;
 }
 
 // delta_prev[b, i] = (sum_o delta[b, o] W[o, i]) * act'(a[b, i]), a = the activated output of the layer below
@@ -624,7 +612,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                     G.gW = grads + H.w_off[l]; G.gb = grads + H.b_off[l];
                     G.partial = partial + W.partial_first[hd][l];
                     G.in_dim = H.dims[l]; G.out_dim = H.dims[l + 1];
-                    G.blocks = (unsigned)(((H.dims[l + 1] + GO - 1) / GO) * ((H.dims[l] + 63) / 64));
+                    G.blocks = (unsigned)(((H.dims[l + 1] + GO - 1) / GO) * (((H.dims[l] + 63) / 64 + 3) / 4));
                     gblocks += G.blocks;
                     if (l > 0) {
                         DeltaProblem& D = da.p[da.n++];
