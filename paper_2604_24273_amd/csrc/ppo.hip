@@ -240,14 +240,24 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
         s_inv = 1.0;
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < a.B; b += blockDim.x) {
-        const int r = a.rows[b];
+    // LG adjacent lanes share a sample: each takes every LG-th action; maxima and sums meet by butterfly
+    constexpr int LG = 4;
+    const int part = threadIdx.x % LG;
+    for (int b0 = 0; b0 < a.B; b0 += 256 / LG) {
+        const int b = b0 + (int)threadIdx.x / LG;
+        const bool live = b < a.B;
+        const int bc = live ? b : a.B - 1;              // idle lanes shadow the last sample and store nothing
+        const int r = a.rows[bc];
         const double A = ((double)a.adv[r] - s_mean) * s_inv;
-        const double* z = a.logits + (size_t)b * a.A;
+        const double* z = a.logits + (size_t)bc * a.A;
         double m = z[0];
-        for (int k = 1; k < a.A; ++k) m = fmax(m, z[k]);
+        for (int k = part; k < a.A; k += LG) m = fmax(m, z[k]);
+#pragma unroll
+        for (int off = 1; off < LG; off <<= 1) m = fmax(m, __shfl_xor(m, off, 64));
         double se = 0.0;
-        for (int k = 0; k < a.A; ++k) se += exp(z[k] - m);
+        for (int k = part; k < a.A; k += LG) se += exp(z[k] - m);
+#pragma unroll
+        for (int off = 1; off < LG; off <<= 1) se += __shfl_xor(se, off, 64);
         const double lse = m + log(se);
         const int act = a.actions[r];
         const double logp = z[act] - lse;
@@ -257,21 +267,27 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
         const double surr2 = clipped * A;
         const double active = surr1 <= surr2 ? 1.0 : 0.0;
         double ent = 0.0;
-        for (int k = 0; k < a.A; ++k) {
+        for (int k = part; k < a.A; k += LG) {
             const double lp = z[k] - lse;
             ent -= exp(lp) * lp;
         }
+#pragma unroll
+        for (int off = 1; off < LG; off <<= 1) ent += __shfl_xor(ent, off, 64);
         const double coef = -(active * A * ratio);
-        for (int k = 0; k < a.A; ++k) {
-            const double lp = z[k] - lse, p = exp(lp);
-            a.dlogits[(size_t)b * a.A + k] = (coef * ((k == act ? 1.0 : 0.0) - p) + a.ent_coef * p * (lp + ent)) / (double)a.B;
+        if (live) {
+            for (int k = part; k < a.A; k += LG) {
+                const double lp = z[k] - lse, p = exp(lp);
+                a.dlogits[(size_t)b * a.A + k] = (coef * ((k == act ? 1.0 : 0.0) - p) + a.ent_coef * p * (lp + ent)) / (double)a.B;
+            }
+            if (part == 0) {
+                const double diff = a.v[b] - (double)a.returns[r];
+                a.dv[b] = diff / (double)a.B;
+                a.row_terms[0 * a.B + b] = fmin(surr1, surr2);
+                a.row_terms[1 * a.B + b] = ent;
+                a.row_terms[2 * a.B + b] = diff * diff;
+                a.row_terms[3 * a.B + b] = 1.0 - active;
+            }
         }
-        const double diff = a.v[b] - (double)a.returns[r];
-        a.dv[b] = diff / (double)a.B;
-        a.row_terms[0 * a.B + b] = fmin(surr1, surr2);
-        a.row_terms[1 * a.B + b] = ent;
-        a.row_terms[2 * a.B + b] = diff * diff;
-        a.row_terms[3 * a.B + b] = 1.0 - active;
     }
     __syncthreads();
     if (threadIdx.x == 0 && a.stats) {
