@@ -103,6 +103,7 @@ def _run_bitlinear(B, R, pl, X, residual=None, taps=True):
     (600, 2560, 6912), (1300, 1000, 4608),                       # few 128 x 128 tiles, long k: k-split launches (ragged N in the second)
     (200, 1000, 4608), (700, 264, 6912),                         # 64 x 32 tiles, k split inside the workgroup
     (2050, 8192, 264), (2048, 8200, 128),      # enough tiles for the 8-wavefront kernel, ragged edges
+    (1024, 640, 2560), (1025, 640, 2560),      # last size of the one-workgroup-per-token quantiser, first of the persistent one
 ])
 def test_bitlinear_forward_parity(m, n, k):
     B, R = _mods()
