@@ -103,6 +103,13 @@ int brl_unpack_codes(const void* packed, int n_out, int k_in, int8_t* codes_out,
 
 /* ------------------------------------------------------------------------
  * BitLinear forward: y = dequant(ternary_matmul(quant(x), W)) (+ residual).
+ * Sec. 3.1 (Framework Architecture, last paragraph): the backbone runs its
+ * ternary weights (Eq. 2) through integer-only kernels, no floating-point
+ * multiply-accumulate.  The paper does not define the activation side; it is
+ * taken from the BitNet b1.58 scheme the paper names as its backbone: one
+ * symmetric int8 scale per token from the absolute maximum (Qb = 127,
+ * round-half-to-even), int32 accumulation, and one fp32 rescale by the token
+ * scale and the matrix scale beta of Eq. 2's threshold.
  *
  * Per token t: a = max(max_k |x_tk|, eps_act); q_tk = clamp(rne(x_tk *
  * (127 / a)), -127, 127); acc_tn = sum_k q_tk code_nk (int32, exact);
@@ -122,7 +129,7 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K,
                       void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Int8-weight BitLinear for a higher-precision critic backbone (Sec. 5.4,
+ * Int8-weight BitLinear for a higher-precision critic backbone (Sec. 5.3,
  * component ablations: the "INT8 critic + 1-bit policy" rows; the paper names
  * the configuration, the quantiser below is this library's reading of it).
  *
@@ -177,7 +184,11 @@ int bitlinear_forward_batch(const void* const* packed, const float* const* beta,
                             float* const* y, int count, void* stream);
 
 /* ------------------------------------------------------------------------
- * One feed-forward block:
+ * One feed-forward block of the frozen backbone f of Sec. 3.1, Eq. 3 (the
+ * paper cites the BitNet b1.58 architecture for f and gives no block
+ * internals; this is that architecture's block: pre-norm, gate / up BitLinear
+ * sharing one quantised input, squared-ReLU gated unit, sub-layer norm, down
+ * BitLinear, residual):
  *   n = RMSNorm_d(x; norm_g);  (G, U) = BitLinear_gate(n), BitLinear_up(n)
  *   (n is quantised once, each matrix keeps its own beta);
  *   h = (max(G,0) * max(G,0)) * U;  m = RMSNorm_f(h; subln_g);
@@ -210,7 +221,9 @@ int ffn_block_forward(const brl_ffn_weights* w /* HOST */, const void* x, int x_
  * at position = index inside the state, causal softmax(q k^T / sqrt(head_dim))
  * v, query head h reading key/value head h / (n_heads / n_kv_heads); then the
  * feed-forward block above.  h[b] = mean over the first lengths[b] positions
- * (all S if lengths is NULL) of RMSNorm(x; final_norm_g), summed in fp64.
+ * (all S if lengths is NULL) of RMSNorm(x; final_norm_g), summed in fp64
+ * (mean pooling is the only pooling; the paper says only that h_t is a vector
+ * of the hidden width).
  * States are independent; large batches are processed in micro-batches of
  * whole states inside the call.  Like every *_forward here the call only
  * enqueues kernels on `stream` (no allocation, no synchronisation), so a
@@ -232,7 +245,9 @@ typedef struct brl_layer_weights {
 typedef struct brl_encoder {
     int   n_layers, d, n_heads, n_kv_heads, head_dim, f, vocab;
     float rope_theta, eps_norm, eps_act;
-    int   attn_precision;               /* BRL_ATTN_* */
+    int   attn_precision;               /* BRL_ATTN_*: fp32 vector ALUs, or fp16 hi + lo pairs on the matrix
+                                           cores (fp32-grade; there is no plain 16-bit mode: its error is
+                                           amplified by the int8 re-quantisation of every later layer) */
     int   weight_format;                /* BRL_W_*: what every *_packed pointer of the layers holds; with
                                            BRL_W_INT8 each *_beta is the scale from bitlinear_quantize_weights_int8 */
     const uint16_t* embedding;          /* [vocab, d] bf16 bit patterns */
@@ -266,6 +281,31 @@ int encoder_forward_packed(const brl_encoder* enc /* HOST */, const int32_t* ids
                            void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The attention stage of an encoder layer on its own (the softmax attention of
+ * the backbone f of Sec. 3.1, Eq. 3; the paper gives no internals, the form is
+ * that of the BitNet b1.58 decoder it cites): rotary embedding of q and k on
+ * pairs (i, i + head_dim/2) at position = index inside the state, causal
+ * softmax(q k^T / sqrt(head_dim)) v, query head h reading key/value head
+ * h / (n_heads / n_kv_heads).  encoder_forward runs exactly these kernels on
+ * the output of its q | k | v BitLinear; this entry point exposes them so that
+ * the stage can be checked by itself.
+ *
+ * qkv [T, (n_heads + 2 n_kv_heads) * head_dim] fp32, a row = q heads | k heads
+ * | v heads; out [T, n_heads * head_dim] fp32.  cu_seqlens NULL (both copies):
+ * B states of S rows each, T = B * S.  Otherwise state b owns rows
+ * cu_seqlens[b] .. cu_seqlens[b+1]-1 (DEVICE and HOST copies of the same
+ * [B+1] int32 array, lengths in 1..S, else BRL_EINVAL) and S bounds the
+ * lengths.  head_dim in {16, 32, 64, 100, 128}; attn_precision BRL_ATTN_*.
+ * With BRL_ATTN_MFMA, states of at most 32 tokens (up to 1024 workgroups) take
+ * a one-kernel path, everything else the pack + fragment kernels.
+ * ------------------------------------------------------------------------ */
+size_t brl_attention_workspace_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim);
+int attention_forward(const float* qkv, int B, int S,
+                      const int32_t* cu_seqlens /* DEVICE or NULL */, const int32_t* cu_seqlens_host /* HOST or NULL */,
+                      int n_heads, int n_kv_heads, int head_dim, float rope_theta, int attn_precision,
+                      float* out, void* workspace, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Policy and value heads (Sec. 3.1, Eq. 3; fp32 parameters, Appendix table):
  * each is an MLP, out = W_L act(... act(W_1 h + b_1) ...) + b_L, accumulated
  * in fp64 and rounded to fp32 once at the output.  The softmax over the
@@ -290,7 +330,7 @@ int policy_value_head(const brl_head* head /* HOST */, const float* h, int B,
                       void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Ensemble critic (Sec. 5.4, component ablations: "3x / 5x 1-bit critics
+ * Ensemble critic (Sec. 5.3, component ablations: "3x / 5x 1-bit critics
  * (avg)"): n_members value heads of identical shape read the same h; every
  * layer of all members runs in one launch.  values_each[e][b] is member e's
  * head output exactly as policy_value_head computes a value; value_mean[b] =

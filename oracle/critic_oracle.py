@@ -7,7 +7,7 @@ of `oracle.bitrl_oracle` (integer matmul, rescale, fully connected head).
 
 What the paper fixes and what it leaves open
 --------------------------------------------
-Sec. 5.4 (component ablations, hybrid-precision rows) names an "INT8 critic + 1-bit
+Sec. 5.3 (component ablations, hybrid-precision rows) names an "INT8 critic + 1-bit
 policy" configuration and "3x / 5x 1-bit critics (avg)" ensembles, and reports returns and
 memory for them; it defines neither the int8 quantiser nor what the ensemble averages.
 Readings taken here (also listed in the design document):
@@ -40,7 +40,7 @@ QB = 127
 
 
 def int8_quantize(W: np.ndarray, eps: float = 1e-5, qmax: int = QB) -> Tuple[np.ndarray, np.float32]:
-    """Per-tensor absmax integer code of W[N, K] (Sec. 5.4, hybrid-precision critic; reading above).
+    """Per-tensor absmax integer code of W[N, K] (Sec. 5.3, hybrid-precision critic; reading above).
 
     qmax = 127 is the int8 critic; qmax = 7 is the grid of the table's int4 critic (codes in
     [-7, 7], here still one code per int8 element: the definition does not depend on storage).
@@ -88,7 +88,7 @@ def int8_bitlinear_forward(x: np.ndarray, codes: np.ndarray, scale, eps: float =
 
 
 def value_ensemble(h: np.ndarray, members: Sequence[O.MLP]) -> Tuple[np.ndarray, np.ndarray]:
-    """Ensemble critic (Sec. 5.4, ensemble rows; reading above).
+    """Ensemble critic (Sec. 5.3, ensemble rows; reading above).
 
     Returns (mean [B] float32, each [n, B] float32)."""
     if len(members) == 0:

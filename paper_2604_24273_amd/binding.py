@@ -108,6 +108,9 @@ _SIGNATURES = {
     "brl_encoder_packed_workspace_bytes": (c_size_t, [C.POINTER(brl_encoder), c_int, c_int, c_int]),
     "encoder_forward_packed": (c_int, [C.POINTER(brl_encoder), c_void_p, c_void_p, c_void_p, c_int, c_int, c_void_p,
                                        c_void_p, c_size_t, c_void_p]),
+    "brl_attention_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int, c_int]),
+    "attention_forward": (c_int, [c_void_p, c_int, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_float, c_int,
+                                  c_void_p, c_void_p, c_size_t, c_void_p]),
     "brl_head_workspace_bytes": (c_size_t, [C.POINTER(brl_head), c_int]),
     "policy_value_head": (c_int, [C.POINTER(brl_head), c_void_p, c_int, c_void_p, c_void_p,
                                   c_void_p, c_size_t, c_void_p]),
@@ -268,6 +271,20 @@ def encoder_forward_packed(enc: brl_encoder, ids: torch.Tensor, cu_seqlens: torc
     _check(lib().encoder_forward_packed(C.byref(enc), _ptr(ids), _ptr(cu_seqlens), cu_seqlens_host.ctypes.data, B, max_len,
                                         _ptr(h), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                         _stream()))
+
+
+def brl_attention_workspace_bytes(B: int, S: int, n_heads: int, n_kv_heads: int, head_dim: int) -> int:
+    return lib().brl_attention_workspace_bytes(B, S, n_heads, n_kv_heads, head_dim)
+
+
+def attention_forward(qkv: torch.Tensor, B: int, S: int, cu_seqlens: Optional[torch.Tensor], cu_seqlens_host,
+                      n_heads: int, n_kv_heads: int, head_dim: int, rope_theta: float, attn_precision: int,
+                      out: torch.Tensor, workspace: torch.Tensor) -> None:
+    """cu_seqlens: int32 device tensor [B+1] or None; cu_seqlens_host: int32 numpy array with the same values or None."""
+    _check(lib().attention_forward(_ptr(qkv), B, S, _ptr(cu_seqlens),
+                                   None if cu_seqlens_host is None else cu_seqlens_host.ctypes.data,
+                                   n_heads, n_kv_heads, head_dim, rope_theta, attn_precision, _ptr(out), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()))
 
 
 def brl_head_workspace_bytes(head: brl_head, B: int) -> int:

@@ -715,6 +715,73 @@ int encoder_forward_packed(const brl_encoder* enc, const int32_t* ids, const int
     return BRL_OK;
 }
 
+namespace {
+
+struct AttnWs {
+    size_t cos_off, sin_off, frag_off, total;
+};
+
+AttnWs attention_ws_layout(int B, int S, int n_heads, int n_kv_heads, int head_dim) {
+    AttnWs L;
+    const size_t tbl = round_up_sz((size_t)S * (head_dim / 2) * 4, ALIGN);
+    L.cos_off = 0;
+    L.sin_off = tbl;
+    L.frag_off = 2 * tbl;
+    L.total = L.frag_off + round_up_sz(attention_mfma_ws_bytes(B, S, n_heads, n_kv_heads, head_dim), ALIGN);
+    return L;
+}
+
+bool attention_shape_ok(int B, int S, int n_heads, int n_kv_heads, int head_dim) {
+    return B >= 1 && S >= 1 && S <= (1 << 20) && n_heads >= 1 && n_kv_heads >= 1 && n_heads % n_kv_heads == 0 &&
+           (head_dim == 16 || head_dim == 32 || head_dim == 64 || head_dim == 100 || head_dim == 128);
+}
+
+}  // namespace
+
+size_t brl_attention_workspace_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim) {
+    if (!attention_shape_ok(B, S, n_heads, n_kv_heads, head_dim)) return 0;
+    return attention_ws_layout(B, S, n_heads, n_kv_heads, head_dim).total;
+}
+
+int attention_forward(const float* qkv, int B, int S, const int32_t* cu_seqlens, const int32_t* cu_seqlens_host,
+                      int n_heads, int n_kv_heads, int head_dim, float rope_theta, int attn_precision, float* out,
+                      void* workspace, size_t ws_bytes, void* stream) {
+    BRL_REQUIRE(qkv && out && workspace && aligned16(qkv) && aligned16(out) && aligned16(workspace),
+                "attention_forward: null or misaligned pointer");
+    BRL_REQUIRE(attention_shape_ok(B, S, n_heads, n_kv_heads, head_dim),
+                "attention_forward: bad shape (B %d, S %d, heads %d / %d, head_dim %d not in {16, 32, 64, 100, 128})", B, S,
+                n_heads, n_kv_heads, head_dim);
+    BRL_REQUIRE(rope_theta > 0.f, "attention_forward: rope_theta must be positive");
+    BRL_REQUIRE(attn_precision == BRL_ATTN_F32 || attn_precision == BRL_ATTN_MFMA,
+                "attention_forward: unknown attn_precision %d", attn_precision);
+    BRL_REQUIRE((cu_seqlens == nullptr) == (cu_seqlens_host == nullptr),
+                "attention_forward: cu_seqlens needs both its device and its host copy");
+    if (cu_seqlens_host) {
+        BRL_REQUIRE(cu_seqlens_host[0] == 0, "attention_forward: cu_seqlens[0] must be 0");
+        for (int b = 0; b < B; ++b) {
+            const long long n = (long long)cu_seqlens_host[b + 1] - cu_seqlens_host[b];
+            BRL_REQUIRE(n >= 1 && n <= S, "attention_forward: state %d has %lld tokens (1..%d allowed)", b, n, S);
+        }
+    }
+    const AttnWs L = attention_ws_layout(B, S, n_heads, n_kv_heads, head_dim);
+    if (ws_bytes < L.total) {
+        set_error("attention_forward: workspace %zu < %zu", ws_bytes, L.total);
+        return BRL_ENOSPC;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(workspace);
+    float* cos_t = reinterpret_cast<float*>(base + L.cos_off);
+    float* sin_t = reinterpret_cast<float*>(base + L.sin_off);
+    if (int rc = launch_rope_table(cos_t, sin_t, S, head_dim, rope_theta, s)) return rc;
+    SeqMap sm;
+    sm.cu = cu_seqlens;
+    sm.b0 = 0;
+    const int ld = (n_heads + 2 * n_kv_heads) * head_dim;
+    if (attn_precision == BRL_ATTN_MFMA)
+        return launch_attention_mfma(qkv, ld, B, S, sm, n_heads, n_kv_heads, head_dim, cos_t, sin_t, base + L.frag_off, out, s);
+    return launch_attention_f32(qkv, ld, B, S, sm, n_heads, n_kv_heads, head_dim, cos_t, sin_t, out, s);
+}
+
 size_t brl_head_workspace_bytes(const brl_head* head, int B) {
     if (!head || B < 1) return 0;
     if (!head->policy.dims || !head->value.dims || head->policy.n_layers < 1 || head->value.n_layers < 1 ||

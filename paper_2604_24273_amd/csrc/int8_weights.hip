@@ -1,5 +1,5 @@
 // Per-tensor absmax int8 weights for the higher-precision critic backbone
-// (paper Sec. 5.4, hybrid-precision rows; the quantiser mirrors the per-token
+// (paper Sec. 5.3, hybrid-precision rows; the quantiser mirrors the per-token
 // activation quantiser on the whole matrix):
 //
 //   a = max(max |W|, eps);  s = qmax / a;  code = clamp(rne(w * s), -qmax, qmax);  scale = a / qmax
