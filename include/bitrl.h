@@ -129,6 +129,30 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K,
                       void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * bitlinear_forward for callers that cannot allocate device memory or hand over
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments (no workspace), same kernels, same
+ * bits in y and in the taps.  The quantised activations (int8 tiles, per-token
+ * scale and code sum: 32-row x 128-column padded M x K bytes + 12 bytes per
+ * token) are kept in an array built into the library,
+ * BRL_STATIC_SCRATCH_BYTES per GPU, held until the process ends.  Larger
+ * products return BRL_ENOSPC (nothing enqueued); M <= 4 needs no scratch.
+ * The call makes no hipMalloc / hipFree and no allocating library call; the
+ * first call on a device looks the array's address up (make it outside graph
+ * capture).  Every call on one GPU shares that GPU's array: the contents are
+ * rewritten by each call (nothing has to start at zero), and calls that
+ * overlap in time on one GPU (different streams or threads) race - order them.
+ * Products that bitlinear_forward would cut along k run uncut here (integer
+ * sums: identical results).
+ * ------------------------------------------------------------------------ */
+#define BRL_STATIC_SCRATCH_BYTES (16u << 20)
+int bitlinear_forward_static(const void* packed, const float* beta, int N, int K,
+                             const void* x, int x_dtype, int M, float eps_act,
+                             float* y, const float* residual,
+                             int8_t* xq_dbg, float* absmax_dbg, int32_t* acc_dbg,
+                             void* stream);
+
+/* ------------------------------------------------------------------------
  * Int8-weight BitLinear for a higher-precision critic backbone (Sec. 5.3,
  * component ablations: the "INT8 critic + 1-bit policy" rows; the paper names
  * the configuration, the quantiser below is this library's reading of it).

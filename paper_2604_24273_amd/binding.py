@@ -88,6 +88,8 @@ _SIGNATURES = {
     "brl_bitlinear_workspace_bytes": (c_size_t, [c_int, c_int, c_int]),
     "bitlinear_forward": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "bitlinear_forward_static": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_int, c_float,
+                                         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "brl_packed_int8_bytes": (c_size_t, [c_int, c_int]),
     "bitlinear_quantize_weights_int8": (c_int, [c_void_p, c_int, c_int, c_float, c_int, c_void_p, c_void_p, c_void_p,
                                                 c_void_p, c_size_t, c_void_p]),
@@ -207,6 +209,17 @@ def bitlinear_forward(packed: torch.Tensor, beta: torch.Tensor, N: int, K: int, 
     _check(lib().bitlinear_forward(_ptr(packed), _ptr(beta), N, K, _ptr(x), _dtype_code(x), M, eps_act, _ptr(y),
                                    _ptr(residual), _ptr(xq_dbg), _ptr(absmax_dbg), _ptr(acc_dbg), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+BRL_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def bitlinear_forward_static(packed: torch.Tensor, beta: torch.Tensor, N: int, K: int, x: torch.Tensor, M: int,
+                             eps_act: float, y: torch.Tensor, residual: Optional[torch.Tensor],
+                             xq_dbg: Optional[torch.Tensor], absmax_dbg: Optional[torch.Tensor],
+                             acc_dbg: Optional[torch.Tensor]) -> None:
+    _check(lib().bitlinear_forward_static(_ptr(packed), _ptr(beta), N, K, _ptr(x), _dtype_code(x), M, eps_act, _ptr(y),
+                                          _ptr(residual), _ptr(xq_dbg), _ptr(absmax_dbg), _ptr(acc_dbg), _stream()))
 
 
 def brl_packed_int8_bytes(n_out: int, k_in: int) -> int:

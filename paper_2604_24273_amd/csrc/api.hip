@@ -421,6 +421,80 @@ int bitlinear_forward(const void* packed, const float* beta, int N, int K, const
     return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, 0, s);
 }
 
+// ---- bitlinear_forward for callers that cannot allocate: the quantised activations live in a
+// file-scope device array instead of a caller workspace.  The array's name is only a host-side
+// handle; its device address is looked up once per device and used from then on.
+static __device__ __align__(256) unsigned char scratch[BRL_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES];     // device address of `scratch` on each device, 0 until first use there
+
+int scratch_of_current_device(char** out) {
+    int dev = -1;
+    BRL_HIP_CHECK(hipGetDevice(&dev));
+    BRL_REQUIRE(dev >= 0 && dev < MAX_DEVICES, "bitlinear_forward_static: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        BRL_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        BRL_REQUIRE(p != nullptr, "bitlinear_forward_static: no address for the scratch array on device %d", dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<char*>(g_scratch_ptr[dev]);
+    return BRL_OK;
+}
+
+// the quantised activations alone: no k-split partial tiles (products that would cut k run uncut, same bits)
+size_t static_actbuf_bytes(int M, int K) {
+    const size_t Mp = round_up(M, NB), Kp = round_up(K, SBK);
+    return round_up_sz(Mp * Kp, ALIGN) + 3 * round_up_sz(Mp * 4, ALIGN);
+}
+}  // namespace
+
+int bitlinear_forward_static(const void* packed, const float* beta, int N, int K, const void* x, int x_dtype, int M,
+                             float eps_act, float* y, const float* residual, int8_t* xq_dbg, float* absmax_dbg,
+                             int32_t* acc_dbg, void* stream) {
+    BRL_REQUIRE(packed && beta && x && y, "bitlinear_forward_static: null pointer");
+    BRL_REQUIRE(aligned16(packed) && aligned16(x) && aligned16(y) && (!residual || aligned16(residual)),
+                "bitlinear_forward_static: pointers must be 16-byte aligned");
+    BRL_REQUIRE(M >= 1, "bitlinear_forward_static: M = %d", M);
+    BRL_REQUIRE(x_dtype == BRL_F32 || x_dtype == BRL_BF16, "bitlinear_forward_static: unknown x_dtype %d", x_dtype);
+    BRL_REQUIRE(eps_act > 0.f, "bitlinear_forward_static: eps_act must be positive");
+    if (int rc = check_linear_shape(N, K, "bitlinear_forward_static")) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M <= 4) {      // the 1..4 token path keeps everything in registers and LDS
+        return launch_gemv(x, x_dtype, M, K, N, static_cast<const uint32_t*>(packed), beta, eps_act, y, residual, xq_dbg,
+                           absmax_dbg, acc_dbg, s);
+    }
+    const size_t need = static_actbuf_bytes(M, K);
+    if (need > (size_t)BRL_STATIC_SCRATCH_BYTES) {
+        set_error("bitlinear_forward_static: %d tokens x %d features need %zu bytes of scratch, the built-in array holds %zu; "
+                  "use bitlinear_forward with a workspace",
+                  M, K, need, (size_t)BRL_STATIC_SCRATCH_BYTES);
+        return BRL_ENOSPC;
+    }
+    char* base = nullptr;
+    if (int rc = scratch_of_current_device(&base)) return rc;
+    const size_t Mp = round_up(M, NB), Kp = round_up(K, SBK);
+    Carver c(base);
+    ActBuf act;
+    act.q = c.take<int8_t>(Mp * Kp);
+    act.absmax = c.take<float>(Mp);
+    act.dscale = c.take<float>(Mp);
+    act.sumq = c.take<int32_t>(Mp);
+    act.splitk = nullptr;
+    act.splitk_ints = 0;
+    QuantArgs qa;
+    memset(&qa, 0, sizeof(qa));
+    qa.x = x; qa.x_dtype = x_dtype; qa.gain = nullptr; qa.eps_norm = 0.f; qa.eps_act = eps_act;
+    qa.M = M; qa.K = K; qa.xq_rowmajor = xq_dbg; qa.absmax_tap = absmax_dbg;
+    if (int rc = launch_act_quant(qa, act, s)) return rc;
+    const WeightSegs w = one_seg(packed, beta, N);
+    return launch_gemm(act, w, M, N, K, y, N, residual, acc_dbg, 0, s);
+}
+
 size_t brl_packed_int8_bytes(int n_out, int k_in) {
     if (n_out < 1 || k_in < 1) return 0;
     return (size_t)round_up(n_out, NB) * (size_t)round_up(k_in, SBK);
