@@ -32,13 +32,18 @@ INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, TOP/s
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
 
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by what
-# the same counters read for a copy kernel of known size); null until measured for the kernel as it stands.
-# encoder-2b: (75 742 KiB FETCH_SIZE x 2.0 + 172 032 KiB WRITE_SIZE x 1.0) per launch of gemm_lds_kernel<2,2,2,4>.
-ROOFLINE_TRAFFIC = {"encoder-2b": 331.3e6, "prefill-3b": None, "rl-states-2b": None}
-# decode pair walk, 16 pairs per launch pair: 35 532.5 KiB FETCH_SIZE x 2.0 per launch against 71.2 MB of
-# packed weights per launch: the batched GEMV fetches 1.02 x its algorithmic bytes (scaled to the pool in use)
-GEMV_BATCH_FETCH_RATIO = 1.022
+# HBM bytes per launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter
+# reads for a copy kernel of known size).  These are NOT measured by a bench run: each entry names the profile
+# summary it was copied from and the kernel it refers to, and is reset to None whenever that kernel changes
+# until the counters have been taken again.
+ROOFLINE_TRAFFIC = {
+    "encoder-2b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
+    "prefill-3b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
+    "rl-states-2b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
+}
+# batched GEMV: fetched bytes / packed-weight bytes per launch, from the same kind of counter run at the pool
+# size the leg uses (None until taken for the kernel and pool as they stand)
+GEMV_BATCH_FETCH = {"ratio": None, "source": None}
 
 
 def linear_macs_per_token(shape) -> int:
@@ -65,6 +70,10 @@ def main() -> int:
     ap.add_argument("--no-ppo", action="store_true")
     ap.add_argument("--no-single-state", action="store_true")
     ap.add_argument("--no-critics", action="store_true", help="skip the int8-weight critic encoder and ensemble legs")
+    ap.add_argument("--no-layer", action="store_true", help="skip the single 16 x 2048 x 2048 BitLinear layer leg")
+    ap.add_argument("--no-ffn", action="store_true", help="skip the 256-token FFN block leg")
+    ap.add_argument("--no-prefill-3b", action="store_true", help="skip the 3B-shape 64 x 512 micro-batch leg")
+    ap.add_argument("--gemv-pool", type=int, default=256, help="distinct weight-pair buffers the GEMV legs walk")
     ap.add_argument("--cpu-sample-states", type=int, default=2)
     ap.add_argument("--gemv-calls", type=int, default=1000)
     ap.add_argument("--streams", type=int, default=1,
@@ -178,7 +187,8 @@ def main() -> int:
     all_gemm_ops = gemm["int8_ops_per_step"] + classes["gemm_narrow"]["int8_ops_per_step"]
     roofline = {"bound": "mfma", "kernel": "gemm_lds_kernel<2,2,2,4> (int8 MFMA BitLinear, 128x256 tile)",
                 "achieved": round(achieved_tops, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                "frac": round(achieved_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": ROOFLINE_TRAFFIC.get(args.workload),
+                "frac": round(achieved_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": ROOFLINE_TRAFFIC[args.workload]["bytes"],
+                "traffic_source": ROOFLINE_TRAFFIC[args.workload]["source"],
                 "avg_launch_ms": round(gemm_avg_ms, 5), "launches_per_step": gemm_launches,
                 "ops_per_launch": ops_per_launch,
                 "all_bitlinear_gemms": {"ms_per_step": round(all_gemm_ms, 4),
@@ -219,7 +229,15 @@ def main() -> int:
     # ---- 1-token GEMV pair (decode shape), 1000 calls
     gemv = None
     if not args.no_gemv:
-        gemv = bench_gemv(torch, B, R, synth, args.gemv_calls)
+        gemv = bench_gemv(torch, B, R, synth, args.gemv_calls, args.gemv_pool)
+
+    # ---- the single BitLinear layer (16 x 2048 x 2048) and the 256-token FFN block of the workload list
+    layer = None
+    if not args.no_layer and args.workload == "encoder-2b":
+        layer = bench_layer(torch, B, R, synth)
+    ffn = None
+    if not args.no_ffn and args.workload == "encoder-2b":
+        ffn = bench_ffn(torch, B, R, synth)
 
     # ---- one short state per call (the paper's deployment shape: a 15-40 token state per environment step)
     single = None
@@ -268,6 +286,13 @@ def main() -> int:
                          % (ns, Bn, "/".join(str(int(n)) for n in lens[:ns]) if packed else str(S), n_layers),
                "seconds": round(cpu_s, 2), "min_cosine_gpu_vs_oracle": round(min(cosines), 6)}
 
+    # ---- one 64-state x 512-token micro-batch of the 3B-shape prefill (1 of the 16 the 1024-state workload makes)
+    prefill = None
+    if not args.no_prefill_3b and args.workload == "encoder-2b":
+        del enc
+        torch.cuda.empty_cache()
+        prefill = bench_prefill_3b(torch, B, R, synth, np)
+
     out = {
         "metric": "encoded RL states/sec at %s shape (BitLinear int8 TOPS as %% of roofline alongside)"
                   % ("3B" if args.workload == "prefill-3b" else "2B"),
@@ -285,6 +310,9 @@ def main() -> int:
         "kernel_classes_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in classes.items()},
         "linear_tops_wall": round(ops_step / (ms_per_step * 1e-3) / 1e12, 2),
         "int8_ceiling_states_per_s": round(Bn / (ops_step / (INT8_MFMA_PEAK_TOPS * 1e12)), 1),
+        "bitlinear_layer_16x2048x2048": layer,
+        "ffn_block_256_tokens": ffn,
+        "prefill_3b_microbatch": prefill,
         "gemv_pair": gemv,
         "single_state_latency": single,
         "ppo_head_update": ppo,
@@ -296,6 +324,146 @@ def main() -> int:
     }
     print(json.dumps(out))
     return 0
+
+
+def _drain_timing(B):
+    for k in range(len(B.KERNEL_CLASSES)):
+        B.brl_timing_read(k)
+
+
+def bench_layer(torch, B, R, synth, calls: int = 200):
+    """One BitLinear layer, W 2048 x 2048 ~ N(0, 0.02) ternarised, X 16 x 2048 ~ N(0, 1) fp32 (seed 0): two launches
+    (per-token quantisation, few-token MFMA kernel).  Far too small for either roofline (1 MB of weights, 0.13 GOP):
+    a latency figure."""
+    n = k = 2048
+    m = 16
+    c = synth.bitlinear_case(0, n, k, m)
+    pl = R.quantize_linear(c["W"])
+    x = R.dev(c["X"])
+    y = torch.empty((m, n), dtype=torch.float32, device="cuda")
+    ws = R.Workspace(B.brl_bitlinear_workspace_bytes(m, n, k))
+
+    def call():
+        B.bitlinear_forward(pl.packed, pl.beta, n, k, x, m, 1e-5, y, None, None, None, None, ws.buf)
+
+    for _ in range(20):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(calls):
+        call()
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t0) / calls * 1e6
+    _drain_timing(B)
+    B.brl_timing_enable(True)
+    for _ in range(calls):
+        call()
+    torch.cuda.synchronize()
+    B.brl_timing_enable(False)
+    nq, qms = B.brl_timing_read(B.BRL_KC_ACT_QUANT)
+    ng, gms, ops = B.brl_timing_read_ops(B.BRL_KC_GEMM_NARROW)
+    _drain_timing(B)
+    gemm_us = gms / max(ng, 1) * 1e3
+    return {"workload": "W 2048x2048 ternary, X 16x2048 fp32, seed 0", "calls": calls,
+            "wall_us_per_call": round(wall_us, 3), "quant_kernel_us": round(qms / max(nq, 1) * 1e3, 3),
+            "gemm_kernel_us": round(gemm_us, 3), "int8_ops": 2.0 * m * n * k,
+            "gemm_tops": round(2.0 * m * n * k / (gemm_us * 1e-6) / 1e12, 3) if gemm_us > 0 else 0.0,
+            "note": "latency bound: 1.05 MB of packed weights and 0.134 GOP are below 0.2 us at either roofline"}
+
+
+def bench_ffn(torch, B, R, synth, calls: int = 200, m: int = 256, d: int = 2560, f: int = 6912):
+    """One 2B-shape FFN block on 256 tokens: RMSNorm -> gate | up BitLinear -> squared-ReLU GLU -> sub-layer norm ->
+    down BitLinear + residual, bf16-valued input (seed 0).  Whole-block time and the int8 rate over its GEMM
+    launches (2 M (2 f d + d f) = 27.2 GOP)."""
+    c = synth.ffn_case(0, m, d, f)
+    h = R.FFNHandle(c["norm_g"], c["W_gate"], c["W_up"], c["subln_g"], c["W_down"])
+    x = R.bf16_from_bits(c["x_bf16"])
+    y = torch.empty((m, d), dtype=torch.float32, device="cuda")
+    ws = R.Workspace(B.brl_ffn_workspace_bytes(m, d, f))
+
+    def call():
+        B.ffn_block_forward(h.struct, x, m, d, f, 1e-5, 1e-5, y, ws.buf)
+
+    for _ in range(20):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(calls):
+        call()
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t0) / calls * 1e6
+    _drain_timing(B)
+    B.brl_timing_enable(True)
+    for _ in range(calls):
+        call()
+    torch.cuda.synchronize()
+    B.brl_timing_enable(False)
+    per = {}
+    gemm_ms, gemm_ops, gemm_n = 0.0, 0.0, 0
+    for kc, name in enumerate(B.KERNEL_CLASSES):
+        n, ms, ops = B.brl_timing_read_ops(kc)
+        if n:
+            per[name] = {"launches_per_call": n / calls, "us_per_call": round(ms / calls * 1e3, 3)}
+        if name in ("gemm", "gemm_narrow"):
+            gemm_ms += ms
+            gemm_ops += ops
+            gemm_n += n
+    gemm_us = gemm_ms / calls * 1e3
+    tops = gemm_ops / calls / (gemm_us * 1e-6) / 1e12 if gemm_us > 0 else 0.0
+    return {"workload": "RMSNorm(2560) -> gate|up 2560->6912 -> sq-ReLU GLU -> subLN(6912) -> down 6912->2560 + residual; "
+                        "256 tokens, bf16-valued input, seed 0",
+            "calls": calls, "wall_us_per_block": round(wall_us, 3), "kernel_classes": per,
+            "gemm_us_per_block": round(gemm_us, 3), "gemm_launches_per_block": gemm_n / calls,
+            "int8_ops_per_block": gemm_ops / calls,
+            "roofline": {"bound": "mfma", "kernel": "the BitLinear GEMM launches of the block (gate|up with the GLU epilogue, down)",
+                         "achieved": round(tops, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                         "frac": round(tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None}}
+
+
+def bench_prefill_3b(torch, B, R, synth, np, states: int = 64, tokens: int = 512, steps: int = 5, warmup: int = 2):
+    """The 3B-shape large-batch prefill, one micro-batch: 64 states x 512 tokens (32 768 token rows) is what one pass
+    of encoder_forward works on at a time; the 1024-state workload is 16 of these back to back
+    (`--workload prefill-3b` times all 16)."""
+    shape = synth.SHAPE_3B
+    t0 = time.time()
+    enc = R.EncoderHandle(shape, seed=0)
+    ids = R.dev(synth.token_ids(0, 500, (states, tokens), shape.vocab))
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+    for _ in range(warmup):
+        enc.forward(ids)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        enc.forward(ids)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    _drain_timing(B)
+    B.brl_timing_enable(True)
+    for _ in range(steps):
+        enc.forward(ids)
+    torch.cuda.synchronize()
+    B.brl_timing_enable(False)
+    per = {}
+    gemm_ms, gemm_ops = 0.0, 0.0
+    for kc, name in enumerate(B.KERNEL_CLASSES):
+        n, kms, ops = B.brl_timing_read_ops(kc)
+        if n:
+            per[name] = round(kms / steps, 3)
+        if name in ("gemm", "gemm_narrow"):
+            gemm_ms += kms
+            gemm_ops += ops
+    ops_step = 2.0 * linear_macs_per_token(shape) * states * tokens
+    tops = gemm_ops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    return {"workload": "3B shape: 26 layers, hidden 3200, 32 heads of 100, FFN 8640, vocab 32000; ONE micro-batch of "
+                        "%d states x %d tokens (1 of the 16 micro-batches of the 1024-state prefill), seed 0" % (states, tokens),
+            "steps": steps, "ms_per_microbatch": round(ms, 3), "states_per_s": round(states / ms * 1e3, 1),
+            "int8_ops_per_microbatch": ops_step, "linear_tops_wall": round(ops_step / (ms * 1e-3) / 1e12, 2),
+            "kernel_classes_ms": per,
+            "roofline": {"bound": "mfma", "kernel": "all BitLinear GEMM launches of the micro-batch", "achieved": round(tops, 2),
+                         "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(tops / INT8_MFMA_PEAK_TOPS, 4),
+                         "traffic": None},
+            "setup_seconds": round(setup_s, 1)}
 
 
 def bench_single_state(torch, B, R, synth, np, enc, head, shape, n_tokens: int = 27, calls: int = 50):
@@ -515,19 +683,23 @@ def bench_ppo(torch, B, R, synth, np, shape, want_cpu: bool, T: int = 2048, batc
     return out
 
 
-def bench_gemv(torch, B, R, synth, calls: int):
-    """Decode-shape pair x[1,2560] -> up[6912] -> down[2560]: streaming over a pool of
-    distinct weight pairs larger than the on-chip caches, and resident on one pair."""
+def bench_gemv(torch, B, R, synth, calls: int, n_pairs: int = 256, n_drawn: int = 8):
+    """Decode-shape pair x[1,2560] -> up[6912] -> down[2560]: streaming over a pool of weight-pair buffers several
+    times larger than the on-chip caches, and resident on one pair.  The first n_drawn pairs are seeded Philox draws
+    (synth.gemv_pair_case, ternarised and packed by the library); the rest of the pool are device copies of their
+    packed blobs in buffers of their own: what a streaming kernel sees is addresses and bit statistics, and host
+    draws of 256 pairs (9 G normals) would take minutes."""
     d, f = 2560, 6912
-    n_pairs = 64
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(0)
-    pairs = []
-    for _ in range(n_pairs):
-        wu = torch.randn((f, d), generator=gen, device="cuda", dtype=torch.float32) * 0.02
-        wd = torch.randn((d, f), generator=gen, device="cuda", dtype=torch.float32) * 0.02
-        pairs.append((R.quantize_linear(wu), R.quantize_linear(wd)))
-        del wu, wd
+    from paper_2604_24273_amd.runtime import PackedLinear
+    drawn = []
+    for i in range(min(n_drawn, n_pairs)):
+        c = synth.gemv_pair_case(0, d, f, pair=i)
+        drawn.append((R.quantize_linear(c["W_up"]), R.quantize_linear(c["W_down"])))
+    pairs = list(drawn)
+    while len(pairs) < n_pairs:
+        up, dn = drawn[len(pairs) % len(drawn)]
+        pairs.append((PackedLinear(up.packed.clone(), up.beta.clone(), up.n_out, up.k_in),
+                      PackedLinear(dn.packed.clone(), dn.beta.clone(), dn.n_out, dn.k_in)))
     x = R.dev(synth.normal(0, 10, (1, d)))
     h = torch.empty((1, f), dtype=torch.float32, device="cuda")
     y = torch.empty((1, d), dtype=torch.float32, device="cuda")
@@ -540,8 +712,10 @@ def bench_gemv(torch, B, R, synth, calls: int):
             B.bitlinear_forward(up.packed, up.beta, f, d, x, 1, 1e-5, h, None, None, None, None, ws.buf)
             B.bitlinear_forward(dn.packed, dn.beta, d, f, h, 1, 1e-5, y, None, None, None, None, ws.buf)
 
-    res = {"bytes_per_pair": bytes_pair, "calls": calls, "pool_pairs": n_pairs,
-           "pool_bytes": n_pairs * 2 * B.brl_packed_bytes(f, d)}
+    res = {"bytes_per_pair": bytes_pair, "calls": calls, "pool_pairs": n_pairs, "pool_pairs_drawn": len(drawn),
+           "pool_bytes": n_pairs * 2 * B.brl_packed_bytes(f, d),
+           "bytes_walked_per_batched_launch": min(calls, n_pairs) * B.brl_packed_bytes(f, d),
+           "last_level_cache_bytes": 256 * 2 ** 20}
     for mode, pool_size in (("streaming", n_pairs), ("resident", 1)):
         run(pool_size, 50)
         torch.cuda.synchronize()
@@ -607,7 +781,9 @@ def bench_gemv(torch, B, R, synth, calls: int):
     res["roofline"] = {"bound": "hbm", "kernel": "gemv_batch_kernel<1> (all pairs of the pool walk in two launches)",
                        "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(gbs / HBM_PEAK_GBS, 4),
-                       "traffic": round(GEMV_BATCH_FETCH_RATIO * calls * bytes_pair / 2)}
+                       "traffic": None if GEMV_BATCH_FETCH["ratio"] is None
+                       else round(GEMV_BATCH_FETCH["ratio"] * calls * bytes_pair / 2),
+                       "traffic_source": GEMV_BATCH_FETCH["source"]}
     return res
 
 

@@ -403,6 +403,13 @@ int value_ensemble_forward(const brl_mlp* members /* HOST */, int n_members, con
  * [epochs * (T / batch), 5] = policy loss, value loss, mean entropy, fraction
  * of clipped samples, gradient norm before clipping.  Sums run in fp64 in a
  * fixed order: the result does not depend on scheduling.
+ * perm entries must lie in [0, T) and actions in [0, A): they are read on the
+ * device only and clamped into range there (an entry outside the range gives a
+ * meaningless update, never an out-of-bounds access).
+ * The Adam bias corrections of each optimiser step are computed on the HOST
+ * from *adam_step and passed to the kernels by value: do not capture
+ * ppo_head_update into a HIP graph - a replay would reuse the corrections (and
+ * step count) of the captured call.
  * ------------------------------------------------------------------------ */
 typedef struct brl_ppo_config {
     int policy_layers;            /* 1..8 weight matrices */

@@ -63,7 +63,8 @@ def build_microbench(verbose: bool = False) -> None:
     out = os.path.join(MICRO, "bin")
     os.makedirs(out, exist_ok=True)
     for name in ("mfma_i8_peak", "stream_copy"):
-        cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-o", os.path.join(out, name), os.path.join(MICRO, name + ".hip")]
+        cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-o", os.path.join(out, name), os.path.join(MICRO, name + ".hip")]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (name, r.stderr[-4000:]))

@@ -876,15 +876,15 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64, two workgroups per CU) or 128 x 128 tiles
     // (4 wavefronts, four per CU).  The wide tile does about 5 % more work per unit time; the narrow
     // one wins when it spreads the tiles more evenly over the compute units.
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
+    static const int cus = [] {        // initialised once, thread-safe
+        int dev = 0, n = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
             (void)hipGetLastError();
-            cus = 256;
+            n = 256;
         }
-    }
+        return n;
+    }();
     const long t_wide = (long)((g.nmb + 3) / 4) * ((g.nnb + 7) / 8);
     const long t_narrow = (long)((g.nmb + 3) / 4) * ((g.nnb + 3) / 4);
     const double fill_wide = (double)t_wide / (double)(((t_wide + cus - 1) / cus) * cus);

@@ -91,6 +91,10 @@ __global__ void gae_kernel(const float* __restrict__ rewards, const float* __res
 // samples (weight rows and inputs are read once for all of them); its four wavefronts take a quarter of the
 // inputs each, sum in fp64 in lane order, fold, and the four parts are added in order.
 // in(b, i) = in64[b, i], or for the first layer the cached encoder output h[rows[b], i].
+// Rollout indices and actions are caller data read on the device: they are clamped into range so that a bad
+// entry can never address memory outside the rollout or the logits (its result is then meaningless, not a fault).
+__device__ inline int clamp_index(int v, int n) { return v < 0 ? 0 : (v >= n ? n - 1 : v); }
+
 constexpr int FB = 4;        // samples per workgroup
 constexpr int FO = 4;        // output units per workgroup
 // One launch runs the same layer level of both heads (they read the same rows of h and depend on nothing of
@@ -108,7 +112,7 @@ struct FwdArgs {
     int n;                   // 1 or 2 problems
     const float* h;
     const int32_t* rows;
-    int B, act;
+    int B, act, T;
 };
 __global__ __launch_bounds__(256) void ppo_forward_kernel(FwdArgs a) {
     const int which = (a.n > 1 && blockIdx.x >= a.p[0].blocks) ? 1 : 0;
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(256) void ppo_forward_kernel(FwdArgs a) {
 #pragma unroll
     for (int q = 0; q < FB; ++q) {
         const int b = min(bg * FB + q, B - 1);
-        hrow[q] = in64 ? nullptr : h + (size_t)rows[b] * in_dim;
+        hrow[q] = in64 ? nullptr : h + (size_t)clamp_index(rows[b], a.T) * in_dim;
         drow[q] = in64 ? in64 + (size_t)b * in_dim : nullptr;
     }
     const int quarter = (in_dim + 3) / 4;
@@ -193,7 +197,7 @@ struct LossArgs {
     const float* logp_old;
     const float* adv;
     const float* returns;
-    int B, A;
+    int B, A, T;
     double clip_eps, ent_coef, adv_eps;
     int normalize_adv;
     double* dlogits;          // [B, A]
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
     if (a.normalize_adv) {
         // mean and (n - 1) standard deviation over the mini-batch: strided partial sums, then a fixed tree
         double part = 0.0;
-        for (int b = threadIdx.x; b < a.B; b += 256) part += (double)a.adv[a.rows[b]];
+        for (int b = threadIdx.x; b < a.B; b += 256) part += (double)a.adv[clamp_index(a.rows[b], a.T)];
         red[threadIdx.x] = part;
         __syncthreads();
         for (int st = 128; st >= 1; st >>= 1) {
@@ -221,7 +225,7 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
         __syncthreads();
         part = 0.0;
         for (int b = threadIdx.x; b < a.B; b += 256) {
-            const double d = (double)a.adv[a.rows[b]] - mean;
+            const double d = (double)a.adv[clamp_index(a.rows[b], a.T)] - mean;
             part += d * d;
         }
         red[threadIdx.x] = part;
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
         const int b = b0 + (int)threadIdx.x / LG;
         const bool live = b < a.B;
         const int bc = live ? b : a.B - 1;              // idle lanes shadow the last sample and store nothing
-        const int r = a.rows[bc];
+        const int r = clamp_index(a.rows[bc], a.T);
         const double A = ((double)a.adv[r] - s_mean) * s_inv;
         const double* z = a.logits + (size_t)bc * a.A;
         double m = z[0];
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(256) void ppo_loss_kernel(LossArgs a) {
 #pragma unroll
         for (int off = 1; off < LG; off <<= 1) se += __shfl_xor(se, off, 64);
         const double lse = m + log(se);
-        const int act = a.actions[r];
+        const int act = clamp_index(a.actions[r], a.A);
         const double logp = z[act] - lse;
         const double ratio = exp(logp - (double)a.logp_old[r]);
         const double surr1 = ratio * A;
@@ -325,7 +329,7 @@ struct GradArgs {
     int n;
     const float* h;
     const int32_t* rows;
-    int B;
+    int B, T;
 };
 __global__ __launch_bounds__(256) void ppo_weight_grad_kernel(GradArgs a) {
     const int which = (a.n > 1 && blockIdx.x >= a.p[0].blocks) ? 1 : 0;
@@ -353,7 +357,7 @@ __global__ __launch_bounds__(256) void ppo_weight_grad_kernel(GradArgs a) {
     for (int q = 0; q < GO; ++q) { acc[q] = 0.0; accb[q] = 0.0; }
 #pragma unroll 8
     for (int b = 0; b < B; ++b) {
-        const double x = in64 ? in64[(size_t)b * in_dim + ii] : (double)h[(size_t)rows[b] * in_dim + ii];
+        const double x = in64 ? in64[(size_t)b * in_dim + ii] : (double)h[(size_t)clamp_index(rows[b], a.T) * in_dim + ii];
 #pragma unroll
         for (int q = 0; q < GO; ++q) {
             const double d = delta[(size_t)b * out_dim + min(o0 + q, out_dim - 1)];
@@ -576,7 +580,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
             for (int l = 0; l < depth; ++l) {
                 FwdArgs fa;
                 memset(&fa, 0, sizeof(fa));
-                fa.h = h; fa.rows = rows; fa.B = batch; fa.act = cfg->act;
+                fa.h = h; fa.rows = rows; fa.B = batch; fa.act = cfg->act; fa.T = T;
                 unsigned blocks = 0;
                 for (int hd = 0; hd < 2; ++hd) {
                     const HeadShape& H = L.head[hd];
@@ -597,7 +601,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
             la.logits = reinterpret_cast<const double*>(base + W.act_off[0][L.head[0].n - 1]);
             la.v = reinterpret_cast<const double*>(base + W.act_off[1][L.head[1].n - 1]);
             la.rows = rows; la.actions = actions; la.logp_old = logp_old; la.adv = adv; la.returns = returns;
-            la.B = batch; la.A = A;
+            la.B = batch; la.A = A; la.T = T;
             la.clip_eps = (double)cfg->clip_eps; la.ent_coef = (double)cfg->ent_coef; la.adv_eps = (double)cfg->adv_eps;
             la.normalize_adv = cfg->normalize_adv;
             la.dlogits = delta[0][0];
@@ -614,7 +618,7 @@ int ppo_head_update(const brl_ppo_config* cfg, float* params, float* adam_m, flo
                 DeltaArgs da;
                 memset(&ga, 0, sizeof(ga));
                 memset(&da, 0, sizeof(da));
-                ga.h = h; ga.rows = rows; ga.B = batch;
+                ga.h = h; ga.rows = rows; ga.B = batch; ga.T = T;
                 da.B = batch; da.act = cfg->act;
                 unsigned gblocks = 0, dblocks = 0;
                 const double* dnext[2] = {dcur[0], dcur[1]};
