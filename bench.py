@@ -73,7 +73,9 @@ def main() -> int:
     ap.add_argument("--no-layer", action="store_true", help="skip the single 16 x 2048 x 2048 BitLinear layer leg")
     ap.add_argument("--no-ffn", action="store_true", help="skip the 256-token FFN block leg")
     ap.add_argument("--no-prefill-3b", action="store_true", help="skip the 3B-shape 64 x 512 micro-batch leg")
-    ap.add_argument("--gemv-pool", type=int, default=256, help="distinct weight-pair buffers the GEMV legs walk")
+    ap.add_argument("--gemv-pool", type=int, default=None,
+                    help="distinct weight-pair buffers the GEMV legs walk (default: one per call, so that a batched "
+                         "launch reads every weight byte exactly once and nothing can come out of a cache)")
     ap.add_argument("--cpu-sample-states", type=int, default=2)
     ap.add_argument("--gemv-calls", type=int, default=1000)
     ap.add_argument("--streams", type=int, default=1,
@@ -229,7 +231,7 @@ def main() -> int:
     # ---- 1-token GEMV pair (decode shape), 1000 calls
     gemv = None
     if not args.no_gemv:
-        gemv = bench_gemv(torch, B, R, synth, args.gemv_calls, args.gemv_pool)
+        gemv = bench_gemv(torch, B, R, synth, args.gemv_calls, args.gemv_pool or args.gemv_calls)
 
     # ---- the single BitLinear layer (16 x 2048 x 2048) and the 256-token FFN block of the workload list
     layer = None
@@ -684,11 +686,12 @@ def bench_ppo(torch, B, R, synth, np, shape, want_cpu: bool, T: int = 2048, batc
 
 
 def bench_gemv(torch, B, R, synth, calls: int, n_pairs: int = 256, n_drawn: int = 8):
-    """Decode-shape pair x[1,2560] -> up[6912] -> down[2560]: streaming over a pool of weight-pair buffers several
-    times larger than the on-chip caches, and resident on one pair.  The first n_drawn pairs are seeded Philox draws
+    """Decode-shape pair x[1,2560] -> up[6912] -> down[2560]: streaming over a pool of weight-pair buffers (by
+    default one pair per call: 8.8 GB, every weight byte is read once per batched launch and the 256 MB last-level
+    cache cannot serve any of it), and resident on one pair.  The first n_drawn pairs are seeded Philox draws
     (synth.gemv_pair_case, ternarised and packed by the library); the rest of the pool are device copies of their
     packed blobs in buffers of their own: what a streaming kernel sees is addresses and bit statistics, and host
-    draws of 256 pairs (9 G normals) would take minutes."""
+    draws of 1000 pairs (35 G normals) would take many minutes."""
     d, f = 2560, 6912
     from paper_2604_24273_amd.runtime import PackedLinear
     drawn = []

@@ -183,7 +183,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GemvArgs g) {
 // i % nwg of problem i / nwg.  A persistent workgroup takes a contiguous run of items and
 // quantises the activations of a problem once (into LDS) for all of that problem's row
 // blocks it owns.  Inside a problem every wavefront owns whole row blocks: it streams the
-// block's packed weights in chunks of GB_CH super-blocks, the next chunk (also across
+// block's packed weights in chunks of CH super-blocks (CH chosen to divide k evenly where it can), the next chunk (also across
 // row blocks) requested before the current one is contracted, and finishes the 32 rows by
 // itself - no partial sums cross wavefronts and no barrier is met until the problem changes.
 // ---------------------------------------------------------------------------
@@ -197,55 +197,68 @@ struct GemvBatchArgs {
     float eps_act;
 };
 
-constexpr int GB_CH = 4;          // super-blocks (1 KB wavefront loads) per chunk
+// CH = super-blocks (1 KB wavefront loads) per chunk: 4, 5 or 6
 
-__device__ inline void gb_request(const uint4* blk, int c, int nsb, int lane, uint4 (&w)[GB_CH]) {
+// Loads are unconditional (super-blocks past the end of k are clamped to the last one and never
+// contracted): with straight-line requests the compiler can count the loads still in flight and
+// waits only for the chunk it is about to contract, not for the one just requested.  The weight
+// pointers come out of a device array, so they are marked as global memory by hand: generic
+// (flat) loads would tie the vector-memory and LDS counters together and force full waits.
+typedef unsigned int gb_u32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) gb_u32x4* gb_wptr;
+template <int CH>
+__device__ inline void gb_request(gb_wptr blk, int c, int nsb, uint4 (&w)[CH]) {
 #pragma unroll
-    for (int u = 0; u < GB_CH; ++u) {
-        const int sb = c * GB_CH + u;
-        if (sb < nsb) w[u] = blk[(size_t)sb * 64 + lane];
+    for (int u = 0; u < CH; ++u) {
+        const int sb = min(c * CH + u, nsb - 1);
+        const gb_u32x4 v = blk[(size_t)sb * 64];
+        w[u] = make_uint4(v.x, v.y, v.z, v.w);
     }
 }
 
-template <int MT>
-__device__ inline void gb_contract(const uint4 (&w)[GB_CH], int c, int nsb, int hh, const int (*xq)[MAX_K / 4],
-                                   int (&acc)[MT]) {
+// No conditions here either: the activations in LDS are zero from the end of k up to a whole number of
+// chunks, so the clamped super-blocks of the last chunk contribute nothing.
+template <int MT, int CH>
+__device__ inline void gb_contract(const uint4 (&w)[CH], int c, int hh, const int (*xq)[MAX_K / 4], int (&acc)[MT]) {
 #pragma unroll
-    for (int u = 0; u < GB_CH; ++u) {
-        const int sb = c * GB_CH + u;
-        if (sb < nsb) {
-            const uint32_t wd[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+    for (int u = 0; u < CH; ++u) {
+        const int sb = c * CH + u;
+        const uint32_t wd[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
 #pragma unroll
-            for (int dd = 0; dd < 4; ++dd) {
-                const uint32_t pw = wd[dd];
-                const int c0 = (int)(pw & 0x03030303u), c1 = (int)((pw >> 2) & 0x03030303u);
-                const int c2 = (int)((pw >> 4) & 0x03030303u), c3 = (int)((pw >> 6) & 0x03030303u);
-                const int xoff = (sb * 128 + dd * 32 + hh * 16) / 4;
+        for (int dd = 0; dd < 4; ++dd) {
+            const uint32_t pw = wd[dd];
+            const int c0 = (int)(pw & 0x03030303u), c1 = (int)((pw >> 2) & 0x03030303u);
+            const int c2 = (int)((pw >> 4) & 0x03030303u), c3 = (int)((pw >> 6) & 0x03030303u);
+            const int xoff = (sb * 128 + dd * 32 + hh * 16) / 4;
 #pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    const int4 xw = *reinterpret_cast<const int4*>(&xq[t][xoff]);
-                    acc[t] = __builtin_amdgcn_sdot4(c0, xw.x, acc[t], false);
-                    acc[t] = __builtin_amdgcn_sdot4(c1, xw.y, acc[t], false);
-                    acc[t] = __builtin_amdgcn_sdot4(c2, xw.z, acc[t], false);
-                    acc[t] = __builtin_amdgcn_sdot4(c3, xw.w, acc[t], false);
-                }
+            for (int t = 0; t < MT; ++t) {
+                const int4 xw = *reinterpret_cast<const int4*>(&xq[t][xoff]);
+                acc[t] = __builtin_amdgcn_sdot4(c0, xw.x, acc[t], false);
+                acc[t] = __builtin_amdgcn_sdot4(c1, xw.y, acc[t], false);
+                acc[t] = __builtin_amdgcn_sdot4(c2, xw.z, acc[t], false);
+                acc[t] = __builtin_amdgcn_sdot4(c3, xw.w, acc[t], false);
             }
         }
     }
 }
 
-template <int MT>
+template <int MT, int CH>
 __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g) {
-    __shared__ __attribute__((aligned(16))) int xq[MT][MAX_K / 4];
+    __shared__ __attribute__((aligned(16))) int xq[MT][MAX_K / 4];   // CH = 5 is only launched where it divides k
     __shared__ float wmax[MT][GV_WAVES];
     __shared__ int wsum[MT][GV_WAVES];
+    constexpr int GB_SLOTS = MT == 4 ? 3 : 16 / MT;          // row blocks a wavefront parks before it stores them
+    __shared__ float ypark[GV_WAVES][GB_SLOTS][MT][32];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int K = g.K, Kp = g.nsb * SBK;
+    // the wavefront index as a scalar: everything derived from it (row blocks, cursors, loop bounds) then lives in
+    // scalar registers and branches on it are uniform
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int K = g.K;
     const long items = (long)g.count * g.nwg;
     const long i0 = items * blockIdx.x / gridDim.x, i1 = items * (blockIdx.x + 1) / gridDim.x;
     const int hh = lane >> 5;
-    const int nchunks = (g.nsb + GB_CH - 1) / GB_CH;
+    const int nchunks = (g.nsb + CH - 1) / CH;
+    const int Kc = nchunks * CH * SBK;                       // the xq rows hold a whole number of chunks
 
     long it = i0;
     while (it < i1) {
@@ -257,7 +270,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
         float dsc[MT];                     // a / 127 per token
         int sq[MT];                        // sum_k q per token
         {
-            const void* x = g.x[p];
+            const void* x = (const void*)(const __attribute__((address_space(1))) char*)g.x[p];
             float4 xv[MT][GV_X4];
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
@@ -287,7 +300,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
 #pragma unroll
                 for (int u = 0; u < GV_X4; ++u) {
                     const int k = 4 * ((int)threadIdx.x + GV_THREADS * u);
-                    if (k < Kp) {
+                    if (k < Kc) {          // zeros from K to a whole number of chunks
                         const float4 v = xv[t][u];
                         const int q0 = (int)fminf(fmaxf(rintf(v.x * sc), -127.f), 127.f);
                         const int q1 = (int)fminf(fmaxf(rintf(v.y * sc), -127.f), 127.f);
@@ -310,67 +323,102 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
                 sq[t] = sum;
             }
         }
-        const float beta = *g.beta[p];
-        float* yp = g.y[p];
-        const uint4* wp = g.packed[p];
+        const float beta = *(const __attribute__((address_space(1))) float*)g.beta[p];
+        __attribute__((address_space(1))) float* yp = (__attribute__((address_space(1))) float*)g.y[p];
+        const gb_wptr wp = (gb_wptr)g.packed[p];
 
         // ---- this wavefront's row blocks: it + wave, + 16, ...; a flat walk over (row block, chunk)
         const long first = it + wave;
         const int mine = first < p_end ? (int)((p_end - first + GV_WAVES - 1) / GV_WAVES) : 0;
         const int total = mine * nchunks;
         const int nb_first = (int)(first % g.nwg);              // row blocks of one problem are consecutive
-        uint4 wa[GB_CH], wb[GB_CH];
+        const size_t blk_stride = (size_t)GV_WAVES * g.nsb * 64;
         int acc[MT];
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[t] = 0;
 
-        auto block_of = [&](int q) { return wp + (size_t)(nb_first + (q / nchunks) * GV_WAVES) * g.nsb * 64; };
-        auto finish = [&](int q) {
-            // last chunk of a row block: fold the two k-halves, rescale, store 32 rows per token
-            const int nb = nb_first + (q / nchunks) * GV_WAVES;
-            const int n = nb * 32 + (lane & 31);
+        if (total > 0) {
+            uint4 wa[CH], wb[CH];
+            // request cursor (runs ahead) and contraction cursor over the same (row block, chunk) sequence
+            gb_wptr rq_blk = wp + (size_t)nb_first * g.nsb * 64 + lane;
+            int rq_c = 0, rq_left = total;
+            auto request = [&](uint4 (&w)[CH]) {
+                gb_request<CH>(rq_blk, rq_c, g.nsb, w);
+                if (rq_left > 1) {             // past the end the last chunk is requested again and dropped
+                    --rq_left;
+                    if (++rq_c == nchunks) { rq_c = 0; rq_blk += blk_stride; }
+                }
+            };
+            int cc = 0, nb = nb_first;         // chunk and row block being contracted
+            int slot = 0, nb_slot0 = nb_first; // results parked in LDS: row blocks nb_slot0, + 16, ... (slot of them)
+            // Results go to LDS first and to memory in groups: a store in flight between the weight loads would
+            // make every later wait a wait for everything (loads and stores share one counter).
+            auto flush = [&]() {
+                for (int sl = 0; sl < slot; ++sl) {
+                    const int n = (nb_slot0 + sl * GV_WAVES) * 32 + (lane & 31);
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const int full = acc[t] + __shfl_xor(acc[t], 32, 64);
-                if (lane < 32 && t < g.M && n < g.N) yp[(size_t)t * g.N + n] = ((float)(full - sq[t]) * dsc[t]) * beta;
-                acc[t] = 0;
-            }
-        };
+                    for (int t = 0; t < MT; ++t)
+                        if (lane < 32 && t < g.M && n < g.N) yp[(size_t)t * g.N + n] = ypark[wave][sl][t][lane];
+                }
+                slot = 0;
+            };
+            auto contract = [&](const uint4 (&w)[CH]) {
+                gb_contract<MT, CH>(w, cc, hh, xq, acc);
+                if (++cc == nchunks) {
+                    // last chunk of a row block: fold the two k-halves, rescale, park 32 rows per token
+                    if (slot == 0) nb_slot0 = nb;
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        const int full = acc[t] + __shfl_xor(acc[t], 32, 64);
+                        if (lane < 32) ypark[wave][slot][t][lane] = ((float)(full - sq[t]) * dsc[t]) * beta;
+                        acc[t] = 0;
+                    }
+                    cc = 0;
+                    nb += GV_WAVES;
+                    if (++slot == GB_SLOTS) flush();
+                }
+            };
 
-        if (total > 0) gb_request(block_of(0), 0, g.nsb, lane, wa);
-        for (int q = 0; q < total; q += 2) {
-            if (q + 1 < total) gb_request(block_of(q + 1), (q + 1) % nchunks, g.nsb, lane, wb);
-            gb_contract<MT>(wa, q % nchunks, g.nsb, hh, xq, acc);
-            if (q % nchunks == nchunks - 1) finish(q);
-            if (q + 2 < total) gb_request(block_of(q + 2), (q + 2) % nchunks, g.nsb, lane, wa);
-            if (q + 1 < total) {
-                gb_contract<MT>(wb, (q + 1) % nchunks, g.nsb, hh, xq, acc);
-                if ((q + 1) % nchunks == nchunks - 1) finish(q + 1);
+            request(wa);
+            for (int q = 0; q < total; q += 2) {
+                request(wb);
+                contract(wa);
+                request(wa);
+                if (q + 1 < total) contract(wb);
             }
+            flush();
         }
         it = p_end;
     }
 }
 
-template <int MT>
-int launch_batch_one(const GemvBatchArgs& g, hipStream_t s) {
-    static int slots = 0;            // workgroups the device holds at once
-    if (slots == 0) {
+template <int MT, int CH>
+int launch_batch_ch(const GemvBatchArgs& g, hipStream_t s) {
+    static const int slots = [] {        // workgroups the device holds at once
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_batch_kernel<MT>, GV_THREADS, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_batch_kernel<MT, CH>, GV_THREADS, 0) != hipSuccess ||
             cus <= 0 || per_cu <= 0) {
             (void)hipGetLastError();
             cus = 256;
             per_cu = 1;
         }
-        slots = cus * per_cu;
-    }
+        return cus * per_cu;
+    }();
     const long items = (long)g.count * g.nwg;
     const int grid = (int)(items < slots ? items : slots);
-    hipLaunchKernelGGL(gemv_batch_kernel<MT>, dim3(grid), dim3(GV_THREADS), 0, s, g);
+    hipLaunchKernelGGL((gemv_batch_kernel<MT, CH>), dim3(grid), dim3(GV_THREADS), 0, s, g);
     return BRL_OK;
+}
+
+// chunk length: one that divides the number of super-blocks (no clamped tail loads), else 4
+template <int MT>
+int launch_batch_one(const GemvBatchArgs& g, hipStream_t s) {
+    if (g.nsb % 4 == 0) return launch_batch_ch<MT, 4>(g, s);
+    if (g.nsb % 6 == 0) return launch_batch_ch<MT, 6>(g, s);
+    if (g.nsb % 5 == 0) return launch_batch_ch<MT, 5>(g, s);
+    return launch_batch_ch<MT, 4>(g, s);
 }
 
 }  // namespace

@@ -196,7 +196,10 @@ def test_gemv_pair_decode_shape_repeated():
 
 
 @pytest.mark.parametrize("m,n,k,count,bf16", [(1, 6912, 2560, 9, False), (1, 2560, 6912, 7, False), (3, 100, 200, 5, True),
-                                              (2, 264, 8200, 3, False), (4, 96, 128, 700, False)])
+                                              (2, 264, 8200, 3, False), (4, 96, 128, 700, False),
+                                              # so many row blocks per workgroup that a wavefront stores its parked
+                                              # results more than once per problem
+                                              (4, 400000, 128, 1, False), (2, 300100, 256, 2, True)])
 def test_bitlinear_forward_batch(m, n, k, count, bf16):
     """Many independent few-token problems in one launch: each equals the oracle and the one-problem entry point."""
     B, R = _mods()
