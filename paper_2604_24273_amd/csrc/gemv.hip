@@ -265,6 +265,27 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
         const int p = (int)(it / g.nwg);
         const long p_end = min(i1, (long)(p + 1) * g.nwg);     // this workgroup's items of problem p: [it, p_end)
 
+        // ---- this wavefront's row blocks: it + wave, + 16, ...; a flat walk over (row block, chunk).  The first
+        // chunk does not depend on the activations: it is requested ahead of their quantisation.
+        const gb_wptr wp = (gb_wptr)g.packed[p];
+        const long first = it + wave;
+        const int mine = first < p_end ? (int)((p_end - first + GV_WAVES - 1) / GV_WAVES) : 0;
+        const int total = mine * nchunks;
+        const int nb_first = (int)(first % g.nwg);              // row blocks of one problem are consecutive
+        const size_t blk_stride = (size_t)GV_WAVES * g.nsb * 64;
+        uint4 wa[CH], wb[CH];
+        // request cursor (runs ahead of the contraction cursor over the same sequence)
+        gb_wptr rq_blk = wp + (size_t)nb_first * g.nsb * 64 + lane;
+        int rq_c = 0, rq_left = total;
+        auto request = [&](uint4 (&w)[CH]) {
+            gb_request<CH>(rq_blk, rq_c, g.nsb, w);
+            if (rq_left > 1) {                 // past the end the last chunk is requested again and dropped
+                --rq_left;
+                if (++rq_c == nchunks) { rq_c = 0; rq_blk += blk_stride; }
+            }
+        };
+        if (total > 0) request(wa);
+
         // ---- quantise the activations of problem p into LDS
         __syncthreads();                   // every wavefront is done with the previous problem's xq
         float dsc[MT];                     // a / 127 per token
@@ -325,30 +346,11 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
         }
         const float beta = *(const __attribute__((address_space(1))) float*)g.beta[p];
         __attribute__((address_space(1))) float* yp = (__attribute__((address_space(1))) float*)g.y[p];
-        const gb_wptr wp = (gb_wptr)g.packed[p];
-
-        // ---- this wavefront's row blocks: it + wave, + 16, ...; a flat walk over (row block, chunk)
-        const long first = it + wave;
-        const int mine = first < p_end ? (int)((p_end - first + GV_WAVES - 1) / GV_WAVES) : 0;
-        const int total = mine * nchunks;
-        const int nb_first = (int)(first % g.nwg);              // row blocks of one problem are consecutive
-        const size_t blk_stride = (size_t)GV_WAVES * g.nsb * 64;
         int acc[MT];
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[t] = 0;
 
         if (total > 0) {
-            uint4 wa[CH], wb[CH];
-            // request cursor (runs ahead) and contraction cursor over the same (row block, chunk) sequence
-            gb_wptr rq_blk = wp + (size_t)nb_first * g.nsb * 64 + lane;
-            int rq_c = 0, rq_left = total;
-            auto request = [&](uint4 (&w)[CH]) {
-                gb_request<CH>(rq_blk, rq_c, g.nsb, w);
-                if (rq_left > 1) {             // past the end the last chunk is requested again and dropped
-                    --rq_left;
-                    if (++rq_c == nchunks) { rq_c = 0; rq_blk += blk_stride; }
-                }
-            };
             int cc = 0, nb = nb_first;         // chunk and row block being contracted
             int slot = 0, nb_slot0 = nb_first; // results parked in LDS: row blocks nb_slot0, + 16, ... (slot of them)
             // Results go to LDS first and to memory in groups: a store in flight between the weight loads would
@@ -379,7 +381,6 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_batch_kernel(GemvBatchArgs g)
                 }
             };
 
-            request(wa);
             for (int q = 0; q < total; q += 2) {
                 request(wb);
                 contract(wa);
