@@ -1,7 +1,7 @@
 // Per-token absmax int8 activation quantisation, with the RMSNorm / sub-layer
-// norm that sits in front of it in the blocks fused in.  A token row is kept in the
-// registers of the 2 or 4 wavefronts that share it, so it is read from HBM once:
-// statistic, absmax and the quantised values all come from the same registers.
+// norm that sits in front of it in the blocks fused in.  A token row is kept in
+// registers, so it is read from HBM once: statistic, absmax and the quantised
+// values all come from the same registers.
 //
 //   (norm)  r = fp32(1 / sqrt(mean_k x_k^2 + eps_n))  [fp64 statistic];  x_k <- (x_k * r) * gain_k
 //   a = max(max_k |x_k|, eps);  s = 127 / a;  q_k = clamp(rne(x_k * s), -127, 127)
@@ -9,20 +9,21 @@
 // Output goes to the tiled int8 layout the MFMA GEMM reads (see common.hpp),
 // plus per-token a, a / 127 and sum_k q_k.  In that layout 16 consecutive k of
 // one token are 16 bytes, and the same 16 k of the next token follow directly:
-// a workgroup therefore takes 8 consecutive tokens at a time, parks their int8 rows
-// in LDS and writes the tile out in full 128-byte runs.  The workgroups are
-// persistent and request the rows of their next tokens before working on the
-// current ones, so that HBM stays busy through the reductions and the write-out.
-// With at most 1024 tokens the time is latency, not bandwidth: act_quant_row_kernel takes one
-// token per workgroup instead.
+// a workgroup therefore takes 8 or 16 consecutive tokens at a time, parks their
+// int8 rows in LDS and writes the tile out in runs of 128 or 256 bytes.
+//
+// Three kernels:
+//   act_quant_wave_kernel  many tokens, rows up to 6912 wide: one wavefront per token
+//   act_quant_kernel       many tokens, wider rows: four wavefronts per token, LDS reductions
+//   act_quant_row_kernel   up to 1024 tokens (latency, not bandwidth): one workgroup per token
 #include "common.hpp"
 
 namespace brl {
 
 namespace {
 
-constexpr int AQ_ROWS = 8;                 // tokens per workgroup
-constexpr int AQ_THREADS = AQ_ROWS * 128;  // two wavefronts per token: each keeps half of the row in registers
+// The persistent kernel runs NWV wavefronts per workgroup (8: two workgroups share a compute unit and
+// one computes while the other waits on memory or a barrier; 16: one workgroup per unit).
 
 struct QK {
     const void* x;
@@ -67,16 +68,17 @@ __device__ inline void load_rows(const QK& a, int row, int lane, int part, float
     }
 }
 
-// The 16 wavefronts of a workgroup take 16 / WPT tokens per round; WPT / 2 rounds fill the 8-token
-// group that is written out together.  A workgroup walks the groups g = blockIdx.x, + gridDim.x, ...
-// and requests the rows of its next round before it works on the current one.
-template <int HV4, int WPT, int GR>
-__global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
-    constexpr int TPR = 16 / WPT;          // tokens per round
+// The NWV wavefronts of a workgroup take NWV / WPT tokens per round; GR / (NWV / WPT) rounds fill the
+// group of GR tokens that is written out together.  A workgroup walks the groups g = blockIdx.x,
+// + gridDim.x, ... and requests the rows of its next round before it works on the current one.
+template <int HV4, int WPT, int GR, int NWV>
+__global__ __launch_bounds__(NWV * 64) void act_quant_kernel(QK a) {
+    constexpr int AQ_THREADS = NWV * 64;
+    constexpr int TPR = NWV / WPT;         // tokens per round
     constexpr int RPG = GR / TPR;          // rounds per group of GR tokens that is written out together
-    static_assert(GR == 8, "groups of 8 tokens: 128-byte runs of the tile");
+    static_assert(GR == 8 || GR == 16 || GR == 32, "a group is 8, 16 or 32 tokens of one 32-token block of the tile");
     static_assert(GR % TPR == 0, "a group is a whole number of rounds");
-    extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // AQ_ROWS x (Kp + 16) bytes, then the gain
+    extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // GR x (Kp + 16) bytes, then the gain
     __shared__ double red_ss[TPR][WPT];
     __shared__ float red_max[TPR][WPT];
     __shared__ int red_sum[TPR][WPT];
@@ -84,12 +86,17 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rl = wave / WPT, part = wave % WPT;
     const int K = a.K;
-    const int stride = a.Kp + 16;          // the 16-byte skew keeps the 8 rows on different LDS banks
+    const int stride = a.Kp + 16;          // the 16-byte skew keeps neighbouring rows on different LDS banks
     const int ngroups = (a.M + GR - 1) / GR;
 
+    // (group, round) of the rows being worked on, of the next ones (already requested) and of the ones
+    // after them (requested at the top of each round): two rounds of loads are in flight, so the memory
+    // pipe does not drain while a round's reductions and barriers run
     int grp = blockIdx.x, rnd = 0;
-    float4 v[HV4];
+    int grp1 = RPG == 1 ? grp + (int)gridDim.x : grp, rnd1 = RPG == 1 ? 0 : 1;
+    float4 v[HV4], v1[HV4];
     load_rows<HV4, WPT>(a, grp * GR + rl, lane, part, v);
+    if (grp1 < ngroups) load_rows<HV4, WPT>(a, grp1 * GR + rnd1 * TPR + rl, lane, part, v1);
 
     // the norm gain is the same for every token: parked in LDS once (read after the first barrier below)
     float* gain_lds = reinterpret_cast<float*>(rowbuf + (size_t)GR * stride);
@@ -99,11 +106,11 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
     }
 
     while (true) {
-        const int next_rnd = (rnd + 1) % RPG;
-        const int next_grp = next_rnd == 0 ? grp + (int)gridDim.x : grp;
-        const bool more = next_grp < ngroups;
-        float4 vn[HV4];
-        if (more) load_rows<HV4, WPT>(a, next_grp * GR + next_rnd * TPR + rl, lane, part, vn);
+        const bool more = grp1 < ngroups;
+        const int rnd2 = (rnd1 + 1) % RPG;
+        const int grp2 = rnd2 == 0 ? grp1 + (int)gridDim.x : grp1;
+        float4 v2[HV4];
+        if (more && grp2 < ngroups) load_rows<HV4, WPT>(a, grp2 * GR + rnd2 * TPR + rl, lane, part, v2);
 
         const int row0 = grp * GR;
         const int row = row0 + rnd * TPR + rl;
@@ -187,7 +194,8 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
 
         if (rnd == RPG - 1) {
             // tiled write-out: thread (token t, chunk kc) moves the 16 bytes of k = 16 kc .. 16 kc + 15;
-            // the GR tokens of one chunk are GR * 16 contiguous bytes of the tile
+            // the GR tokens of one chunk are GR * 16 contiguous bytes of the tile (with GR = 32 a wavefront
+            // writes whole 1 KB fragments and the workgroup one contiguous 32-token block)
             const int t = threadIdx.x % GR;
             const int mb = row0 >> 5, r0 = row0 & 31;
             const int nchunks = a.Kp >> 4;
@@ -202,9 +210,162 @@ __global__ __launch_bounds__(AQ_THREADS) void act_quant_kernel(QK a) {
         if (!more) break;
         // (the barriers of the next round order its LDS writes after the reads above)
 #pragma unroll
-        for (int i = 0; i < HV4; ++i) v[i] = vn[i];
-        grp = next_grp;
-        rnd = next_rnd;
+        for (int i = 0; i < HV4; ++i) { v[i] = v1[i]; v1[i] = v2[i]; }
+        grp = grp1; rnd = rnd1;
+        grp1 = grp2; rnd1 = rnd2;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Many tokens, one wavefront per token.  A wavefront keeps its token's whole row in registers
+// (NC float4 per lane), so the statistic, the absolute maximum and the code sum are reduced inside
+// the wavefront with lane exchanges: no LDS reductions and no barrier per token, and the wavefronts
+// of a workgroup drift apart instead of marching in step.  The int8 rows of a group of GR tokens
+// are parked in LDS and written out together as whole pieces of the tiled layout (one barrier
+// pair per group).  Loads are unconditional (row and column indices clamped, values masked
+// afterwards).  Small workgroups, several per compute unit, no software prefetch: measured at
+// 8192 x 2560, eight wavefronts and 16-token groups take 19.4 us against 26.7 us for sixteen
+// wavefronts and 32-token groups (which start, load, and write out all over the chip in the same
+// phase) and 21 - 24 us with the next row prefetched into registers (fewer resident wavefronts).
+// ---------------------------------------------------------------------------
+template <int NC, bool BF16>
+__device__ inline void load_row_clamped(const QK& a, int row, int lane, float4 (&v)[NC]) {
+    const int K = a.K;
+    const int rc = min(row, a.M - 1);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int k = min(4 * (lane + 64 * c), K - 4);          // K % 4 == 0, K >= 4
+        if constexpr (BF16) {
+            typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+            const __attribute__((address_space(1))) u32x2* src =
+                (const __attribute__((address_space(1))) u32x2*)(reinterpret_cast<const uint16_t*>(a.x) + (size_t)rc * K + k);
+            const u32x2 raw = *src;
+            v[c] = make_float4(bf16_to_f32((uint16_t)(raw.x & 0xffffu)), bf16_to_f32((uint16_t)(raw.x >> 16)),
+                               bf16_to_f32((uint16_t)(raw.y & 0xffffu)), bf16_to_f32((uint16_t)(raw.y >> 16)));
+        } else {
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            const __attribute__((address_space(1))) f32x4* src =
+                (const __attribute__((address_space(1))) f32x4*)(reinterpret_cast<const float*>(a.x) + (size_t)rc * K + k);
+            const f32x4 r = *src;
+            v[c] = make_float4(r.x, r.y, r.z, r.w);
+        }
+    }
+}
+
+template <int NC, int GR, int NWV, bool BF16>
+__global__ __launch_bounds__(NWV * 64) void act_quant_wave_kernel(QK a) {
+    constexpr int NT = NWV * 64;
+    constexpr int TPW = GR / NWV;            // tokens of a group per wavefront
+    static_assert(GR % NWV == 0 && (GR == 8 || GR == 16 || GR == 32), "a group is 8, 16 or 32 tokens, split evenly");
+    extern __shared__ __attribute__((aligned(16))) unsigned char rowbuf[];   // GR x (Kp + 16) bytes, then the gain
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int K = a.K;
+    const int stride = a.Kp + 16;
+    const int ngroups = (a.M + GR - 1) / GR;
+    const bool norm = a.gain != nullptr;
+
+    float* gain_lds = reinterpret_cast<float*>(rowbuf + (size_t)GR * stride);
+    if (norm) {
+        for (int k = 4 * threadIdx.x; k < NC * 256; k += 4 * NT)
+            *reinterpret_cast<float4*>(gain_lds + k) =
+                k < K ? *reinterpret_cast<const float4*>(a.gain + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+
+    // flat walk over this wavefront's tokens: token j of the walk is token wave + (j % TPW) * NWV of group
+    // blockIdx.x + (j / TPW) * gridDim.x
+    int grp = blockIdx.x, tw = 0;
+    float4 v[NC];
+    if (grp < ngroups) load_row_clamped<NC, BF16>(a, grp * GR + wave, lane, v);
+    __syncthreads();                               // the gain is in LDS
+
+    while (grp < ngroups) {
+        const int tw_n = tw + 1 == TPW ? 0 : tw + 1;
+        const int grp_n = tw + 1 == TPW ? grp + (int)gridDim.x : grp;
+
+        const int t = wave + tw * NWV;             // token inside the group
+        const int row = grp * GR + t;
+        const bool live = row < a.M;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const bool in = live && 4 * (lane + 64 * c) < K;
+            v[c].x = in ? v[c].x : 0.f; v[c].y = in ? v[c].y : 0.f; v[c].z = in ? v[c].z : 0.f; v[c].w = in ? v[c].w : 0.f;
+        }
+        if (norm) {
+            double ss = 0.0;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                ss += (double)v[c].x * (double)v[c].x;
+                ss += (double)v[c].y * (double)v[c].y;
+                ss += (double)v[c].z * (double)v[c].z;
+                ss += (double)v[c].w * (double)v[c].w;
+                __builtin_amdgcn_sched_barrier(0);      // one chunk at a time: the row itself fills the registers
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+            const float r = (float)(1.0 / sqrt(ss / (double)K + (double)a.eps_norm));
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float4 g = *reinterpret_cast<const float4*>(gain_lds + 4 * (lane + 64 * c));
+                v[c].x = (v[c].x * r) * g.x;
+                v[c].y = (v[c].y * r) * g.y;
+                v[c].z = (v[c].z * r) * g.z;
+                v[c].w = (v[c].w * r) * g.w;
+                if (c % 2 == 1) __builtin_amdgcn_sched_barrier(0);   // two gain reads in flight at a time
+            }
+        }
+        float amax = 0.f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[c].x), fabsf(v[c].y)), fmaxf(fabsf(v[c].z), fabsf(v[c].w))));
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        const float ac = fmaxf(amax, a.eps_act);
+        const float sc = 127.0f / ac;
+
+        int sum = 0;
+        uint32_t* myrow = reinterpret_cast<uint32_t*>(rowbuf + (size_t)t * stride);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int k = 4 * (lane + 64 * c);
+            const int q0 = (int)fminf(fmaxf(rintf(v[c].x * sc), -127.f), 127.f);
+            const int q1 = (int)fminf(fmaxf(rintf(v[c].y * sc), -127.f), 127.f);
+            const int q2 = (int)fminf(fmaxf(rintf(v[c].z * sc), -127.f), 127.f);
+            const int q3 = (int)fminf(fmaxf(rintf(v[c].w * sc), -127.f), 127.f);
+            sum += q0 + q1 + q2 + q3;
+            const uint32_t word = (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) | ((uint32_t)(q2 & 0xff) << 16) |
+                                  ((uint32_t)(q3 & 0xff) << 24);
+            if (k < a.Kp) myrow[k >> 2] = word;
+            if (a.xq_rowmajor && live && k < K) *reinterpret_cast<uint32_t*>(a.xq_rowmajor + (size_t)row * K + k) = word;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if (lane == 0 && live) {
+            a.absmax[row] = ac;
+            a.dscale[row] = ac / 127.0f;
+            a.sumq[row] = sum;
+            if (a.absmax_tap) a.absmax_tap[row] = ac;
+        }
+
+        if (tw + 1 == TPW) {
+            // the group is complete once every wavefront has parked its tokens
+            __syncthreads();
+            const int tt = threadIdx.x % GR;
+            const int row0 = grp * GR;
+            const int mb = row0 >> 5, r0 = row0 & 31;
+            const int nchunks = a.Kp >> 4;
+            for (int kc = threadIdx.x / GR; kc < nchunks; kc += NT / GR) {
+                const uint4 val = *reinterpret_cast<const uint4*>(rowbuf + (size_t)tt * stride + 16 * kc);
+                const int sb = kc >> 3, dd = (kc >> 1) & 3, hh = kc & 1;
+                const size_t off = ((((size_t)mb * a.nsb + sb) * 4 + dd) * 64 + (hh * 32 + r0 + tt)) * 16;
+                *reinterpret_cast<uint4*>(a.q_tiled + off) = val;
+            }
+            __syncthreads();                       // before the next group's tokens overwrite the rows
+        }
+        if (grp_n < ngroups) load_row_clamped<NC, BF16>(a, grp_n * GR + wave + tw_n * NWV, lane, v);
+        grp = grp_n;
+        tw = tw_n;
     }
 }
 
@@ -312,15 +473,17 @@ int launch_rows(const QK& a, hipStream_t s) {
     return BRL_OK;
 }
 
-template <int HV4, int WPT, int GR>
+template <int HV4, int WPT, int GR, int NWV>
 int launch_one(const QK& a, hipStream_t s) {
+    constexpr int AQ_THREADS = NWV * 64;
     const int ngroups = (a.M + GR - 1) / GR;
     const size_t lds = (size_t)GR * (a.Kp + 16) + (a.gain ? (size_t)a.Kp * 4 : 0);
     static int slots = 0;            // workgroups the device holds at once
     static bool raised = false;      // more than the default 64 KB of dynamic LDS allowed
     constexpr size_t max_lds = (size_t)GR * (HV4 * WPT * 256 + 16) + (size_t)HV4 * WPT * 256 * 4;
+    static_assert(max_lds <= 160 * 1024, "the rows of a group and the gain fit the LDS of a compute unit");
     if (!raised && max_lds > 65536) {
-        BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<HV4, WPT, GR>),
+        BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<HV4, WPT, GR, NWV>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds));
         raised = true;
     }
@@ -328,7 +491,7 @@ int launch_one(const QK& a, hipStream_t s) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, act_quant_kernel<HV4, WPT, GR>, AQ_THREADS, max_lds) !=
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, act_quant_kernel<HV4, WPT, GR, NWV>, AQ_THREADS, max_lds) !=
                 hipSuccess ||
             cus <= 0 || per_cu <= 0) {
             (void)hipGetLastError();
@@ -338,7 +501,46 @@ int launch_one(const QK& a, hipStream_t s) {
         slots = cus * per_cu;
     }
     const int grid = ngroups < slots ? ngroups : slots;
-    hipLaunchKernelGGL((act_quant_kernel<HV4, WPT, GR>), dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    hipLaunchKernelGGL((act_quant_kernel<HV4, WPT, GR, NWV>), dim3(grid), dim3(AQ_THREADS), lds, s, a);
+    return BRL_OK;
+}
+
+template <int NC, int GR, int NWV>
+int launch_wave(const QK& a, hipStream_t s) {
+    constexpr int NT = NWV * 64;
+    constexpr size_t lds = (size_t)GR * (NC * 256 + 16) + (size_t)NC * 256 * 4;      // sized for the widest row of this NC
+    static_assert(lds <= 160 * 1024, "the rows of a group and the gain fit the LDS of a compute unit");
+    const int ngroups = (a.M + GR - 1) / GR;
+    const bool bf16 = a.x_dtype == BRL_BF16;
+    static const int slots = [] {        // workgroups the device holds at once (the two input types use the same resources)
+        int dev = 0, cus = 0, per_cu = 0;
+        hipError_t e = hipSuccess;
+        if (lds > 65536) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_wave_kernel<NC, GR, NWV, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_wave_kernel<NC, GR, NWV, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        }
+        if (e != hipSuccess || hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, act_quant_wave_kernel<NC, GR, NWV, false>, NT, lds) !=
+                hipSuccess ||
+            cus <= 0 || per_cu <= 0) {
+            (void)hipGetLastError();
+            return -1;
+        }
+        return cus * per_cu;
+    }();
+    if (slots <= 0) {
+        set_error("act_quant: the device cannot hold a workgroup with %zu bytes of LDS", lds);
+        return BRL_EHIP;
+    }
+    const int grid = ngroups < slots ? ngroups : slots;
+    if (bf16)
+        hipLaunchKernelGGL((act_quant_wave_kernel<NC, GR, NWV, true>), dim3(grid), dim3(NT), lds, s, a);
+    else
+        hipLaunchKernelGGL((act_quant_wave_kernel<NC, GR, NWV, false>), dim3(grid), dim3(NT), lds, s, a);
     return BRL_OK;
 }
 
@@ -360,16 +562,21 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
         set_error("act_quant: K = %d exceeds the supported %d", in.K, MAX_K);
         return BRL_EINVAL;
     }
+    // Many tokens: one wavefront per token; NC float4 per lane hold the row (NC * 256 >= Kp), and as many
+    // tokens of a 32-token block are written out together as the LDS holds next to the gain.
     if (a.Kp <= 1024) {
-        rc = rows ? launch_rows<1, 4>(a, s) : launch_one<2, 2, 8>(a, s);
-    } else if (a.Kp <= 3072) {
-        rc = rows ? launch_rows<3, 4>(a, s) : launch_one<6, 2, 8>(a, s);
+        rc = rows ? launch_rows<1, 4>(a, s) : launch_wave<4, 16, 8>(a, s);
+    } else if (a.Kp <= 2560) {
+        rc = rows ? launch_rows<3, 4>(a, s) : launch_wave<10, 16, 8>(a, s);
+    } else if (a.Kp <= 3328) {
+        rc = rows ? launch_rows<4, 4>(a, s) : launch_wave<13, 16, 8>(a, s);
     } else if (a.Kp <= 4608) {
-        rc = rows ? launch_rows<3, 6>(a, s) : launch_one<9, 2, 8>(a, s);
-    } else if (a.Kp <= 7168) {
-        rc = rows ? launch_rows<4, 7>(a, s) : launch_one<7, 4, 8>(a, s);
+        rc = rows ? launch_rows<3, 6>(a, s) : launch_wave<18, 16, 8>(a, s);
+    } else if (a.Kp <= 6912) {
+        rc = rows ? launch_rows<4, 7>(a, s) : launch_wave<27, 16, 8>(a, s);
     } else {
-        rc = rows ? launch_rows<4, 9>(a, s) : launch_one<9, 4, 8>(a, s);
+        // the widest rows do not fit one wavefront's registers: four wavefronts per token, LDS reductions
+        rc = rows ? launch_rows<4, 9>(a, s) : launch_one<9, 4, 8, 16>(a, s);
     }
     if (rc != BRL_OK) return rc;
     BRL_LAUNCH_CHECK("act_quant_kernel");
