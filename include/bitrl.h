@@ -330,6 +330,39 @@ int attention_forward(const float* qkv, int B, int S,
                       float* out, void* workspace, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * State-to-token front end: serialize(s_t) of Sec. 3.1, Eq. 3 ("converts
+ * environment states to natural language text"; Sec. 5.2: a state of 17 - 27
+ * dimensions is 15 - 40 tokens, about 1.2 ms of host time on the paper's
+ * device).  HOST code, HOST pointers, no GPU work.  The paper gives neither
+ * the text format nor the tokenizer, and the backbone's own tokenizer is not
+ * part of this library; this is a documented stand-in whose ids have the right
+ * number and range:
+ *   text    "state:" then, per dimension, " v" with v the value clamped to
+ *           [-9.9, 9.9] and written with one decimal, correctly rounded from
+ *           the exact fp32 value (exact ties to the even digit), zero without
+ *           a sign, NaN as 0.0;
+ *   ids     0 begin-of-state, 1 "state:", 2 .. 200 the number strings " -9.9"
+ *           .. " 9.9" (id = 101 + 10 v), 201 .. 456 the single bytes; text is
+ *           tokenised greedily, longest entry first, after id 0.
+ * A state of n_dims values is n_dims + 2 tokens.
+ *
+ * brl_serialize_text: writes the NUL-terminated text if cap > the returned
+ *   length; returns the text length in bytes either way (0 for bad arguments).
+ * brl_tokenize: ids of any byte string (free text falls back to byte ids);
+ *   *n_ids is the token count; BRL_ENOSPC if it exceeds max_ids (the first
+ *   max_ids ids are still written).
+ * serialize_states: states [B, n_dims] fp32 -> ids_out [B * (n_dims + 2)] and
+ *   cu_seqlens_out [B + 1], the layout encoder_forward_packed takes (copy ids
+ *   and cu_seqlens to the device, pass cu_seqlens_out as its host copy);
+ *   BRL_EINVAL if the encoder's vocab is below BRL_SERIALIZE_VOCAB.
+ * ------------------------------------------------------------------------ */
+#define BRL_SERIALIZE_VOCAB 457
+size_t brl_serialize_text(const float* state /* HOST */, int n_dims, char* text_out /* HOST */, size_t cap);
+int brl_tokenize(const char* text /* HOST */, size_t n_bytes, int32_t* ids_out /* HOST */, int max_ids, int* n_ids /* HOST */);
+int serialize_states(const float* states /* HOST */, int B, int n_dims, int vocab,
+                     int32_t* ids_out /* HOST */, int32_t* cu_seqlens_out /* HOST */);
+
+/* ------------------------------------------------------------------------
  * Policy and value heads (Sec. 3.1, Eq. 3; fp32 parameters, Appendix table):
  * each is an MLP, out = W_L act(... act(W_1 h + b_1) ...) + b_L, accumulated
  * in fp64 and rounded to fp32 once at the output.  The softmax over the

@@ -113,6 +113,9 @@ _SIGNATURES = {
     "brl_attention_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int, c_int]),
     "attention_forward": (c_int, [c_void_p, c_int, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_float, c_int,
                                   c_void_p, c_void_p, c_size_t, c_void_p]),
+    "brl_serialize_text": (c_size_t, [c_void_p, c_int, C.c_char_p, c_size_t]),
+    "brl_tokenize": (c_int, [C.c_char_p, c_size_t, c_void_p, c_int, C.POINTER(c_int)]),
+    "serialize_states": (c_int, [c_void_p, c_int, c_int, c_int, c_void_p, c_void_p]),
     "brl_head_workspace_bytes": (c_size_t, [C.POINTER(brl_head), c_int]),
     "policy_value_head": (c_int, [C.POINTER(brl_head), c_void_p, c_int, c_void_p, c_void_p,
                                   c_void_p, c_size_t, c_void_p]),
@@ -298,6 +301,38 @@ def attention_forward(qkv: torch.Tensor, B: int, S: int, cu_seqlens: Optional[to
                                    None if cu_seqlens_host is None else cu_seqlens_host.ctypes.data,
                                    n_heads, n_kv_heads, head_dim, rope_theta, attn_precision, _ptr(out), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+BRL_SERIALIZE_VOCAB = 457
+
+
+def brl_serialize_text(state) -> str:
+    """state: contiguous float32 numpy array [n_dims] on the host."""
+    n = int(state.shape[0])
+    need = lib().brl_serialize_text(state.ctypes.data, n, None, 0)
+    buf = C.create_string_buffer(need + 1)
+    lib().brl_serialize_text(state.ctypes.data, n, buf, need + 1)
+    return buf.value.decode("ascii")
+
+
+def brl_tokenize(text: bytes):
+    """ids (list of int) of a byte string under the stand-in vocabulary."""
+    import numpy as np
+    cap = len(text) + 1
+    ids = np.empty(cap, dtype=np.int32)
+    n = c_int(0)
+    _check(lib().brl_tokenize(text, len(text), ids.ctypes.data, cap, C.byref(n)))
+    return [int(i) for i in ids[:n.value]]
+
+
+def serialize_states(states, vocab: int):
+    """states: contiguous float32 numpy array [B, n_dims] on the host -> (ids int32 [B * (n_dims + 2)], cu_seqlens int32 [B + 1])."""
+    import numpy as np
+    b, n = states.shape
+    ids = np.empty(b * (n + 2), dtype=np.int32)
+    cu = np.empty(b + 1, dtype=np.int32)
+    _check(lib().serialize_states(states.ctypes.data, b, n, vocab, ids.ctypes.data, cu.ctypes.data))
+    return ids, cu
 
 
 def brl_head_workspace_bytes(head: brl_head, B: int) -> int:

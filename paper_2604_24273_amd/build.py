@@ -17,7 +17,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libbitrl.so")
 
-SOURCES = ["api.hip", "quantize_weights.hip", "act_quant.hip", "gemm.hip", "gemv.hip", "attention.hip", "attention_mfma.hip", "misc.hip", "ppo.hip", "int8_weights.hip"]
+SOURCES = ["api.hip", "quantize_weights.hip", "act_quant.hip", "gemm.hip", "gemv.hip", "attention.hip", "attention_mfma.hip", "misc.hip", "ppo.hip", "int8_weights.hip", "serialize.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
