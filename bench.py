@@ -73,6 +73,8 @@ def main() -> int:
     ap.add_argument("--no-layer", action="store_true", help="skip the single 16 x 2048 x 2048 BitLinear layer leg")
     ap.add_argument("--no-ffn", action="store_true", help="skip the 256-token FFN block leg")
     ap.add_argument("--no-prefill-3b", action="store_true", help="skip the 3B-shape 64 x 512 micro-batch leg")
+    ap.add_argument("--no-vendor-gemm", action="store_true",
+                    help="skip the context leg that times the vendor int8 GEMM (torch._int_mm) on the same layer shapes")
     ap.add_argument("--gemv-pool", type=int, default=None,
                     help="distinct weight-pair buffers the GEMV legs walk (default: one per call, so that a batched "
                          "launch reads every weight byte exactly once and nothing can come out of a cache)")
@@ -241,6 +243,10 @@ def main() -> int:
     if not args.no_ffn and args.workload == "encoder-2b":
         ffn = bench_ffn(torch, B, R, synth)
 
+    vendor = None
+    if not args.no_vendor_gemm and args.workload == "encoder-2b":
+        vendor = bench_vendor_gemm(torch, Bn * S, shape)
+
     # ---- one short state per call (the paper's deployment shape: a 15-40 token state per environment step)
     single = None
     if not args.no_gemv and not args.no_single_state and shape is synth.SHAPE_2B:
@@ -315,6 +321,7 @@ def main() -> int:
         "bitlinear_layer_16x2048x2048": layer,
         "ffn_block_256_tokens": ffn,
         "prefill_3b_microbatch": prefill,
+        "vendor_int8_gemm_context": vendor,
         "gemv_pair": gemv,
         "single_state_latency": single,
         "ppo_head_update": ppo,
@@ -466,6 +473,40 @@ def bench_prefill_3b(torch, B, R, synth, np, states: int = 64, tokens: int = 512
                          "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(tops / INT8_MFMA_PEAK_TOPS, 4),
                          "traffic": None},
             "setup_seconds": round(setup_s, 1)}
+
+
+def bench_vendor_gemm(torch, M: int, shape):
+    """Context only, not part of the library's path: the vendor's dense int8 GEMM (hipBLASLt behind torch._int_mm,
+    int8 x int8 -> int32, no 2-bit decode, no rescale, no GLU) on the four BitLinear products of a 2B-shape layer,
+    with operands distributed like the library's (int8 activations of sigma 36, ternary weights as int8)."""
+    dq, dkv = shape.n_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    shapes = {"qkv": (dq + 2 * dkv, shape.d), "o": (shape.d, dq), "gate_up": (2 * shape.f, shape.d), "down": (shape.d, shape.f)}
+    out = {}
+    try:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(0)
+        for name, (N, K) in shapes.items():
+            a = torch.clamp(torch.round(torch.randn((M, K), generator=gen, device="cuda") * 36.0), -127, 127).to(torch.int8)
+            b = torch.randint(-1, 2, (K, N), generator=gen, device="cuda", dtype=torch.int8)
+            for _ in range(3):
+                torch._int_mm(a, b)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                torch._int_mm(a, b)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / 10 * 1e3
+            out[name] = {"M": M, "N": N, "K": K, "us": round(us, 1), "tops": round(2.0 * M * N * K / (us * 1e-6) / 1e12, 1)}
+            del a, b
+        tot_ops = sum(2.0 * v["M"] * v["N"] * v["K"] for v in out.values())
+        tot_us = sum(v["us"] for v in out.values())
+        out["all_four"] = {"us": round(tot_us, 1), "tops": round(tot_ops / (tot_us * 1e-6) / 1e12, 1)}
+        out["note"] = "torch._int_mm (hipBLASLt), dense int8 weights; context for the library's BitLinear rate, not a target"
+    except Exception as e:          # an unsupported build of torch must not fail the benchmark
+        out = {"unavailable": str(e)[:160]}
+    return out
 
 
 def bench_single_state(torch, B, R, synth, np, enc, head, shape, n_tokens: int = 27, calls: int = 50):

@@ -137,13 +137,12 @@ BitlinearWs bitlinear_ws_layout(int M, int N, int K) {
 }
 
 struct FfnWs {
-    size_t xf_off, act1_off, gu_off, act2_off, total;
+    size_t act1_off, gu_off, act2_off, total;
 };
 
 FfnWs ffn_ws_layout(int M, int d, int f) {
     FfnWs L;
-    L.xf_off = 0;
-    L.act1_off = round_up_sz((size_t)M * d * 4, ALIGN);
+    L.act1_off = 0;
     L.gu_off = L.act1_off + actbuf_bytes(M, d);
     L.act2_off = L.gu_off + round_up_sz((size_t)M * f * 4, ALIGN);
     L.total = L.act2_off + actbuf_bytes(M, f);
@@ -184,6 +183,8 @@ int run_ffn(const brl_ffn_weights* w, int w8, const float* x32, const void* xin,
     qb.eps_norm = eps_norm; qb.eps_act = eps_act; qb.M = M; qb.K = f;
     if (int rc = launch_act_quant(qb, act2, s)) return rc;
     const WeightSegs dn = one_seg(w->down_packed, w->down_beta, d, w8);
+    // the residual is the block input itself: read as bf16 where the caller gave bf16 (no widened copy)
+    if (x32 == nullptr) return launch_gemm(act2, dn, M, d, f, y, d, static_cast<const float*>(xin), nullptr, 0, s, 1);
     return launch_gemm(act2, dn, M, d, f, y, d, x32, nullptr, 0, s);
 }
 
@@ -592,12 +593,7 @@ int ffn_block_forward(const brl_ffn_weights* w, const void* x, int x_dtype, int 
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* base = static_cast<char*>(workspace);
-    const float* x32 = static_cast<const float*>(x);
-    if (x_dtype == BRL_BF16) {
-        float* xf = reinterpret_cast<float*>(base + L.xf_off);
-        if (int rc = launch_widen_bf16(static_cast<const uint16_t*>(x), (size_t)M * d, xf, s)) return rc;
-        x32 = xf;
-    }
+    const float* x32 = x_dtype == BRL_BF16 ? nullptr : static_cast<const float*>(x);   // null: residual read as bf16
     Carver c1(base + L.act1_off);
     const ActBuf act1 = take_actbuf(c1, M, d);
     Carver c2(base + L.act2_off);

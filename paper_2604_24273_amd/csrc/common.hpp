@@ -125,8 +125,9 @@ int launch_act_quant(const QuantArgs& a, const ActBuf& out, hipStream_t s);
 
 // int8 MFMA GEMM with fused dequant epilogue
 // glu = 1: w holds (gate, up); y [M, N/2] receives (max(G,0) * max(G,0)) * U
+// res_bf16 = 1: `residual` points at bf16 bit patterns [M, ldy] (widened exactly when read)
 int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K,
-                float* y, int ldy, const float* residual, int32_t* acc_dbg, int glu, hipStream_t s);
+                float* y, int ldy, const float* residual, int32_t* acc_dbg, int glu, hipStream_t s, int res_bf16 = 0);
 
 // bandwidth-bound GEMV (M <= 4), activation quantisation fused
 int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t* packed, const float* beta,
@@ -175,6 +176,5 @@ struct EnsembleLayer {
 };
 int launch_ensemble_layer(const EnsembleLayer& a, hipStream_t s);
 int launch_ensemble_mean(const float* each, int n, int B, float* mean, hipStream_t s);
-int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s);   // n % 8 == 0
 
 }  // namespace brl

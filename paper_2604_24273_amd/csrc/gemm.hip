@@ -56,7 +56,8 @@ struct GemmArgs {
     int tiles_m, tiles_n, group_m;
     float* y;
     int ldy;
-    const float* residual;
+    const float* residual;   // [M, ldy] fp32, or bf16 bit patterns when res_bf16 (widened exactly on load)
+    int res_bf16;
     int32_t* acc_dbg;
     int fast_epilogue;       // every segment a multiple of 32 rows, ldy % 4 == 0, no debug tap
     double ops;              // int8 operations of the product (for the timing hooks)
@@ -66,6 +67,20 @@ struct GemmArgs {
     int sb_per_split;        //      (tile, range); raw int32 partial tiles go to `partials` [splits][M][nnb * 32]
     int32_t* partials;       //      and splitk_epilogue_kernel finishes the product
 };
+
+// residual element(s) at flat index o (o % 4 == 0 for the four-wide form)
+__device__ inline float res_at(const GemmArgs& g, size_t o) {
+    if (g.res_bf16) return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(g.residual)[o] << 16);
+    return g.residual[o];
+}
+__device__ inline float4 res4_at(const GemmArgs& g, size_t o) {
+    if (g.res_bf16) {
+        const uint2 raw = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(g.residual) + o);
+        return make_float4(__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                           __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u));
+    }
+    return *reinterpret_cast<const float4*>(g.residual + o);
+}
 
 __device__ inline v4i expand_codes(uint32_t p) {
     v4i r;
@@ -265,7 +280,7 @@ __device__ inline void epilogue_plain(const GemmArgs& g, v16i (&acc)[TM][TN], in
         if constexpr (RES) {     // rows past M are clamped for the load and never stored
 #pragma unroll
             for (int p = 0; p < NPRE; ++p)
-                res[p] = *reinterpret_cast<const float4*>(g.residual + (size_t)min(mbase + row[p], g.M - 1) * g.ldy + col);
+                res[p] = res4_at(g, (size_t)min(mbase + row[p], g.M - 1) * g.ldy + col);
         }
         scatter_half<TM, TN>(acc, idx >> 1, idx & 1, lane, scr);
 #pragma unroll
@@ -342,7 +357,7 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
                         const int a = scr[row * LD + c] - (g.sumq ? g.sumq[m] : 0);
                         const size_t o = (size_t)m * g.ldy + col0 + (c & 31);
                         float val = ((float)a * g.dscale[m]) * (*g.beta[seg]);
-                        if (g.residual) val = val + g.residual[o];
+                        if (g.residual) val = val + res_at(g, o);
                         g.y[o] = val;
                         if (g.acc_dbg) g.acc_dbg[o] = a;
                     }
@@ -414,7 +429,7 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(GemmArgs g) {
             g.y[o] = (pz * pz) * U;
         } else {
             float val = ((float)(a0[e] - sq) * d) * (*g.beta[seg]);
-            if (g.residual) val = val + g.residual[o];
+            if (g.residual) val = val + res_at(g, o);
             g.y[o] = val;
             if (g.acc_dbg) g.acc_dbg[o] = a0[e] - sq;
         }
@@ -641,7 +656,7 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_direct_kernel(GemmArgs
             block_columns(g, min(nb0 + (g.glu ? 2 * jb : jb), g.nnb - 1), seg, col0, ncols);
             e_d[q] = g.dscale[m];
             e_sq[q] = g.sumq ? g.sumq[m] : 0;
-            e_res[q] = (g.residual && c < ncols) ? g.residual[(size_t)m * g.ldy + col0 + c] : 0.f;
+            e_res[q] = (g.residual && c < ncols) ? res_at(g, (size_t)m * g.ldy + col0 + c) : 0.f;
         }
     }
 
@@ -792,7 +807,7 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
 }  // namespace
 
 int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float* y, int ldy,
-                const float* residual, int32_t* acc_dbg, int glu, hipStream_t s) {
+                const float* residual, int32_t* acc_dbg, int glu, hipStream_t s, int res_bf16) {
     GemmArgs g;
     g.A = reinterpret_cast<const uint4*>(a.q);
     g.dscale = a.dscale;
@@ -821,6 +836,7 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     g.y = y;
     g.ldy = ldy;
     g.residual = residual;
+    g.res_bf16 = residual ? res_bf16 : 0;
     g.acc_dbg = acc_dbg;
     g.splits = 1;
     g.sb_per_split = g.nsb;

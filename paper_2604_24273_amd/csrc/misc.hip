@@ -26,20 +26,6 @@ __global__ void embed_kernel(const uint16_t* __restrict__ table, const int32_t* 
     *reinterpret_cast<float4*>(o + 4) = hi;
 }
 
-// fp32 copy of a bf16 tensor (exact widening); eight elements per thread
-__global__ void widen_bf16_kernel(const uint16_t* __restrict__ in, size_t n8, float* __restrict__ out) {
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n8) return;
-    const uint4 raw = *reinterpret_cast<const uint4*>(in + idx * 8);
-    float4 lo, hi;
-    lo.x = __uint_as_float(raw.x << 16); lo.y = __uint_as_float(raw.x & 0xffff0000u);
-    lo.z = __uint_as_float(raw.y << 16); lo.w = __uint_as_float(raw.y & 0xffff0000u);
-    hi.x = __uint_as_float(raw.z << 16); hi.y = __uint_as_float(raw.z & 0xffff0000u);
-    hi.z = __uint_as_float(raw.w << 16); hi.w = __uint_as_float(raw.w & 0xffff0000u);
-    *reinterpret_cast<float4*>(out + idx * 8) = lo;
-    *reinterpret_cast<float4*>(out + idx * 8 + 4) = hi;
-}
-
 // rinv[m] = fp32(1 / sqrt(mean_k x[m,k]^2 + eps)), statistic in fp64; one wavefront per row
 __global__ __launch_bounds__(256) void row_rinv_kernel(const float* __restrict__ x, int M, int d, float eps,
                                                         float* __restrict__ rinv) {
@@ -156,14 +142,6 @@ int launch_ensemble_mean(const float* each, int n, int B, float* mean, hipStream
     LaunchTimer tm(BRL_KC_OTHER, s);
     hipLaunchKernelGGL(ensemble_mean_kernel, dim3((B + 255) / 256), dim3(256), 0, s, each, n, B, mean);
     BRL_LAUNCH_CHECK("ensemble_mean_kernel");
-    return BRL_OK;
-}
-
-int launch_widen_bf16(const uint16_t* in, size_t n, float* out, hipStream_t s) {
-    const size_t n8 = n / 8;
-    LaunchTimer tm(BRL_KC_OTHER, s);
-    hipLaunchKernelGGL(widen_bf16_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, in, n8, out);
-    BRL_LAUNCH_CHECK("widen_bf16_kernel");
     return BRL_OK;
 }
 
