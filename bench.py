@@ -37,13 +37,16 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
 # summary it was copied from and the kernel it refers to, and is reset to None whenever that kernel changes
 # until the counters have been taken again.
 ROOFLINE_TRAFFIC = {
-    "encoder-2b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
+    # FETCH_SIZE 76 254.9 KiB x 2.0 + WRITE_SIZE 172 032 KiB x 1.0, averaged over the QKV and gate|up launches
+    "encoder-2b": {"bytes": 332.3e6, "kernel": "gemm_lds_kernel<2,2,2,4>",
+                   "source": "profiles/bench_encoder_2b_hbm_traffic_counters.txt"},
     "prefill-3b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
     "rl-states-2b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
 }
-# batched GEMV: fetched bytes / packed-weight bytes per launch, from the same kind of counter run at the pool
-# size the leg uses (None until taken for the kernel and pool as they stand)
-GEMV_BATCH_FETCH = {"ratio": None, "source": None}
+# batched GEMV: fetched bytes (FETCH_SIZE x 2.0; the outputs, 0.4 % of the bytes, are not in it) / algorithmic bytes
+# per launch, from the same kind of counter run with one pair of weight buffers per product, as in the timed leg
+# (256 products per launch: 1132.8 MB and 1139.9 MB fetched by the two kinds of launch against 2 x 1138.5 MB)
+GEMV_BATCH_FETCH = {"ratio": 0.998, "source": "profiles/bench_encoder_2b_hbm_traffic_counters.txt"}
 
 
 def linear_macs_per_token(shape) -> int:
