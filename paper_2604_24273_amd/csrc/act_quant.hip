@@ -13,7 +13,7 @@
 // int8 rows in LDS and writes the tile out in runs of 128 or 256 bytes.
 //
 // Three kernels:
-//   act_quant_wave_kernel  many tokens, rows up to 6912 wide: one wavefront per token
+//   act_quant_wave_kernel  many tokens, rows up to 8704 wide: one wavefront per token
 //   act_quant_kernel       many tokens, wider rows: four wavefronts per token, LDS reductions
 //   act_quant_row_kernel   up to 1024 tokens (latency, not bandwidth): one workgroup per token
 #include "common.hpp"
@@ -230,23 +230,27 @@ __global__ __launch_bounds__(NWV * 64) void act_quant_kernel(QK a) {
 // ---------------------------------------------------------------------------
 template <int NC, bool BF16>
 __device__ inline void load_row_clamped(const QK& a, int row, int lane, float4 (&v)[NC]) {
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
     const int K = a.K;
     const int rc = min(row, a.M - 1);
+    // The row index is the same for the whole wavefront: a scalar row base and one 32-bit byte offset per
+    // chunk.  The offsets are rebuilt for every row from a value the compiler cannot see through; hoisted
+    // out of the token loop they would occupy two registers per chunk next to the row itself.
+    const __attribute__((address_space(1))) char* base =
+        (const __attribute__((address_space(1))) char*)a.x + (size_t)rc * K * (BF16 ? 2 : 4);
+    unsigned lane_k;
+    asm volatile("v_lshlrev_b32 %0, 2, %1" : "=v"(lane_k) : "v"(lane));
+    const unsigned k_last = (unsigned)(K - 4);                  // K % 4 == 0, K >= 4
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int k = min(4 * (lane + 64 * c), K - 4);          // K % 4 == 0, K >= 4
+        const unsigned k = min(lane_k + 256u * c, k_last);
         if constexpr (BF16) {
-            typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-            const __attribute__((address_space(1))) u32x2* src =
-                (const __attribute__((address_space(1))) u32x2*)(reinterpret_cast<const uint16_t*>(a.x) + (size_t)rc * K + k);
-            const u32x2 raw = *src;
+            const u32x2 raw = *(const __attribute__((address_space(1))) u32x2*)(base + k * 2u);
             v[c] = make_float4(bf16_to_f32((uint16_t)(raw.x & 0xffffu)), bf16_to_f32((uint16_t)(raw.x >> 16)),
                                bf16_to_f32((uint16_t)(raw.y & 0xffffu)), bf16_to_f32((uint16_t)(raw.y >> 16)));
         } else {
-            typedef float f32x4 __attribute__((ext_vector_type(4)));
-            const __attribute__((address_space(1))) f32x4* src =
-                (const __attribute__((address_space(1))) f32x4*)(reinterpret_cast<const float*>(a.x) + (size_t)rc * K + k);
-            const f32x4 r = *src;
+            const f32x4 r = *(const __attribute__((address_space(1))) f32x4*)(base + k * 4u);
             v[c] = make_float4(r.x, r.y, r.z, r.w);
         }
     }
@@ -574,6 +578,8 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
         rc = rows ? launch_rows<3, 6>(a, s) : launch_wave<18, 16, 8>(a, s);
     } else if (a.Kp <= 6912) {
         rc = rows ? launch_rows<4, 7>(a, s) : launch_wave<27, 16, 8>(a, s);
+    } else if (a.Kp <= 8704) {
+        rc = rows ? launch_rows<4, 9>(a, s) : launch_wave<34, 8, 8>(a, s);
     } else {
         // the widest rows do not fit one wavefront's registers: four wavefronts per token, LDS reductions
         rc = rows ? launch_rows<4, 9>(a, s) : launch_one<9, 4, 8, 16>(a, s);
