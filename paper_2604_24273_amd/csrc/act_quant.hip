@@ -568,16 +568,20 @@ int launch_act_quant(const QuantArgs& in, const ActBuf& out, hipStream_t s) {
     }
     // Many tokens: one wavefront per token; NC float4 per lane hold the row (NC * 256 >= Kp), and as many
     // tokens of a 32-token block are written out together as the LDS holds next to the gain.
+    // A few thousand tokens make too few 16-token groups to fill the chip: groups of 8 then (measured: 2560 wide,
+    // 1536 / 2048 / 6144 tokens 8.3 / 9.1 / 15.9 us against 10.9 / 11.5 / 17.2; 6912 wide, 1536 / 2048 tokens
+    // 17.3 / 19.6 us against 21.4 / 22.8, and the other way round from 3072 tokens on).
+    const bool few_narrow = in.M <= 6144, few_wide = in.M <= 2048;
     if (a.Kp <= 1024) {
         rc = rows ? launch_rows<1, 4>(a, s) : launch_wave<4, 16, 8>(a, s);
     } else if (a.Kp <= 2560) {
-        rc = rows ? launch_rows<3, 4>(a, s) : launch_wave<10, 16, 8>(a, s);
+        rc = rows ? launch_rows<3, 4>(a, s) : few_narrow ? launch_wave<10, 8, 8>(a, s) : launch_wave<10, 16, 8>(a, s);
     } else if (a.Kp <= 3328) {
-        rc = rows ? launch_rows<4, 4>(a, s) : launch_wave<13, 16, 8>(a, s);
+        rc = rows ? launch_rows<4, 4>(a, s) : few_narrow ? launch_wave<13, 8, 8>(a, s) : launch_wave<13, 16, 8>(a, s);
     } else if (a.Kp <= 4608) {
-        rc = rows ? launch_rows<3, 6>(a, s) : launch_wave<18, 16, 8>(a, s);
+        rc = rows ? launch_rows<3, 6>(a, s) : few_wide ? launch_wave<18, 8, 8>(a, s) : launch_wave<18, 16, 8>(a, s);
     } else if (a.Kp <= 6912) {
-        rc = rows ? launch_rows<4, 7>(a, s) : launch_wave<27, 16, 8>(a, s);
+        rc = rows ? launch_rows<4, 7>(a, s) : few_wide ? launch_wave<27, 8, 8>(a, s) : launch_wave<27, 16, 8>(a, s);
     } else if (a.Kp <= 8704) {
         rc = rows ? launch_rows<4, 9>(a, s) : launch_wave<34, 8, 8>(a, s);
     } else {
