@@ -81,7 +81,8 @@ def main() -> int:
     ap.add_argument("--gemv-pool", type=int, default=None,
                     help="distinct weight-pair buffers the GEMV legs walk (default: one per call, so that a batched "
                          "launch reads every weight byte exactly once and nothing can come out of a cache)")
-    ap.add_argument("--cpu-sample-states", type=int, default=2)
+    ap.add_argument("--cpu-sample-states", type=int, default=6,
+                    help="states of the batch the CPU oracle is timed on (about 2 s each on 16 cores)")
     ap.add_argument("--gemv-calls", type=int, default=1000)
     ap.add_argument("--streams", type=int, default=1,
                     help="extra leg: also time the batch as this many concurrent micro-batches on separate HIP streams")
