@@ -103,7 +103,9 @@ def _run_bitlinear(B, R, pl, X, residual=None, taps=True):
     (600, 2560, 6912), (1300, 1000, 4608),                       # few 128 x 128 tiles, long k: k-split launches (ragged N in the second)
     (200, 1000, 4608), (700, 264, 6912),                         # 64 x 32 tiles, k split inside the workgroup
     (2050, 8192, 264), (2048, 8200, 128),      # enough tiles for the 8-wavefront kernel, ragged edges
-    (1024, 640, 2560), (1025, 640, 2560),      # last size of the one-workgroup-per-token quantiser, first of the persistent one
+    (1024, 640, 2560), (1025, 640, 2560),      # last size of the one-workgroup-per-token quantiser, first of the one-wavefront-per-token one
+    (1100, 64, 8640), (1030, 40, 8200),        # widest rows of the one-wavefront-per-token quantiser (34 chunks), ragged k
+    (2100, 64, 6912), (6200, 32, 2560),        # 16-token groups (past 2048 tokens at 6912 wide, past 6144 at 2560 wide)
 ])
 def test_bitlinear_forward_parity(m, n, k):
     B, R = _mods()
@@ -238,7 +240,11 @@ def test_bitlinear_forward_batch(m, n, k, count, bf16):
 # ---------------------------------------------------------------------- FFN
 
 @pytest.mark.parametrize("m,d,f,bf16", [(256, 2560, 6912, True), (37, 256, 392, False), (3, 128, 264, True), (130, 3200, 8640, False),
-                                        (160, 256, 4224, False), (160, 4224, 512, False)])   # k-split down / k-split gate|up (GLU)
+                                        (160, 256, 4224, False), (160, 4224, 512, False),    # k-split down / k-split gate|up (GLU)
+                                        # norms inside the one-wavefront-per-token quantiser: 34, 27 and 10 chunks per row,
+                                        # groups of 8 tokens and (2100 at 6912 wide, 6200 at 2560 wide) of 16
+                                        (1100, 128, 8640, False), (1100, 96, 6912, False), (2100, 96, 6912, False),
+                                        (1200, 2560, 640, True), (6200, 2560, 64, False)])
 def test_ffn_block_parity(m, d, f, bf16):
     B, R = _mods()
     print("ffn_block_forward", m, d, f, flush=True)
