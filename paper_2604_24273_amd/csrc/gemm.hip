@@ -41,6 +41,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr long DIRECT_MAX_WGS = 640;          // 64 x 32 tiles, 8 wavefronts
 constexpr long DIRECT16_MAX_WGS = 512;        // 32 x 32 tiles, 16 wavefronts
 constexpr long DIRECT16_MAX_WGS_GLU = 900;    // 32 x 32 output tiles of the GLU form, 8 wavefronts
+constexpr long NARROW8_MAX_TILES = 320;       // 128 x 128 tiles up to which eight wavefronts share a tile
 
 struct GemmArgs {
     const uint4* A;          // tiled activations, 16 bytes per lane per fragment
@@ -790,7 +791,7 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
     g.group_m = 4;
     const int total = g.tiles_m * g.tiles_n * g.splits;
     const int grid = ((total + 7) / 8) * 8;
-    LaunchTimer tm(WN == 4 ? BRL_KC_GEMM : BRL_KC_GEMM_NARROW, s, g.ops);
+    LaunchTimer tm(WN * TN == 8 ? BRL_KC_GEMM : BRL_KC_GEMM_NARROW, s, g.ops);     // 256-column tiles are the wide class
     if constexpr (W8)
         hipLaunchKernelGGL((gemm_lds_w8_kernel<TM, TN, WM, WN>), dim3(grid), dim3(WM * WN * 64), 0, s, g);
     else
@@ -903,6 +904,11 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     }();
     const long t_wide = (long)((g.nmb + 3) / 4) * ((g.nnb + 7) / 8);
     const long t_narrow = (long)((g.nmb + 3) / 4) * ((g.nnb + 3) / 4);
+    // About one 128 x 128 tile per compute unit or fewer: the same tile on eight wavefronts of 64 x 32 (two per
+    // SIMD from the one resident workgroup instead of one).  Measured at the 2B layer shapes: 640 tokens QKV 21 ->
+    // 17 us, O 19 -> 17; 1024 tokens QKV 21 -> 19, O 20 -> 17, down 37 -> 33; 1792 tokens (280 tiles) 4 to 7 %;
+    // from 400 tiles on the four-wavefront tile is ahead.  (The GLU epilogue needs column pairs: not for it.)
+    if (!glu && t_narrow <= NARROW8_MAX_TILES) return launch_lds<2, 1, 2, 4, false>(g, s);
     const double fill_wide = (double)t_wide / (double)(((t_wide + cus - 1) / cus) * cus);
     const double fill_narrow = (double)t_narrow / (double)(((t_narrow + cus - 1) / cus) * cus);
     if (t_wide >= 2 * cus && fill_wide >= 0.95 * fill_narrow) return launch_lds<2, 2, 2, 4, false>(g, s);
