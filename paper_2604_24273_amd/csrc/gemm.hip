@@ -21,6 +21,8 @@
 //                      are staged in LDS with direct global->LDS loads, double
 //                      buffered; in GLU mode the epilogue writes
 //                      h = max(G,0)^2 U from interleaved gate / up blocks.
+//                      A launch of about one tile per compute unit or fewer puts
+//                      eight wavefronts of 64 x 32 on the 128 x 128 tile.
 //                      gemm_lds_w8_kernel is the same loop on int8 weight blobs.
 //                      With few tiles and a long k several workgroups share a
 //                      tile, each on its own k range (raw int32 partial tiles,

@@ -106,6 +106,7 @@ def _run_bitlinear(B, R, pl, X, residual=None, taps=True):
     (1024, 640, 2560), (1025, 640, 2560),      # last size of the one-workgroup-per-token quantiser, first of the one-wavefront-per-token one
     (1100, 64, 8640), (1030, 40, 8200),        # widest rows of the one-wavefront-per-token quantiser (34 chunks), ragged k
     (2100, 64, 6912), (6200, 32, 2560),        # 16-token groups (past 2048 tokens at 6912 wide, past 6144 at 2560 wide)
+    (1100, 40, 9216),                          # the widest rows supported: four wavefronts per token
 ])
 def test_bitlinear_forward_parity(m, n, k):
     B, R = _mods()
@@ -244,7 +245,8 @@ def test_bitlinear_forward_batch(m, n, k, count, bf16):
                                         # norms inside the one-wavefront-per-token quantiser: 34, 27 and 10 chunks per row,
                                         # groups of 8 tokens and (2100 at 6912 wide, 6200 at 2560 wide) of 16
                                         (1100, 128, 8640, False), (1100, 96, 6912, False), (2100, 96, 6912, False),
-                                        (1200, 2560, 640, True), (6200, 2560, 64, False)])
+                                        (1200, 2560, 640, True), (6200, 2560, 64, False),
+                                        (1100, 64, 9000, False)])      # four wavefronts per token, ragged k
 def test_ffn_block_parity(m, d, f, bf16):
     B, R = _mods()
     print("ffn_block_forward", m, d, f, flush=True)
