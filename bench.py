@@ -37,8 +37,8 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
 # summary it was copied from and the kernel it refers to, and is reset to None whenever that kernel changes
 # until the counters have been taken again.
 ROOFLINE_TRAFFIC = {
-    # FETCH_SIZE 76 254.9 KiB x 2.0 + WRITE_SIZE 172 032 KiB x 1.0, averaged over the QKV and gate|up launches
-    "encoder-2b": {"bytes": 332.3e6, "kernel": "gemm_lds_kernel<2,2,2,4>",
+    # FETCH_SIZE 75 400.6 KiB x 2.0 + WRITE_SIZE 172 032 KiB x 1.0, averaged over the QKV and gate|up launches
+    "encoder-2b": {"bytes": 330.6e6, "kernel": "gemm_lds_kernel<2,2,2,4>",
                    "source": "profiles/bench_encoder_2b_hbm_traffic_counters.txt"},
     "prefill-3b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
     "rl-states-2b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
