@@ -30,6 +30,9 @@ if ROOT not in sys.path:
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, TOP/s
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E, GB/s
+# timing classes of the library that are BitLinear matrix products (the last: the wide tile on the q | k | v product,
+# with the epilogue that writes the attention kernel's operands)
+GEMM_CLASSES = ("gemm", "gemm_narrow", "gemm_qkv_attn")
 
 
 # HBM bytes per launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter
@@ -191,8 +194,8 @@ def main() -> int:
     gemm_avg_ms = gemm["ms_per_step"] / gemm_launches
     ops_per_launch = gemm["int8_ops_per_step"] / gemm_launches
     achieved_tops = ops_per_launch / (gemm_avg_ms * 1e-3) / 1e12 if gemm_avg_ms > 0 else 0.0
-    all_gemm_ms = gemm["ms_per_step"] + classes["gemm_narrow"]["ms_per_step"]
-    all_gemm_ops = gemm["int8_ops_per_step"] + classes["gemm_narrow"]["int8_ops_per_step"]
+    all_gemm_ms = sum(classes[c]["ms_per_step"] for c in GEMM_CLASSES)
+    all_gemm_ops = sum(classes[c]["int8_ops_per_step"] for c in GEMM_CLASSES)
     roofline = {"bound": "mfma", "kernel": "gemm_lds_kernel<2,2,2,4> (int8 MFMA BitLinear, 128x256 tile)",
                 "achieved": round(achieved_tops, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": ROOFLINE_TRAFFIC[args.workload]["bytes"],
@@ -417,7 +420,7 @@ def bench_ffn(torch, B, R, synth, calls: int = 200, m: int = 256, d: int = 2560,
         n, ms, ops = B.brl_timing_read_ops(kc)
         if n:
             per[name] = {"launches_per_call": n / calls, "us_per_call": round(ms / calls * 1e3, 3)}
-        if name in ("gemm", "gemm_narrow"):
+        if name in GEMM_CLASSES:
             gemm_ms += ms
             gemm_ops += ops
             gemm_n += n
@@ -463,7 +466,7 @@ def bench_prefill_3b(torch, B, R, synth, np, states: int = 64, tokens: int = 512
         n, kms, ops = B.brl_timing_read_ops(kc)
         if n:
             per[name] = round(kms / steps, 3)
-        if name in ("gemm", "gemm_narrow"):
+        if name in GEMM_CLASSES:
             gemm_ms += kms
             gemm_ops += ops
     ops_step = 2.0 * linear_macs_per_token(shape) * states * tokens

@@ -249,7 +249,11 @@ int ffn_block_forward(const brl_ffn_weights* w /* HOST */, const void* x, int x_
  * (mean pooling is the only pooling; the paper says only that h_t is a vector
  * of the hidden width).
  * States are independent; large batches are processed in micro-batches of
- * whole states inside the call.  Like every *_forward here the call only
+ * whole states inside the call.  How the stages are cut into kernels depends
+ * on the shapes only (with head_dim 128, S a multiple of 32 and a few thousand
+ * token rows the q | k | v product writes the attention operands itself instead
+ * of fp32 rows); a state's result does not: it has the same bits in a batch of
+ * any size, padded or stored back to back.  Like every *_forward here the call only
  * enqueues kernels on `stream` (no allocation, no synchronisation), so a
  * sequence of calls can be captured into a HIP graph - after one ordinary call
  * of the same shapes, because the first use of a kernel queries the device's
@@ -481,7 +485,8 @@ int ppo_head_update(const brl_ppo_config* cfg /* HOST */, float* params, float* 
 #define BRL_KC_ATTENTION        4
 #define BRL_KC_OTHER            5   /* embedding, pooling, heads, fills */
 #define BRL_KC_GEMM_NARROW      6   /* int8 MFMA BitLinear, 128 x 128 tile and the few-token kernels */
-#define BRL_KC_COUNT            7
+#define BRL_KC_GEMM_QKV_ATTN    7   /* the 128 x 256 tile on the q | k | v product, writing the attention kernel's operands */
+#define BRL_KC_COUNT            8
 
 int brl_timing_enable(int on);
 int brl_timing_read(int kernel_class, long long* launches, double* total_ms);

@@ -402,8 +402,8 @@ def ppo_head_update(cfg: brl_ppo_config, params: torch.Tensor, adam_m: torch.Ten
 
 
 BRL_KC_QUANTIZE_WEIGHTS, BRL_KC_ACT_QUANT, BRL_KC_GEMM, BRL_KC_GEMV, BRL_KC_ATTENTION, BRL_KC_OTHER, \
-    BRL_KC_GEMM_NARROW = range(7)
-KERNEL_CLASSES = ("quantize_weights", "act_quant", "gemm", "gemv", "attention", "other", "gemm_narrow")
+    BRL_KC_GEMM_NARROW, BRL_KC_GEMM_QKV_ATTN = range(8)
+KERNEL_CLASSES = ("quantize_weights", "act_quant", "gemm", "gemv", "attention", "other", "gemm_narrow", "gemm_qkv_attn")
 
 
 def brl_timing_enable(on: bool) -> None:

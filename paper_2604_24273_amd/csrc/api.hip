@@ -192,6 +192,7 @@ struct EncWs {
     int states_mb;      // states per micro-batch
     size_t x_off, act_off, big_off, cos_off, sin_off, rinv_off, frag_off, total;
     int big_ld_qkv;
+    bool q_frags;       // the fragment area also has room for q fragments (q | k | v product with the attention-operand epilogue)
 };
 
 constexpr int ENC_MB_TOKENS = 32768;
@@ -217,7 +218,9 @@ EncWs encoder_ws_layout(const brl_encoder* e, int B, int S) {
     L.sin_off = L.cos_off + tbl;
     L.rinv_off = L.sin_off + tbl;
     L.frag_off = L.rinv_off + round_up_sz(Mt * 4, ALIGN);
-    L.total = L.frag_off + round_up_sz(attention_mfma_ws_bytes(smb, S, e->n_heads, e->n_kv_heads, e->head_dim), ALIGN);
+    L.q_frags = e->attn_precision == BRL_ATTN_MFMA && e->weight_format != BRL_W_INT8 && e->head_dim == 128 && S % 32 == 0;
+    L.total = L.frag_off +
+              round_up_sz(attention_mfma_ws_bytes(smb, S, e->n_heads, e->n_kv_heads, e->head_dim, L.q_frags), ALIGN);
     L.big_ld_qkv = dq + 2 * dkv;
     return L;
 }
@@ -641,6 +644,21 @@ int run_encoder_microbatch(const brl_encoder* enc, const EncWs& L, char* base, c
         add_seg(wqkv, w.wq_packed, w.wq_beta, dq);
         add_seg(wqkv, w.wk_packed, w.wk_beta, dkv);
         add_seg(wqkv, w.wv_packed, w.wv_beta, dkv);
+        // Uniform batches at head_dim 128 with enough rows for the wide tile: the product writes the attention
+        // kernel's operands itself (no fp32 q | k | v rows, no pack kernel); same bits as the two-step form.
+        const bool fused = L.q_frags && !sm.cu && !w8 && enc->attn_precision == BRL_ATTN_MFMA &&
+                           gemm_attn_eligible(Mt, enc->n_heads, enc->n_kv_heads, dh, S);
+        if (fused) {
+            AttnOperands ao;
+            ao.cos_t = cos_t; ao.sin_t = sin_t;
+            ao.qscale = (float)(1.0 / sqrt((double)dh)) * 1.4426950408889634f;
+            ao.kvf = base + L.frag_off;
+            ao.qf = attention_q_fragments(base + L.frag_off, nb, S, enc->n_kv_heads, dh);
+            ao.S = S; ao.n_heads = enc->n_heads; ao.n_kv_heads = enc->n_kv_heads;
+            if (int rc = launch_gemm_attn(act, wqkv, Mt, d, ao, s)) return rc;
+            if (int rc = launch_attention_mfma_prepacked(nb, S, enc->n_heads, enc->n_kv_heads, base + L.frag_off, att, s))
+                return rc;
+        } else {
         if (int rc = launch_gemm(act, wqkv, Mt, dq + 2 * dkv, d, qkv, L.big_ld_qkv, nullptr, nullptr, 0, s)) return rc;
         if (enc->attn_precision == BRL_ATTN_MFMA) {
             if (int rc = launch_attention_mfma(qkv, L.big_ld_qkv, nb, S, sm, enc->n_heads, enc->n_kv_heads, dh, cos_t,
@@ -650,6 +668,7 @@ int run_encoder_microbatch(const brl_encoder* enc, const EncWs& L, char* base, c
             if (int rc = launch_attention_f32(qkv, L.big_ld_qkv, nb, S, sm, enc->n_heads, enc->n_kv_heads, dh, cos_t,
                                               sin_t, att, s))
                 return rc;
+        }
         }
         QuantArgs qo;
         memset(&qo, 0, sizeof(qo));
@@ -703,6 +722,7 @@ constexpr int PACK_MB_STATES = 2048;      // states per micro-batch of the packe
 // at most PACK_MB_STATES states.
 EncWs encoder_packed_ws_layout(const brl_encoder* e, int B, int T, int max_len) {
     EncWs L;
+    L.q_frags = false;       // states stored back to back do not start at multiples of 32 rows
     memset(&L, 0, sizeof(L));
     L.states_mb = B < PACK_MB_STATES ? B : PACK_MB_STATES;
     size_t Mt = (size_t)(T < ENC_MB_TOKENS ? T : ENC_MB_TOKENS);

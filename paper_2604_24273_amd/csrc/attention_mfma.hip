@@ -25,6 +25,9 @@
 //                     filled by direct global->LDS loads, double buffered.
 // V fragments are stored transposed with the keys of a block permuted so that
 // the 8 keys a lane's probabilities stand for are 16 contiguous bytes.
+// Where the q | k | v product has already written the fragments (its epilogue does for
+// uniform batches at head_dim 128, q included), only attention_frag_kernel runs, in the
+// form that reads its q fragments straight into registers (launch_attention_mfma_prepacked).
 #include "common.hpp"
 
 
@@ -176,6 +179,7 @@ struct FragArgs {
     const float* sin_t;
     float qscale;         // softmax scale in log2 units, folded into q
     const uint4* KVF;
+    const uint4* QF;      // q fragments [B][Hq][NRB][KS][hi,lo][64 lanes] (only where the producer wrote them)
     int B, S, NRB, Hq, Hkv, dh;
     SeqMap sm;
     int n_work;           // B * Hkv * chunks
@@ -255,7 +259,9 @@ struct AttnTile {
 // measured shapes (fewer resident workgroups, longer tails).
 constexpr int ATTN_WPG = 4;
 constexpr int SHORT_MAX_WORK = 1024;      // beyond this many workgroups the two-kernel path keeps more of them resident
-template <int DHP, int VW, int WPG>
+// QPRE: the q rows arrive as fragments (rotated, scaled, split by the kernel that produced them) and are read
+// straight into the operand registers; otherwise they are staged from the fp32 rows here.
+template <int DHP, int VW, int WPG, bool QPRE = false>
 __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a) {
     using T = AttnTile<DHP>;
     constexpr int KS = T::KS, DB = T::DB;
@@ -289,7 +295,14 @@ __global__ __launch_bounds__(WPG * 64, 2) void attention_frag_kernel(FragArgs a)
 
     v8h qh[KS], ql[KS];
     const int qpos = qb * 32 + (lane & 31);
-    {
+    if constexpr (QPRE) {
+        const uint4* qf = a.QF + ((size_t)(b * a.Hq + head) * a.NRB + max(qb, 0)) * (KS * 2 * 64) + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qh[ks] = __builtin_bit_cast(v8h, qf[(ks * 2 + 0) * 64]);
+            ql[ks] = __builtin_bit_cast(v8h, qf[(ks * 2 + 1) * 64]);
+        }
+    } else {
         // the stage buffers are free before the first key block arrives: the q rows are parked there,
         // four wavefronts at a time
         char* region = reinterpret_cast<char*>((wave & 2) ? stage1 : stage0) + (wave & 1) * (128 * DHP);
@@ -479,11 +492,14 @@ inline int padded_head_dim(int dh) { return dh <= 32 ? 32 : (dh <= 64 ? 64 : 128
 
 }  // namespace
 
-size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim) {
-    (void)n_heads;
+size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim, bool q_frags) {
     const int dhp = padded_head_dim(head_dim);
     const size_t nrb = (size_t)(S + 31) / 32, ks = dhp / 16, db = dhp / 32;
-    return (size_t)B * n_kv_heads * nrb * (ks * 2 + db * 4) * 1024;
+    return (size_t)B * n_kv_heads * nrb * (ks * 2 + db * 4) * 1024 + (q_frags ? (size_t)B * n_heads * nrb * ks * 2 * 1024 : 0);
+}
+
+void* attention_q_fragments(void* frag_ws, int B, int S, int n_kv_heads, int head_dim) {
+    return static_cast<char*>(frag_ws) + attention_mfma_ws_bytes(B, S, 0, n_kv_heads, head_dim, false);
 }
 
 namespace {
@@ -521,7 +537,7 @@ int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& 
     FragArgs f;
     f.qkv = qkv; f.ld = ld; f.cos_t = cos_t; f.sin_t = sin_t;
     f.qscale = (float)(1.0 / sqrt((double)head_dim)) * 1.4426950408889634f;
-    f.KVF = p.KVF; f.B = B; f.S = S; f.NRB = nrb; f.Hq = n_heads; f.Hkv = n_kv_heads; f.dh = head_dim;
+    f.KVF = p.KVF; f.QF = nullptr; f.B = B; f.S = S; f.NRB = nrb; f.Hq = n_heads; f.Hkv = n_kv_heads; f.dh = head_dim;
     f.sm = sm;
     f.n_work = B * n_kv_heads * chunks;
     f.out = out;
@@ -536,6 +552,32 @@ int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& 
         if (v4) launch_pair<128, 4>(p, f, pgrid, f.n_work, s); else launch_pair<128, 2>(p, f, pgrid, f.n_work, s);
     }
     BRL_LAUNCH_CHECK("attention_mfma");
+    return BRL_OK;
+}
+
+// The fragments are already in frag_ws (K / V, then q): written by the epilogue of the q | k | v product.
+int launch_attention_mfma_prepacked(int B, int S, int n_heads, int n_kv_heads, void* frag_ws, float* out, hipStream_t s) {
+    constexpr int dh = 128;
+    if (S % 32 != 0 || n_heads % n_kv_heads != 0) {
+        set_error("attention: prepacked operands need 32 | S (S = %d) and whole head groups", S);
+        return BRL_EINVAL;
+    }
+    const int nrb = S / 32;
+    const int group = n_heads / n_kv_heads;
+    const int chunks = (group * nrb + ATTN_WPG - 1) / ATTN_WPG;
+    FragArgs f;
+    f.qkv = nullptr; f.ld = 0; f.cos_t = nullptr; f.sin_t = nullptr;
+    f.qscale = 0.f;
+    f.KVF = static_cast<const uint4*>(frag_ws);
+    f.QF = static_cast<const uint4*>(attention_q_fragments(frag_ws, B, S, n_kv_heads, dh));
+    f.B = B; f.S = S; f.NRB = nrb; f.Hq = n_heads; f.Hkv = n_kv_heads; f.dh = dh;
+    f.sm.cu = nullptr; f.sm.b0 = 0;
+    f.n_work = B * n_kv_heads * chunks;
+    f.out = out;
+    LaunchTimer tm(BRL_KC_ATTENTION, s);
+    const dim3 agrid((unsigned)(8 * ((f.n_work + 7) / 8)));
+    hipLaunchKernelGGL((attention_frag_kernel<128, 4, ATTN_WPG, true>), agrid, dim3(ATTN_WPG * 64), 0, s, f);
+    BRL_LAUNCH_CHECK("attention_mfma (prepacked)");
     return BRL_OK;
 }
 

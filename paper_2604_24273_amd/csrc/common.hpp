@@ -129,6 +129,19 @@ int launch_act_quant(const QuantArgs& a, const ActBuf& out, hipStream_t s);
 int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K,
                 float* y, int ldy, const float* residual, int32_t* acc_dbg, int glu, hipStream_t s, int res_bf16 = 0);
 
+// The q | k | v product of a uniform batch (head_dim 128, 32 | S) written as the operands of the matrix-core
+// attention kernel instead of fp32 rows: rotated q (scaled) and k as fp16 hi / lo fragments, v transposed.
+struct AttnOperands {
+    const float* cos_t;   // [S][64]
+    const float* sin_t;
+    float qscale;
+    void* kvf;            // K / V fragments, as attn_pack_kernel lays them out
+    void* qf;             // q fragments [B][Hq][S/32][8][hi,lo][64 lanes] of 16 bytes
+    int S, n_heads, n_kv_heads;
+};
+bool gemm_attn_eligible(int M, int n_heads, int n_kv_heads, int head_dim, int S);
+int launch_gemm_attn(const ActBuf& a, const WeightSegs& w, int M, int K, const AttnOperands& out, hipStream_t s);
+
 // bandwidth-bound GEMV (M <= 4), activation quantisation fused
 int launch_gemv(const void* x, int x_dtype, int M, int K, int N, const uint32_t* packed, const float* beta,
                 float eps_act, float* y, const float* residual, int8_t* xq_dbg, float* absmax_dbg,
@@ -154,7 +167,9 @@ __device__ inline int seq_len(const SeqMap& m, int b, int S) {
 int launch_rope_table(float* cos_t, float* sin_t, int S, int head_dim, float theta, hipStream_t s);
 int launch_attention_f32(const float* qkv, int ld, int B, int S, const SeqMap& sm, int n_heads, int n_kv_heads,
                          int head_dim, const float* cos_t, const float* sin_t, float* out, hipStream_t s);
-size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim);
+size_t attention_mfma_ws_bytes(int B, int S, int n_heads, int n_kv_heads, int head_dim, bool q_frags = false);
+void* attention_q_fragments(void* frag_ws, int B, int S, int n_kv_heads, int head_dim);   // where the q fragments start
+int launch_attention_mfma_prepacked(int B, int S, int n_heads, int n_kv_heads, void* frag_ws, float* out, hipStream_t s);
 int launch_attention_mfma(const float* qkv, int ld, int B, int S, const SeqMap& sm, int n_heads, int n_kv_heads,
                           int head_dim, const float* cos_t, const float* sin_t, void* frag_ws, float* out, hipStream_t s);
 int launch_embed(const uint16_t* table, const int32_t* ids, int M, int d, int vocab, float* x, hipStream_t s);

@@ -23,6 +23,10 @@
 //                      h = max(G,0)^2 U from interleaved gate / up blocks.
 //                      A launch of about one tile per compute unit or fewer puts
 //                      eight wavefronts of 64 x 32 on the 128 x 128 tile.
+//                      gemm_lds_attn_kernel is the wide tile on the q | k | v product of a
+//                      uniform batch at head_dim 128: its epilogue rotates q and k and
+//                      writes them and v as the fp16 hi / lo fragments the attention
+//                      kernel reads (no fp32 rows, no pack kernel).
 //                      gemm_lds_w8_kernel is the same loop on int8 weight blobs.
 //                      With few tiles and a long k several workgroups share a
 //                      tile, each on its own k range (raw int32 partial tiles,
@@ -31,6 +35,8 @@
 //                      wavefronts of a workgroup split k and finish the tile
 //                      together through LDS.
 // launch_gemm picks among them by how many workgroups each would make.
+#include <cstring>
+
 #include "common.hpp"
 
 namespace brl {
@@ -69,6 +75,15 @@ struct GemmArgs {
     int splits;              // > 1: k is cut into `splits` ranges of sb_per_split super-blocks, one workgroup per
     int sb_per_split;        //      (tile, range); raw int32 partial tiles go to `partials` [splits][M][nnb * 32]
     int32_t* partials;       //      and splitk_epilogue_kernel finishes the product
+    // attention-operand epilogue (the q | k | v product of a uniform batch, head_dim 128): instead of fp32 rows the
+    // kernel writes what the attention kernel reads - q and k rotated (q also scaled) as fp16 hi / lo MFMA fragments,
+    // v transposed fragments - see epilogue_attn
+    const float* att_cos;    // [S][64]
+    const float* att_sin;
+    float att_qscale;
+    uint4* att_kvf;          // [B][Hkv][NRB][ K: [8][hi,lo] | V: [4][2][hi,lo] ][64 lanes]
+    uint4* att_qf;           // [B][Hq][NRB][8][hi,lo][64 lanes]
+    int att_S, att_nrb, att_Hq, att_Hkv;
 };
 
 // residual element(s) at flat index o (o % 4 == 0 for the four-wide form)
@@ -370,6 +385,127 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
     }
 }
 
+// Attention operands straight from the q | k | v product (head_dim 128, 32 | S, uniform layout).  A wavefront's
+// 64 columns are one half of a head; the rotary partner of a column sits 64 columns away, in the wavefront next
+// to it (wave ^ 1), so both turn their half blocks through LDS and read each other's.  The arithmetic per
+// element is the one the separate pack kernel applies to the fp32 rows ((x c -+ x' s) * scale, then hi = fp16,
+// lo = fp16(t - hi)) on the same fp32 values the plain epilogue would have written, so the fragments hold the
+// same bits.  v needs no turn: its transposed fragment order is the accumulator's own lane order.
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+// fp32 -> fp16 of a value the compiler must first round to fp32: without the barrier it folds the last multiply
+// into the conversion (v_fma_mixlo_f16, one rounding instead of two), and the hi part used for the lo part then
+// differs, on ties, from the one that is stored - and from what the pack kernel makes of the fp32 rows in memory
+__device__ inline _Float16 half_of_rounded(float x) {
+    asm("" : "+v"(x));
+    return (_Float16)x;
+}
+
+template <int TM, int TN>
+__device__ inline void epilogue_attn(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, const float (&beta)[TN],
+                                     int lane, int* scr, const int* scr_partner) {
+    static_assert(TN == 2, "a wavefront holds one half of a 128-wide head");
+    constexpr int LD = Epi<TM, TN>::LD;
+    constexpr int KS = 8, DB = 4, KVFR = KS * 2 + DB * 4;       // 1 KB fragments per key block at head_dim 128
+    int seg, col0, ncols;
+    block_columns(g, min(nb0, g.nnb - 1), seg, col0, ncols);
+    const bool cols_live = nb0 < g.nnb;
+    const int head_all = col0 >> 7;                             // head over q | k | v
+    const int half = (col0 >> 6) & 1;
+    const float bsel = beta[0];                                 // both column blocks lie in one head, i.e. one matrix
+    const int2* rows = park_rows<TM, TN>(g, mb0, lane, scr);
+
+    if (seg == 2 && cols_live) {
+        // v: lane (column dl of block j, h) holds the keys 16 tt + 8 (e >> 2) + 4 h + (e & 3) of step tt
+        const int kvh = head_all - g.att_Hq - g.att_Hkv;
+        const int dl = lane & 31, h = lane >> 5;
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mb = mb0 + i;
+            if (mb >= g.nmb) continue;
+            const int b = (mb * 32) / g.att_S, rb = ((mb * 32) % g.att_S) >> 5;
+            uint4* dst = g.att_kvf + ((size_t)(b * g.att_Hkv + kvh) * g.att_nrb + rb) * (KVFR * 64);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int r = half * 2 + j;
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+                    half8 hi, lo;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int v = 8 * tt + e;
+                        const int2 rw = rows[i * 32 + 8 * (v >> 2) + 4 * h + (v & 3)];
+                        const float y = ((float)(acc[i][j][v] - rw.y) * __int_as_float(rw.x)) * bsel;
+                        const _Float16 yh = half_of_rounded(y);
+                        hi[e] = yh;
+                        lo[e] = (_Float16)(y - (float)yh);
+                    }
+                    dst[(KS * 2 + (r * 2 + tt) * 2 + 0) * 64 + h * 32 + dl] = __builtin_bit_cast(uint4, hi);
+                    dst[(KS * 2 + (r * 2 + tt) * 2 + 1) * 64 + h * 32 + dl] = __builtin_bit_cast(uint4, lo);
+                }
+            }
+        }
+    }
+
+    // q and k: four half blocks of 16 token rows; every wavefront of the workgroup takes part in the barriers
+    constexpr int LPR = TN * 8, RPP = 64 / LPR, NP = 16 / RPP;
+    const int c4 = lane % LPR, r0 = lane / LPR;
+    const bool rot = seg != 2 && cols_live;
+    const float scale = seg == 0 ? g.att_qscale : 1.0f;
+#pragma unroll
+    for (int idx = 0; idx < 2 * TM; ++idx) {
+        const int mb = mb0 + (idx >> 1), hb = idx & 1;
+        const int mbc = min(mb, g.nmb - 1);
+        const int b = (mbc * 32) / g.att_S, rb = ((mbc * 32) % g.att_S) >> 5;
+        // the rotary factors of this half block's rows are requested before the turn and the barrier
+        float4 cs[NP], sn[NP];
+        if (rot) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int pos = rb * 32 + hb * 16 + p * RPP + r0;        // position inside the state
+                cs[p] = *reinterpret_cast<const float4*>(g.att_cos + (size_t)pos * 64 + 4 * c4);
+                sn[p] = *reinterpret_cast<const float4*>(g.att_sin + (size_t)pos * 64 + 4 * c4);
+            }
+            scatter_half<TM, TN>(acc, idx >> 1, hb, lane, scr);
+        }
+        __syncthreads();
+        if (rot && mb < g.nmb) {
+            uint4* dst = seg == 0
+                ? g.att_qf + ((size_t)(b * g.att_Hq + head_all) * g.att_nrb + rb) * (KS * 2 * 64)
+                : g.att_kvf + ((size_t)(b * g.att_Hkv + (head_all - g.att_Hq)) * g.att_nrb + rb) * (KVFR * 64);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int row = p * RPP + r0;                    // row of the half block
+                const int2 rw = rows[idx * 16 + row];
+                const float d = __int_as_float(rw.x);
+                const int sq = rw.y;
+                const int4 a = *reinterpret_cast<const int4*>(&scr[row * LD + 4 * c4]);
+                const int4 pa = *reinterpret_cast<const int4*>(&scr_partner[row * LD + 4 * c4]);
+                const int ai[4] = {a.x, a.y, a.z, a.w}, pi[4] = {pa.x, pa.y, pa.z, pa.w};
+                const float cf[4] = {cs[p].x, cs[p].y, cs[p].z, cs[p].w}, sf[4] = {sn[p].x, sn[p].y, sn[p].z, sn[p].w};
+                half4 hi, lo;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float xs = ((float)(ai[q] - sq) * d) * bsel;
+                    const float xp = ((float)(pi[q] - sq) * d) * bsel;
+                    const float t = (half == 0 ? (xs * cf[q] - xp * sf[q]) : (xs * cf[q] + xp * sf[q])) * scale;
+                    const _Float16 th = half_of_rounded(t);
+                    hi[q] = th;
+                    lo[q] = (_Float16)(t - (float)th);
+                }
+                const int comp = half * 64 + 4 * c4;             // first of the lane's four components of the head
+                const int ks = comp >> 4, kg = (comp >> 3) & 1, e0 = comp & 7;
+                char* slot = reinterpret_cast<char*>(dst + (ks * 2 + 0) * 64 + kg * 32 + hb * 16 + row) + e0 * 2;
+                *reinterpret_cast<half4*>(slot) = hi;
+                *reinterpret_cast<half4*>(slot + 1024) = lo;     // the lo plane is the next 1 KB fragment
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // k-split launches: the raw accumulators of this workgroup's k range, row-major, 16 bytes per lane
 template <int TM, int TN>
 __device__ inline void epilogue_partial(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, int split, int lane,
@@ -509,7 +645,7 @@ struct LdsTile {
     }
 };
 
-template <int TM, int TN, int WM, int WN, bool W8>
+template <int TM, int TN, int WM, int WN, bool W8, bool ATTN = false>
 __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     using Tile = LdsTile<TM, TN, WM, WN, W8>;
     constexpr int NW = Tile::NW;
@@ -590,13 +726,26 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     __syncthreads();
     static_assert((NW / 2) * Epi<TM, TN>::REGION * 4 <= Tile::STAGE * 16, "half of the epilogue regions per stage");
     int* scr = reinterpret_cast<int*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * Epi<TM, TN>::REGION;
-    if (g.splits > 1) epilogue_partial<TM, TN>(g, acc, mb0, nb0, split, lane, scr);
-    else epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
+    if constexpr (ATTN) {
+        static_assert(WN % 2 == 0 && (NW / 2) % 2 == 0, "a wavefront and its neighbour wave ^ 1 share a stage buffer");
+        const int* scr_partner =
+            reinterpret_cast<const int*>(wave < NW / 2 ? stage0 : stage1) + ((wave ^ 1) % (NW / 2)) * Epi<TM, TN>::REGION;
+        epilogue_attn<TM, TN>(g, acc, mb0, nb0, beta, lane, scr, scr_partner);
+    } else if (g.splits > 1) {
+        epilogue_partial<TM, TN>(g, acc, mb0, nb0, split, lane, scr);
+    } else {
+        epilogue<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
+    }
 }
 
 template <int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64, 4) void gemm_lds_kernel(GemmArgs g) {
     gemm_lds_body<TM, TN, WM, WN, false>(g);
+}
+
+// the wide tile with the attention-operand epilogue (q | k | v product)
+__global__ __launch_bounds__(512, 4) void gemm_lds_attn_kernel(GemmArgs g) {
+    gemm_lds_body<2, 2, 2, 4, false, true>(g);
 }
 
 // the same tile loop on int8 weight blobs
@@ -809,9 +958,83 @@ int launch_lds(GemmArgs& g, hipStream_t s) {
 
 }  // namespace
 
+namespace {
+
+int device_cus() {
+    static const int cus = [] {        // initialised once, thread-safe
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            n = 256;
+        }
+        return n;
+    }();
+    return cus;
+}
+
+// would launch_gemm run this many-token product on the 128 x 256 tile?  (the rule at the end of launch_gemm)
+bool wide_tile_chosen(int nmb, int nnb) {
+    const int cus = device_cus();
+    const long t_wide = (long)((nmb + 3) / 4) * ((nnb + 7) / 8);
+    const long t_narrow = (long)((nmb + 3) / 4) * ((nnb + 3) / 4);
+    const double fill_wide = (double)t_wide / (double)(((t_wide + cus - 1) / cus) * cus);
+    const double fill_narrow = (double)t_narrow / (double)(((t_narrow + cus - 1) / cus) * cus);
+    return t_wide >= 2 * cus && fill_wide >= 0.95 * fill_narrow;
+}
+
+}  // namespace
+
+bool gemm_attn_eligible(int M, int n_heads, int n_kv_heads, int head_dim, int S) {
+    const int N = (n_heads + 2 * n_kv_heads) * head_dim;
+    return head_dim == 128 && S % 32 == 0 && M % 32 == 0 && M % S == 0 && N % 256 == 0 && wide_tile_chosen(M / 32, N / 32);
+}
+
+int launch_gemm_attn(const ActBuf& a, const WeightSegs& w, int M, int K, const AttnOperands& out, hipStream_t s) {
+    if (w.count != 3 || w.w8 || !gemm_attn_eligible(M, out.n_heads, out.n_kv_heads, 128, out.S) ||
+        w.n_end[0] != out.n_heads * 128 || w.n_end[1] - w.n_end[0] != out.n_kv_heads * 128 ||
+        w.n_end[2] - w.n_end[1] != out.n_kv_heads * 128) {
+        set_error("gemm: the attention-operand epilogue needs the q | k | v product of a uniform batch at head_dim 128");
+        return BRL_EINVAL;
+    }
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = reinterpret_cast<const uint4*>(a.q);
+    g.dscale = a.dscale;
+    g.sumq = a.sumq;
+    g.wfrag = 64;
+    g.nseg = 3;
+    for (int i = 0; i < 3; ++i) {
+        g.wp[i] = reinterpret_cast<const uint4*>(w.packed[i]);
+        g.beta[i] = w.beta[i];
+        g.nb_end[i] = w.nb_end[i];
+        g.n_end[i] = w.n_end[i];
+    }
+    g.M = M;
+    g.nmb = M / NB;
+    g.nnb = w.nb_end[2];
+    g.nsb = round_up(K, SBK) / SBK;
+    g.ops = 2.0 * (double)M * (double)w.n_end[2] * (double)K;
+    g.splits = 1;
+    g.sb_per_split = g.nsb;
+    g.att_cos = out.cos_t; g.att_sin = out.sin_t; g.att_qscale = out.qscale;
+    g.att_kvf = static_cast<uint4*>(out.kvf); g.att_qf = static_cast<uint4*>(out.qf);
+    g.att_S = out.S; g.att_nrb = out.S / 32; g.att_Hq = out.n_heads; g.att_Hkv = out.n_kv_heads;
+    g.tiles_m = (g.nmb + 3) / 4;
+    g.tiles_n = (g.nnb + 7) / 8;
+    g.group_m = 4;
+    const int total = g.tiles_m * g.tiles_n;
+    const int grid = ((total + 7) / 8) * 8;
+    LaunchTimer tm(BRL_KC_GEMM_QKV_ATTN, s, g.ops);
+    hipLaunchKernelGGL(gemm_lds_attn_kernel, dim3(grid), dim3(512), 0, s, g);
+    BRL_LAUNCH_CHECK("gemm_lds_attn_kernel");
+    return BRL_OK;
+}
+
 int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float* y, int ldy,
                 const float* residual, int32_t* acc_dbg, int glu, hipStream_t s, int res_bf16) {
     GemmArgs g;
+    memset(&g, 0, sizeof(g));
     g.A = reinterpret_cast<const uint4*>(a.q);
     g.dscale = a.dscale;
     g.sumq = w.w8 ? nullptr : a.sumq;
@@ -895,25 +1118,13 @@ int launch_gemm(const ActBuf& a, const WeightSegs& w, int M, int N, int K, float
     // 128 x 256 workgroup tiles (8 wavefronts of 64 x 64, two workgroups per CU) or 128 x 128 tiles
     // (4 wavefronts, four per CU).  The wide tile does about 5 % more work per unit time; the narrow
     // one wins when it spreads the tiles more evenly over the compute units.
-    static const int cus = [] {        // initialised once, thread-safe
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
-            (void)hipGetLastError();
-            n = 256;
-        }
-        return n;
-    }();
-    const long t_wide = (long)((g.nmb + 3) / 4) * ((g.nnb + 7) / 8);
     const long t_narrow = (long)((g.nmb + 3) / 4) * ((g.nnb + 3) / 4);
     // About one 128 x 128 tile per compute unit or fewer: the same tile on eight wavefronts of 64 x 32 (two per
     // SIMD from the one resident workgroup instead of one).  Measured at the 2B layer shapes: 640 tokens QKV 21 ->
     // 17 us, O 19 -> 17; 1024 tokens QKV 21 -> 19, O 20 -> 17, down 37 -> 33; 1792 tokens (280 tiles) 4 to 7 %;
     // from 400 tiles on the four-wavefront tile is ahead.  (The GLU epilogue needs column pairs: not for it.)
     if (!glu && t_narrow <= NARROW8_MAX_TILES) return launch_lds<2, 1, 2, 4, false>(g, s);
-    const double fill_wide = (double)t_wide / (double)(((t_wide + cus - 1) / cus) * cus);
-    const double fill_narrow = (double)t_narrow / (double)(((t_narrow + cus - 1) / cus) * cus);
-    if (t_wide >= 2 * cus && fill_wide >= 0.95 * fill_narrow) return launch_lds<2, 2, 2, 4, false>(g, s);
+    if (wide_tile_chosen(g.nmb, g.nnb)) return launch_lds<2, 2, 2, 4, false>(g, s);
     return launch_lds<2, 2, 2, 2, false>(g, s);
 }
 

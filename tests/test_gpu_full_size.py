@@ -164,3 +164,37 @@ def test_encoder_micro_batching_is_invisible():
                               synth.final_norm_gain(2, shape), cfg, lengths=lengths[sample])
     for j, b in enumerate(sample):
         assert _cos(h.cpu().numpy()[b], h_ref[j]) >= 0.999
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("n_states,S", [(128, 128), (170, 96)])
+def test_qkv_product_writing_attention_operands_matches_two_step_path(n_states, S):
+    """Uniform batches at head_dim 128 with enough rows for the 128 x 256 tile: the q | k | v product writes the
+    attention kernel's operands itself (rotated q and k fragments, transposed v) instead of fp32 rows.  The same
+    states through calls too small for that path (one state per call), and through the back-to-back layout,
+    take the two-step path (fp32 rows, pack kernel): every bit of the pooled output must agree.  170 states of
+    96 tokens end in a tile with two of its four 32-row blocks and put state boundaries inside tiles."""
+    from paper_2604_24273_amd import runtime as R
+    shape = synth.tiny_shape(n_layers=2, d=256, n_heads=4, n_kv_heads=2, head_dim=128, f=512, vocab=300,
+                             rope_theta=500000.0)
+    host = []
+    enc = R.EncoderHandle(shape, seed=5, layer_sink=lambda l, w: host.append(w))
+    ids = synth.token_ids(5, 500, (n_states, S), shape.vocab)
+    print("fused q|k|v epilogue: %d states x %d tokens" % (n_states, S), flush=True)
+    h = enc.forward(R.dev(ids))
+    assert torch.equal(h, enc.forward(R.dev(ids)))
+    for b in (0, 1, n_states // 2, n_states - 1):
+        one = enc.forward(R.dev(ids[b:b + 1]))
+        assert torch.equal(h[b:b + 1], one), b
+    cu = (np.arange(n_states + 1) * S).astype(np.int32)
+    hp = enc.forward_packed(R.dev(ids.reshape(-1).astype(np.int32)), cu, max_len=S)
+    assert torch.equal(h, hp)
+    cfg = O.EncoderConfig(shape.n_layers, shape.d, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.f,
+                          shape.vocab, shape.rope_theta)
+    sample = [0, n_states - 1]
+    h_ref = O.encoder_forward(ids[sample], synth.embedding_bf16(5, shape), _oracle_layers(host),
+                              synth.final_norm_gain(5, shape), cfg)
+    for j, b in enumerate(sample):
+        c = _cos(h.cpu().numpy()[b], h_ref[j])
+        print("state %d: cosine %.7f" % (b, c), flush=True)
+        assert c >= 0.999
