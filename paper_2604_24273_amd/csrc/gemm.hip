@@ -392,7 +392,6 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
 // lo = fp16(t - hi)) on the same fp32 values the plain epilogue would have written, so the fragments hold the
 // same bits.  v needs no turn: its transposed fragment order is the accumulator's own lane order.
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
 // fp32 -> fp16 of a value the compiler must first round to fp32: without the barrier it folds the last multiply
 // into the conversion (v_fma_mixlo_f16, one rounding instead of two), and the hi part used for the lo part then
@@ -449,24 +448,31 @@ __device__ inline void epilogue_attn(const GemmArgs& g, v16i (&acc)[TM][TN], int
         }
     }
 
-    // q and k: four half blocks of 16 token rows; every wavefront of the workgroup takes part in the barriers
-    constexpr int LPR = TN * 8, RPP = 64 / LPR, NP = 16 / RPP;
-    const int c4 = lane % LPR, r0 = lane / LPR;
+    // q and k: four half blocks of 16 token rows; every wavefront of the workgroup takes part in the barriers.
+    // A lane takes eight consecutive components of one row: one whole 16-byte entry of a fragment per plane.
+    constexpr int LPR = TN * 4, RPP = 64 / LPR, NP = 16 / RPP;   // 8 lanes per row, 8 rows per pass, 2 passes
+    const int c8 = lane % LPR, r0 = lane / LPR;
     const bool rot = seg != 2 && cols_live;
     const float scale = seg == 0 ? g.att_qscale : 1.0f;
+    const int comp = half * 64 + 8 * c8;                          // first of the lane's eight components of the head
+    const int ks = comp >> 4, kg = (comp >> 3) & 1;
 #pragma unroll
     for (int idx = 0; idx < 2 * TM; ++idx) {
         const int mb = mb0 + (idx >> 1), hb = idx & 1;
         const int mbc = min(mb, g.nmb - 1);
         const int b = (mbc * 32) / g.att_S, rb = ((mbc * 32) % g.att_S) >> 5;
         // the rotary factors of this half block's rows are requested before the turn and the barrier
-        float4 cs[NP], sn[NP];
+        float4 cs[NP][2], sn[NP][2];
         if (rot) {
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
                 const int pos = rb * 32 + hb * 16 + p * RPP + r0;        // position inside the state
-                cs[p] = *reinterpret_cast<const float4*>(g.att_cos + (size_t)pos * 64 + 4 * c4);
-                sn[p] = *reinterpret_cast<const float4*>(g.att_sin + (size_t)pos * 64 + 4 * c4);
+                const float* cp = g.att_cos + (size_t)pos * 64 + 8 * c8;
+                const float* sp = g.att_sin + (size_t)pos * 64 + 8 * c8;
+                cs[p][0] = *reinterpret_cast<const float4*>(cp);
+                cs[p][1] = *reinterpret_cast<const float4*>(cp + 4);
+                sn[p][0] = *reinterpret_cast<const float4*>(sp);
+                sn[p][1] = *reinterpret_cast<const float4*>(sp + 4);
             }
             scatter_half<TM, TN>(acc, idx >> 1, hb, lane, scr);
         }
@@ -481,13 +487,17 @@ __device__ inline void epilogue_attn(const GemmArgs& g, v16i (&acc)[TM][TN], int
                 const int2 rw = rows[idx * 16 + row];
                 const float d = __int_as_float(rw.x);
                 const int sq = rw.y;
-                const int4 a = *reinterpret_cast<const int4*>(&scr[row * LD + 4 * c4]);
-                const int4 pa = *reinterpret_cast<const int4*>(&scr_partner[row * LD + 4 * c4]);
-                const int ai[4] = {a.x, a.y, a.z, a.w}, pi[4] = {pa.x, pa.y, pa.z, pa.w};
-                const float cf[4] = {cs[p].x, cs[p].y, cs[p].z, cs[p].w}, sf[4] = {sn[p].x, sn[p].y, sn[p].z, sn[p].w};
-                half4 hi, lo;
+                const int4 a0 = *reinterpret_cast<const int4*>(&scr[row * LD + 8 * c8]);
+                const int4 a1 = *reinterpret_cast<const int4*>(&scr[row * LD + 8 * c8 + 4]);
+                const int4 p0 = *reinterpret_cast<const int4*>(&scr_partner[row * LD + 8 * c8]);
+                const int4 p1 = *reinterpret_cast<const int4*>(&scr_partner[row * LD + 8 * c8 + 4]);
+                const int ai[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                const int pi[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                const float cf[8] = {cs[p][0].x, cs[p][0].y, cs[p][0].z, cs[p][0].w, cs[p][1].x, cs[p][1].y, cs[p][1].z, cs[p][1].w};
+                const float sf[8] = {sn[p][0].x, sn[p][0].y, sn[p][0].z, sn[p][0].w, sn[p][1].x, sn[p][1].y, sn[p][1].z, sn[p][1].w};
+                half8 hi, lo;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < 8; ++q) {
                     const float xs = ((float)(ai[q] - sq) * d) * bsel;
                     const float xp = ((float)(pi[q] - sq) * d) * bsel;
                     const float t = (half == 0 ? (xs * cf[q] - xp * sf[q]) : (xs * cf[q] + xp * sf[q])) * scale;
@@ -495,11 +505,9 @@ __device__ inline void epilogue_attn(const GemmArgs& g, v16i (&acc)[TM][TN], int
                     hi[q] = th;
                     lo[q] = (_Float16)(t - (float)th);
                 }
-                const int comp = half * 64 + 4 * c4;             // first of the lane's four components of the head
-                const int ks = comp >> 4, kg = (comp >> 3) & 1, e0 = comp & 7;
-                char* slot = reinterpret_cast<char*>(dst + (ks * 2 + 0) * 64 + kg * 32 + hb * 16 + row) + e0 * 2;
-                *reinterpret_cast<half4*>(slot) = hi;
-                *reinterpret_cast<half4*>(slot + 1024) = lo;     // the lo plane is the next 1 KB fragment
+                uint4* slot = dst + (ks * 2 + 0) * 64 + kg * 32 + hb * 16 + row;
+                slot[0] = __builtin_bit_cast(uint4, hi);
+                slot[64] = __builtin_bit_cast(uint4, lo);        // the lo plane is the next 1 KB fragment
             }
         }
         __syncthreads();
