@@ -40,8 +40,9 @@ GEMM_CLASSES = ("gemm", "gemm_narrow", "gemm_qkv_attn")
 # summary it was copied from and the kernel it refers to, and is reset to None whenever that kernel changes
 # until the counters have been taken again.
 ROOFLINE_TRAFFIC = {
-    # FETCH_SIZE 75 400.6 KiB x 2.0 + WRITE_SIZE 172 032 KiB x 1.0, averaged over the QKV and gate|up launches
-    "encoder-2b": {"bytes": 330.6e6, "kernel": "gemm_lds_kernel<2,2,2,4>",
+    # FETCH_SIZE 113 006 KiB x 2.0 + WRITE_SIZE 221 184 KiB x 1.0 per gate|up launch (the only product of the 2B
+    # step that runs this kernel since the q | k | v product has its own); algorithmic: 21 + 8.8 MB in, 226.5 MB out
+    "encoder-2b": {"bytes": 457.9e6, "kernel": "gemm_lds_kernel<2,2,2,4>",
                    "source": "profiles/bench_encoder_2b_hbm_traffic_counters.txt"},
     "prefill-3b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
     "rl-states-2b": {"bytes": None, "kernel": "gemm_lds_kernel<2,2,2,4>", "source": None},
