@@ -385,12 +385,15 @@ __device__ inline void epilogue(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0,
     }
 }
 
-// Attention operands straight from the q | k | v product (head_dim 128, 32 | S, uniform layout).  A wavefront's
-// 64 columns are one half of a head; the rotary partner of a column sits 64 columns away, in the wavefront next
-// to it (wave ^ 1), so both turn their half blocks through LDS and read each other's.  The arithmetic per
-// element is the one the separate pack kernel applies to the fp32 rows ((x c -+ x' s) * scale, then hi = fp16,
-// lo = fp16(t - hi)) on the same fp32 values the plain epilogue would have written, so the fragments hold the
-// same bits.  v needs no turn: its transposed fragment order is the accumulator's own lane order.
+// Attention operands straight from the q | k | v product (head_dim 128, 32 | S, uniform layout).  A wavefront
+// holds two 32-column blocks of one head: columns c .. c + 31 of its first half and the 32 columns 64 further
+// on, the rotary partners of the first (the tile loop hands it the weight pieces in that order).  Both blocks
+// of a half block of 16 rows are turned through the wavefront's own LDS region; a lane then has eight
+// components of a row and their eight partners, rotates both, scales q, splits into fp16 hi / lo and stores
+// four whole 16-byte fragment entries.  No other wavefront is involved.  The arithmetic per element is the one
+// the separate pack kernel applies to the fp32 rows ((x c -+ x' s) * scale, then hi = fp16, lo = fp16(t - hi))
+// on the same fp32 values the plain epilogue would have written, so the fragments hold the same bits.  v needs
+// no turn: its transposed fragment order is the accumulator's own lane order.
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 // fp32 -> fp16 of a value the compiler must first round to fp32: without the barrier it folds the last multiply
@@ -403,23 +406,24 @@ __device__ inline _Float16 half_of_rounded(float x) {
 
 template <int TM, int TN>
 __device__ inline void epilogue_attn(const GemmArgs& g, v16i (&acc)[TM][TN], int mb0, int nb0, const float (&beta)[TN],
-                                     int lane, int* scr, const int* scr_partner) {
-    static_assert(TN == 2, "a wavefront holds one half of a 128-wide head");
+                                     int lane, int* scr) {
+    static_assert(TN == 2, "a block of a head's first half and the block of its rotary partners");
     constexpr int LD = Epi<TM, TN>::LD;
     constexpr int KS = 8, DB = 4, KVFR = KS * 2 + DB * 4;       // 1 KB fragments per key block at head_dim 128
     int seg, col0, ncols;
     block_columns(g, min(nb0, g.nnb - 1), seg, col0, ncols);
     const bool cols_live = nb0 < g.nnb;
     const int head_all = col0 >> 7;                             // head over q | k | v
-    const int half = (col0 >> 6) & 1;
-    const float bsel = beta[0];                                 // both column blocks lie in one head, i.e. one matrix
+    const int sub = (col0 >> 5) & 1;                            // which 32 columns of the head's first half
+    const float bsel = beta[0];                                 // both blocks lie in one head, i.e. one matrix
     const int2* rows = park_rows<TM, TN>(g, mb0, lane, scr);
+    __builtin_amdgcn_wave_barrier();
 
-    if (seg == 2 && cols_live) {
+    if (seg == 2) {
+        if (!cols_live) return;
         // v: lane (column dl of block j, h) holds the keys 16 tt + 8 (e >> 2) + 4 h + (e & 3) of step tt
         const int kvh = head_all - g.att_Hq - g.att_Hkv;
         const int dl = lane & 31, h = lane >> 5;
-        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int mb = mb0 + i;
@@ -428,7 +432,7 @@ __device__ inline void epilogue_attn(const GemmArgs& g, v16i (&acc)[TM][TN], int
             uint4* dst = g.att_kvf + ((size_t)(b * g.att_Hkv + kvh) * g.att_nrb + rb) * (KVFR * 64);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int r = half * 2 + j;
+                const int r = sub + 2 * j;                      // 32-column block of the head
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {
                     half8 hi, lo;
@@ -446,71 +450,57 @@ __device__ inline void epilogue_attn(const GemmArgs& g, v16i (&acc)[TM][TN], int
                 }
             }
         }
+        return;
     }
+    if (!cols_live) return;
 
-    // q and k: four half blocks of 16 token rows; every wavefront of the workgroup takes part in the barriers.
-    // A lane takes eight consecutive components of one row: one whole 16-byte entry of a fragment per plane.
-    constexpr int LPR = TN * 4, RPP = 64 / LPR, NP = 16 / RPP;   // 8 lanes per row, 8 rows per pass, 2 passes
-    const int c8 = lane % LPR, r0 = lane / LPR;
-    const bool rot = seg != 2 && cols_live;
+    // q and k: four lanes per row, eight components and their eight partners per lane; one pass per half block
+    const int c8 = lane & 3, row = lane >> 2;                     // row of the half block
     const float scale = seg == 0 ? g.att_qscale : 1.0f;
-    const int comp = half * 64 + 8 * c8;                          // first of the lane's eight components of the head
-    const int ks = comp >> 4, kg = (comp >> 3) & 1;
+    const int comp = sub * 32 + 8 * c8;                           // first of the lane's components of the first half
+    const int ks = comp >> 4, kg = (comp >> 3) & 1;               // the partners are four k-steps on
 #pragma unroll
     for (int idx = 0; idx < 2 * TM; ++idx) {
         const int mb = mb0 + (idx >> 1), hb = idx & 1;
-        const int mbc = min(mb, g.nmb - 1);
-        const int b = (mbc * 32) / g.att_S, rb = ((mbc * 32) % g.att_S) >> 5;
-        // the rotary factors of this half block's rows are requested before the turn and the barrier
-        float4 cs[NP][2], sn[NP][2];
-        if (rot) {
+        if (mb >= g.nmb) break;
+        const int b = (mb * 32) / g.att_S, rb = ((mb * 32) % g.att_S) >> 5;
+        // the rotary factors of the lane's row are requested before the turn
+        const int pos = rb * 32 + hb * 16 + row;                  // position inside the state
+        const float* cp = g.att_cos + (size_t)pos * 64 + comp;
+        const float* sp = g.att_sin + (size_t)pos * 64 + comp;
+        const float4 c0 = *reinterpret_cast<const float4*>(cp), c1 = *reinterpret_cast<const float4*>(cp + 4);
+        const float4 s0 = *reinterpret_cast<const float4*>(sp), s1 = *reinterpret_cast<const float4*>(sp + 4);
+        scatter_half<TM, TN>(acc, idx >> 1, hb, lane, scr);
+        const int2 rw = rows[idx * 16 + row];
+        const float d = __int_as_float(rw.x);
+        const int sq = rw.y;
+        const int4 a0 = *reinterpret_cast<const int4*>(&scr[row * LD + 8 * c8]);
+        const int4 a1 = *reinterpret_cast<const int4*>(&scr[row * LD + 8 * c8 + 4]);
+        const int4 p0 = *reinterpret_cast<const int4*>(&scr[row * LD + 32 + 8 * c8]);
+        const int4 p1 = *reinterpret_cast<const int4*>(&scr[row * LD + 32 + 8 * c8 + 4]);
+        const int ai[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        const int pi[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        const float cf[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        const float sf[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        half8 hi1, lo1, hi2, lo2;
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                const int pos = rb * 32 + hb * 16 + p * RPP + r0;        // position inside the state
-                const float* cp = g.att_cos + (size_t)pos * 64 + 8 * c8;
-                const float* sp = g.att_sin + (size_t)pos * 64 + 8 * c8;
-                cs[p][0] = *reinterpret_cast<const float4*>(cp);
-                cs[p][1] = *reinterpret_cast<const float4*>(cp + 4);
-                sn[p][0] = *reinterpret_cast<const float4*>(sp);
-                sn[p][1] = *reinterpret_cast<const float4*>(sp + 4);
-            }
-            scatter_half<TM, TN>(acc, idx >> 1, hb, lane, scr);
+        for (int q = 0; q < 8; ++q) {
+            const float x1 = ((float)(ai[q] - sq) * d) * bsel;    // component of the first half
+            const float x2 = ((float)(pi[q] - sq) * d) * bsel;    // its partner, 64 components on
+            const float t1 = (x1 * cf[q] - x2 * sf[q]) * scale;
+            const float t2 = (x2 * cf[q] + x1 * sf[q]) * scale;
+            const _Float16 h1 = half_of_rounded(t1), h2 = half_of_rounded(t2);
+            hi1[q] = h1; lo1[q] = (_Float16)(t1 - (float)h1);
+            hi2[q] = h2; lo2[q] = (_Float16)(t2 - (float)h2);
         }
-        __syncthreads();
-        if (rot && mb < g.nmb) {
-            uint4* dst = seg == 0
-                ? g.att_qf + ((size_t)(b * g.att_Hq + head_all) * g.att_nrb + rb) * (KS * 2 * 64)
-                : g.att_kvf + ((size_t)(b * g.att_Hkv + (head_all - g.att_Hq)) * g.att_nrb + rb) * (KVFR * 64);
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                const int row = p * RPP + r0;                    // row of the half block
-                const int2 rw = rows[idx * 16 + row];
-                const float d = __int_as_float(rw.x);
-                const int sq = rw.y;
-                const int4 a0 = *reinterpret_cast<const int4*>(&scr[row * LD + 8 * c8]);
-                const int4 a1 = *reinterpret_cast<const int4*>(&scr[row * LD + 8 * c8 + 4]);
-                const int4 p0 = *reinterpret_cast<const int4*>(&scr_partner[row * LD + 8 * c8]);
-                const int4 p1 = *reinterpret_cast<const int4*>(&scr_partner[row * LD + 8 * c8 + 4]);
-                const int ai[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-                const int pi[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-                const float cf[8] = {cs[p][0].x, cs[p][0].y, cs[p][0].z, cs[p][0].w, cs[p][1].x, cs[p][1].y, cs[p][1].z, cs[p][1].w};
-                const float sf[8] = {sn[p][0].x, sn[p][0].y, sn[p][0].z, sn[p][0].w, sn[p][1].x, sn[p][1].y, sn[p][1].z, sn[p][1].w};
-                half8 hi, lo;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const float xs = ((float)(ai[q] - sq) * d) * bsel;
-                    const float xp = ((float)(pi[q] - sq) * d) * bsel;
-                    const float t = (half == 0 ? (xs * cf[q] - xp * sf[q]) : (xs * cf[q] + xp * sf[q])) * scale;
-                    const _Float16 th = half_of_rounded(t);
-                    hi[q] = th;
-                    lo[q] = (_Float16)(t - (float)th);
-                }
-                uint4* slot = dst + (ks * 2 + 0) * 64 + kg * 32 + hb * 16 + row;
-                slot[0] = __builtin_bit_cast(uint4, hi);
-                slot[64] = __builtin_bit_cast(uint4, lo);        // the lo plane is the next 1 KB fragment
-            }
-        }
-        __syncthreads();
+        uint4* dst = seg == 0
+            ? g.att_qf + ((size_t)(b * g.att_Hq + head_all) * g.att_nrb + rb) * (KS * 2 * 64)
+            : g.att_kvf + ((size_t)(b * g.att_Hkv + (head_all - g.att_Hq)) * g.att_nrb + rb) * (KVFR * 64);
+        uint4* slot = dst + (ks * 2) * 64 + kg * 32 + hb * 16 + row;
+        slot[0] = __builtin_bit_cast(uint4, hi1);
+        slot[64] = __builtin_bit_cast(uint4, lo1);               // the lo plane is the next 1 KB fragment
+        slot[8 * 64] = __builtin_bit_cast(uint4, hi2);           // four k-steps = eight fragments on
+        slot[9 * 64] = __builtin_bit_cast(uint4, lo2);
     }
 }
 
@@ -617,13 +607,16 @@ struct LdsTile {
 
     // The MFMAs of one stage.  Activation fragments are requested from LDS two uses before the
     // MFMAs that consume them.
-    static __device__ inline void compute(v16i (&acc)[TM][TN], const uint4* st, int wm, int wn, int lane) {
+    // p0: the wavefront's first weight piece of the tile; its TN pieces are p0, p0 + PSTR, ...
+    template <int PSTR = 1>
+    static __device__ inline void compute(v16i (&acc)[TM][TN], const uint4* st, int wm, int p0, int lane) {
+        static_assert(PSTR == 1 || !W8, "strided pieces: 2-bit weights only");
         const uint4* sa = st + (wm * TM * KD) * 64 + lane;
-        const uint4* sbp = st + (AFR + wn * TN * (W8 ? KD : 1)) * 64 + lane;
+        const uint4* sbp = st + (AFR + p0 * (W8 ? KD : 1)) * 64 + lane;
         uint4 bq[W8 ? 1 : TN];
         if constexpr (!W8) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bq[j] = sbp[j * 64];
+            for (int j = 0; j < TN; ++j) bq[j] = sbp[j * PSTR * 64];
         }
         constexpr int NF = KD * TM;
         uint4 fr[NF];
@@ -669,7 +662,11 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     const int mb_tile0 = tile_m * WM * TM;
     const int mb0 = mb_tile0 + wm * TM;
     const int nb_tile0 = tile_n * WN * TN;
-    const int nb0 = nb_tile0 + wn * TN;
+    // weight blocks of the wavefront: TN neighbours, or (attention-operand epilogue) a 32-column block of a head's
+    // first half and the block 64 columns on, which holds the rotary partners of its columns
+    constexpr int PSTR = ATTN ? 2 : 1;
+    const int p0 = ATTN ? (wn >> 1) * 4 + (wn & 1) : wn * TN;
+    const int nb0 = nb_tile0 + p0;
 
     // sources of the stage pieces this wavefront copies (clamped: padding is never stored)
     const uint4* asrc[Tile::APW];
@@ -717,17 +714,17 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
         __syncthreads();
         Tile::issue(asrc, bsrc, sb + 1, stage1, wave);
         __builtin_amdgcn_sched_barrier(0);       // the copy requests stay ahead of the MFMAs that hide them
-        Tile::compute(acc, stage0, wm, wn, lane);
+        Tile::template compute<PSTR>(acc, stage0, wm, p0, lane);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (sb + 2 < sb_last) Tile::issue(asrc, bsrc, sb + 2, stage0, wave);
         __builtin_amdgcn_sched_barrier(0);
-        Tile::compute(acc, stage1, wm, wn, lane);
+        Tile::template compute<PSTR>(acc, stage1, wm, p0, lane);
     }
     if (sb < sb_last) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        Tile::compute(acc, stage0, wm, wn, lane);
+        Tile::template compute<PSTR>(acc, stage0, wm, p0, lane);
     }
 
     // the stages are free once every wavefront has left the k loop: reuse them for the epilogue
@@ -735,10 +732,8 @@ __device__ __forceinline__ void gemm_lds_body(const GemmArgs& g) {
     static_assert((NW / 2) * Epi<TM, TN>::REGION * 4 <= Tile::STAGE * 16, "half of the epilogue regions per stage");
     int* scr = reinterpret_cast<int*>(wave < NW / 2 ? stage0 : stage1) + (wave % (NW / 2)) * Epi<TM, TN>::REGION;
     if constexpr (ATTN) {
-        static_assert(WN % 2 == 0 && (NW / 2) % 2 == 0, "a wavefront and its neighbour wave ^ 1 share a stage buffer");
-        const int* scr_partner =
-            reinterpret_cast<const int*>(wave < NW / 2 ? stage0 : stage1) + ((wave ^ 1) % (NW / 2)) * Epi<TM, TN>::REGION;
-        epilogue_attn<TM, TN>(g, acc, mb0, nb0, beta, lane, scr, scr_partner);
+        static_assert(WN == 4 && TN == 2, "a 256-column tile is two heads of 128: four wavefronts of 32 + 32 columns");
+        epilogue_attn<TM, TN>(g, acc, mb0, nb0, beta, lane, scr);
     } else if (g.splits > 1) {
         epilogue_partial<TM, TN>(g, acc, mb0, nb0, split, lane, scr);
     } else {
