@@ -198,3 +198,41 @@ def test_qkv_product_writing_attention_operands_matches_two_step_path(n_states, 
         c = _cos(h.cpu().numpy()[b], h_ref[j])
         print("state %d: cosine %.7f" % (b, c), flush=True)
         assert c >= 0.999
+
+
+@pytest.mark.timeout(600)
+def test_fused_qkv_path_replays_from_a_hip_graph():
+    """The path above captured into a HIP graph (after one ordinary call of the same shapes): every replay, with
+    other eager work and synchronisations between the replays, reproduces the eager result bit for bit."""
+    from paper_2604_24273_amd import binding as B
+    from paper_2604_24273_amd import runtime as R
+    shape = synth.tiny_shape(n_layers=2, d=256, n_heads=4, n_kv_heads=2, head_dim=128, f=512, vocab=300,
+                             rope_theta=500000.0)
+    enc = R.EncoderHandle(shape, seed=6)
+    ids = R.dev(synth.token_ids(6, 500, (128, 128), shape.vocab))
+    other = R.dev(synth.token_ids(6, 501, (128, 128), shape.vocab))
+    ws = R.Workspace(B.brl_encoder_workspace_bytes(enc.struct, 128, 128))
+    h = torch.empty((128, shape.d), dtype=torch.float32, device="cuda")
+
+    def call(x):
+        B.encoder_forward(enc.struct, x, 128, 128, None, h, ws.buf)
+
+    call(ids)
+    torch.cuda.synchronize()
+    want = h.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(ids)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(ids)
+    for k in range(4):
+        call(other)                      # eager work on the same workspace and output in between
+        torch.cuda.synchronize()
+        assert not torch.equal(h, want)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(h, want), "replay %d differs from the eager result" % k
