@@ -482,27 +482,27 @@ int launch_one(const QK& a, hipStream_t s) {
     constexpr int AQ_THREADS = NWV * 64;
     const int ngroups = (a.M + GR - 1) / GR;
     const size_t lds = (size_t)GR * (a.Kp + 16) + (a.gain ? (size_t)a.Kp * 4 : 0);
-    static int slots = 0;            // workgroups the device holds at once
-    static bool raised = false;      // more than the default 64 KB of dynamic LDS allowed
     constexpr size_t max_lds = (size_t)GR * (HV4 * WPT * 256 + 16) + (size_t)HV4 * WPT * 256 * 4;
     static_assert(max_lds <= 160 * 1024, "the rows of a group and the gain fit the LDS of a compute unit");
-    if (!raised && max_lds > 65536) {
-        BRL_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<HV4, WPT, GR, NWV>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds));
-        raised = true;
-    }
-    if (slots == 0) {
+    static const int slots = [] {    // workgroups the device holds at once; initialised once, thread-safe
         int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
+        hipError_t e = hipSuccess;
+        if (max_lds > 65536)         // more than the default 64 KB of dynamic LDS
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&act_quant_kernel<HV4, WPT, GR, NWV>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
+        if (e != hipSuccess || hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, act_quant_kernel<HV4, WPT, GR, NWV>, AQ_THREADS, max_lds) !=
                 hipSuccess ||
             cus <= 0 || per_cu <= 0) {
             (void)hipGetLastError();
-            cus = 256;
-            per_cu = 1;
+            return -1;
         }
-        slots = cus * per_cu;
+        return cus * per_cu;
+    }();
+    if (slots <= 0) {
+        set_error("act_quant: the device cannot hold a workgroup with %zu bytes of LDS", max_lds);
+        return BRL_EHIP;
     }
     const int grid = ngroups < slots ? ngroups : slots;
     hipLaunchKernelGGL((act_quant_kernel<HV4, WPT, GR, NWV>), dim3(grid), dim3(AQ_THREADS), lds, s, a);
